@@ -1,0 +1,168 @@
+/*
+ * wave.h -- C ABI of the wave-index library for AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of the wave index of
+ * "RetroInfer: A Vector Storage Engine for Scalable Long-Context LLM
+ * Inference": the segmented spherical k-means that builds the cluster index
+ * over a key/value cache (section "Wave Index", paragraphs "Index
+ * Organization" and "Lightweight Index Construction and Updates") and the
+ * decode step that replaces full attention by tripartite attention (paragraph
+ * "Tripartite Attention Approximation", the estimation equations, and the
+ * decode steps 1-4 of the system overview).
+ *
+ * Conventions
+ *  - Every pointer marked DEVICE is caller-owned GPU memory; HOST pointers are
+ *    ordinary host memory.  The library allocates no device memory and keeps
+ *    no state between calls (the optional profiler below excepted).
+ *  - Every call returns a wave_status; nothing aborts or throws.  Argument
+ *    errors are found on the host before any kernel is launched.
+ *  - wave_index_build and wave_attention_decode only ENQUEUE work on the given
+ *    HIP stream (a hipStream_t passed as void*; NULL is the default stream).
+ *    Results are valid once the caller has synchronised that stream.  Two
+ *    calls that share a workspace must be ordered on one stream.
+ *  - Tensors are dense, row-major, last index fastest.  dtype is the storage
+ *    type of q, K, V and of the index's floating arrays.  Accumulation is
+ *    fp32 in decode and fp64/fp32-MFMA in the build (see each call).
+ *  - Notation follows the paper: d head dimension, N context tokens, p steady
+ *    tokens (n_sink + n_local), m clusters per (sequence, KV head), r retrieved
+ *    clusters, C centroids, s sizes, VS value sums, L segment length, k
+ *    clusters per segment, T k-means iterations, G = Hq / Hkv.
+ *  - Supported shapes: d in {64, 128}; 1 <= G <= 8; dtype f32 or bf16;
+ *    clusters_per_segment <= 4096; N < 2^31.
+ */
+#ifndef WAVE_H
+#define WAVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WAVE_OK = 0,
+  WAVE_ERR_ARG = 1,             /* null pointer, negative count, iters < 1, ...        */
+  WAVE_ERR_SHAPE = 2,           /* unsupported d, G, k, or inconsistent dimensions     */
+  WAVE_ERR_DTYPE = 3,           /* dtype not WAVE_F32 / WAVE_BF16                      */
+  WAVE_ERR_WORKSPACE = 4,       /* workspace null, misaligned (256 B) or too small     */
+  WAVE_ERR_STEADY_MISMATCH = 5, /* decode's n_sink/n_local differ from the index's     */
+  WAVE_ERR_HIP = 6              /* a HIP runtime call or kernel launch failed          */
+} wave_status;
+
+typedef enum { WAVE_F32 = 0, WAVE_BF16 = 1 } wave_dtype;
+
+/* Index of B x Hkv independent (sequence, KV head) units: the meta index
+ * (centroid, value sum, size per cluster: "Index Organization" and the value-sum
+ * equation) and the cluster-contiguous key/value rows.  Plain data; the caller
+ * fills the dimension fields, calls wave_index_plan for S, m, N_idx and the
+ * buffer sizes, allocates the nine buffers on the DEVICE and stores the
+ * pointers.  Copying the arrays copies the index. */
+typedef struct {
+  int32_t dtype;                /* wave_dtype                                          */
+  int32_t B, Hkv, d, N;
+  int32_t n_sink, n_local;      /* steady zone: first n_sink and last n_local tokens,  */
+                                /* attended by position and excluded from clustering   */
+  int32_t segment_len;          /* L                                                   */
+  int32_t clusters_per_segment; /* k; a ragged last segment of L_s tokens has          */
+                                /* min(k, L_s) clusters                                */
+  int32_t S, m, N_idx;          /* derived: segments, clusters and indexed tokens per  */
+                                /* unit; N_idx = N - (steady tokens)                   */
+  int32_t p;                    /* derived: steady tokens = min(N, n_sink) + local part */
+  int32_t reserved_;
+  void *centroids;              /* DEVICE [B,Hkv,m,d] dtype: mean of raw member keys   */
+  void *vsum;                   /* DEVICE [B,Hkv,m,d] dtype: sum of member values      */
+  int32_t *sizes;               /* DEVICE [B,Hkv,m]     0 = empty cluster              */
+  int32_t *offsets;             /* DEVICE [B,Hkv,m+1]   rows of cluster c in k_perm /  */
+                                /*        v_perm are [offsets[c], offsets[c+1])        */
+  int32_t *perm;                /* DEVICE [B,Hkv,N_idx] original position of each row  */
+  void *k_perm, *v_perm;        /* DEVICE [B,Hkv,N_idx,d] dtype, rows ordered by       */
+                                /*        (segment, cluster, original position)        */
+  void *k_steady, *v_steady;    /* DEVICE [B,Hkv,p,d] dtype: sink rows then local rows */
+} wave_index;
+
+enum { WAVE_INDEX_BUFFERS = 9 };
+
+/* Host only.  Reads the dimension fields of *ix, writes S, m, N_idx, p into it
+ * and the byte size of each of the nine buffers into bytes[] in the order
+ * centroids, vsum, sizes, offsets, perm, k_perm, v_perm, k_steady, v_steady.
+ * build_workspace_bytes (may be NULL) receives the scratch wave_index_build
+ * needs; decode_workspace_bytes (may be NULL) the scratch wave_attention_decode
+ * needs for Hq query heads and topk_clusters retrieved clusters.  Sizes of
+ * zero-length buffers are reported as 0; their pointers may be NULL. */
+wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
+                            size_t *build_workspace_bytes, int Hq, int topk_clusters,
+                            size_t *decode_workspace_bytes);
+
+/* Index construction ("Index Organization", "Lightweight Index Construction"):
+ * per unit and per segment of L tokens, spherical k-means on the centred,
+ * unit-normalised keys (seeded distinct-point initialisation, `iters` rounds of
+ * assign + update, ties to the lowest cluster id, empty clusters keep their
+ * centroid; the partition is the one of the last assign); then per cluster its
+ * size, the mean of its raw keys, the sum of its values, and the key/value rows
+ * permuted so that clusters are contiguous.  Similarities are bf16 MFMA
+ * products accumulated in fp32 (fp32 FMA for f32 data); any point whose two
+ * best similarities are closer than the accumulation error bound is re-decided
+ * in fp64; centring, normalisation, centroid updates, means and value sums
+ * accumulate in fp64 and are rounded once (to nearest even) to dtype.
+ *   K, V       DEVICE [B,Hkv,N,d] dtype, read only, may be released after the
+ *              stream work completes
+ *   ix         dimensions + planned fields + the nine DEVICE buffers (written)
+ *   workspace  DEVICE, 256-byte aligned, >= build_workspace_bytes */
+wave_status wave_index_build(const void *K, const void *V, wave_index *ix, int iters,
+                             uint64_t seed, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/* One decode step of tripartite attention for B x Hq query heads (query head
+ * hq uses the index of KV head hq / G and ranks clusters on its own):
+ * score every non-empty centroid against q, take the topk_clusters best
+ * (ties to the lower id), attend exactly over the steady tokens and over every
+ * token of the selected clusters, let each other cluster contribute
+ * s_i * exp(q.C_i / sqrt(d)) to the normaliser and exp(q.C_i / sqrt(d)) * VS_i
+ * to the numerator (estimation equations), and merge the zones under one
+ * softmax normalisation by log-sum-exp.
+ *   q          DEVICE [B,Hq,d] dtype
+ *   out        DEVICE [B,Hq,d] fp32; lse DEVICE [B,Hq] fp32 = log sum of
+ *              exp(scaled logits) over the three zones (natural log)
+ *   selected   DEVICE [B,Hq,topk_clusters] int32 or NULL: selected cluster ids
+ *              ascending, padded with -1
+ *   n_sink, n_local  must equal the index's, else WAVE_ERR_STEADY_MISMATCH
+ *   topk_clusters >= number of non-empty clusters retrieves everything (the
+ *   result is then exact attention); 0 leaves steady + estimation only.
+ * Scores accumulate in fp32; a cluster whose fp32 score lies within the
+ * accumulation error bound of the selection threshold is re-scored in fp64, so
+ * the selected set is the fp64 ranking's. */
+wave_status wave_attention_decode(const void *q, const wave_index *ix, int Hq, int topk_clusters,
+                                  int n_sink, int n_local, float *out, float *lse,
+                                  int32_t *selected, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/* Test hook, host only: the k_s distinct seed-token indices (relative to the
+ * segment start) with which segment s of unit (b, h) starts k-means: the first
+ * k_s entries of a Fisher-Yates shuffle of 0..L_s-1 driven by splitmix64 keyed
+ * on (seed, b, h, s).  out: HOST [k_s]. */
+wave_status wave_init_indices(uint64_t seed, int b, int h, int s, int L_s, int k_s, int32_t *out);
+
+/* Test hook: one assign step of the build on one segment, with the build's
+ * own kernels.  xhat DEVICE [L_s,d] dtype (normalised keys), chat DEVICE
+ * [k_s,d] dtype (centroids), assign DEVICE [L_s] int32 (written).
+ * workspace DEVICE >= 4*L_s + 1024 bytes, 256-byte aligned. */
+wave_status wave_kmeans_assign_step(const void *xhat, const void *chat, int dtype, int L_s, int k_s,
+                                    int d, int32_t *assign, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+
+/* Profiler (the library's only global state).  While enabled, every kernel the
+ * library launches is bracketed by HIP events on its stream.
+ * wave_profile_read synchronises, adds up the elapsed time per kernel name
+ * since the last read and writes up to `cap` entries: names[i] points to a
+ * static string, total_ms[i] and launches[i] to the sums.  Returns the number
+ * of distinct kernels, or -1 on a HIP error. */
+wave_status wave_profile_enable(int on);
+int wave_profile_read(const char **names, float *total_ms, int *launches, int cap);
+
+const char *wave_status_string(wave_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WAVE_H */

@@ -1,0 +1,271 @@
+"""ctypes binding of libwave.so (include/wave.h): argument marshalling only.
+
+Every function here has the name of the C entry point it calls.  torch
+supplies device memory and the current HIP stream; no arithmetic of the method
+happens in Python.  There is no CPU fallback: if the library has not been
+built, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwave.so")
+
+WAVE_F32, WAVE_BF16 = 0, 1
+WAVE_INDEX_BUFFERS = 9
+BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_perm", "k_steady",
+                "v_steady")
+STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
+                4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
+EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode", "wave_init_indices",
+           "wave_kmeans_assign_step", "wave_profile_enable", "wave_profile_read",
+           "wave_status_string")
+
+
+class wave_index(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("N", ctypes.c_int32), ("n_sink", ctypes.c_int32),
+                ("n_local", ctypes.c_int32), ("segment_len", ctypes.c_int32),
+                ("clusters_per_segment", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("m", ctypes.c_int32), ("N_idx", ctypes.c_int32), ("p", ctypes.c_int32),
+                ("reserved_", ctypes.c_int32),
+                ("centroids", ctypes.c_void_p), ("vsum", ctypes.c_void_p),
+                ("sizes", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
+                ("perm", ctypes.c_void_p), ("k_perm", ctypes.c_void_p),
+                ("v_perm", ctypes.c_void_p), ("k_steady", ctypes.c_void_p),
+                ("v_steady", ctypes.c_void_p)]
+
+
+class WaveError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().wave_status_string(status).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({msg})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2505_02922_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, u64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_size_t
+        L.wave_index_plan.argtypes = [ctypes.POINTER(wave_index), ctypes.POINTER(sz),
+                                      ctypes.POINTER(sz), i32, i32, ctypes.POINTER(sz)]
+        L.wave_index_build.argtypes = [vp, vp, ctypes.POINTER(wave_index), i32, u64, vp, sz, vp]
+        L.wave_attention_decode.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32, vp,
+                                            vp, vp, vp, sz, vp]
+        L.wave_init_indices.argtypes = [u64, i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
+        L.wave_kmeans_assign_step.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.wave_profile_enable.argtypes = [i32]
+        L.wave_profile_read.argtypes = [ctypes.POINTER(ctypes.c_char_p),
+                                        ctypes.POINTER(ctypes.c_float),
+                                        ctypes.POINTER(ctypes.c_int), i32]
+        L.wave_status_string.argtypes = [i32]
+        L.wave_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return WAVE_F32
+    if dt == torch.bfloat16:
+        return WAVE_BF16
+    raise WaveError(3, "dtype")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None or t.numel() == 0:
+        return None
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Index:
+    """A wave_index struct plus the torch tensors that own its buffers."""
+
+    def __init__(self, c: wave_index, tensors: Dict[str, torch.Tensor], dtype: torch.dtype,
+                 build_ws_bytes: int):
+        self.c = c
+        self.t = tensors
+        self.dtype = dtype
+        self.build_ws_bytes = build_ws_bytes
+
+    def __getattr__(self, name):
+        if name in ("B", "Hkv", "d", "N", "n_sink", "n_local", "segment_len",
+                    "clusters_per_segment", "S", "m", "N_idx", "p"):
+            return getattr(self.c, name)
+        if name in BUFFER_NAMES:
+            return self.t[name]
+        raise AttributeError(name)
+
+
+def _shapes(c: wave_index) -> Dict[str, Tuple[int, ...]]:
+    u = (c.B, c.Hkv)
+    return {"centroids": u + (c.m, c.d), "vsum": u + (c.m, c.d), "sizes": u + (c.m,),
+            "offsets": u + (c.m + 1,), "perm": u + (c.N_idx,), "k_perm": u + (c.N_idx, c.d),
+            "v_perm": u + (c.N_idx, c.d), "k_steady": u + (c.p, c.d), "v_steady": u + (c.p, c.d)}
+
+
+def wave_index_plan(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
+                    segment_len: int, clusters_per_segment: int, Hq: Optional[int] = None,
+                    topk_clusters: int = 0) -> Tuple[wave_index, List[int], int, Optional[int]]:
+    """Returns (struct with derived fields, byte sizes of the nine buffers,
+    build workspace bytes, decode workspace bytes or None)."""
+    c = wave_index()
+    c.dtype, c.B, c.Hkv, c.d, c.N = _dtype_code(dtype), B, Hkv, d, N
+    c.n_sink, c.n_local, c.segment_len, c.clusters_per_segment = n_sink, n_local, segment_len, clusters_per_segment
+    sizes = (ctypes.c_size_t * WAVE_INDEX_BUFFERS)()
+    bws, dws = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    st = lib().wave_index_plan(ctypes.byref(c), sizes, ctypes.byref(bws), Hq or 0, topk_clusters,
+                               ctypes.byref(dws) if Hq else None)
+    if st != 0:
+        raise WaveError(st, "wave_index_plan")
+    return c, list(sizes), bws.value, (dws.value if Hq else None)
+
+
+def alloc_index(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
+                segment_len: int, clusters_per_segment: int, device="cuda") -> Index:
+    """Plans and allocates an empty index on the device."""
+    c, sizes, bws, _ = wave_index_plan(dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
+                                       clusters_per_segment)
+    tensors = {}
+    for name, nbytes in zip(BUFFER_NAMES, sizes):
+        dt = torch.int32 if name in ("sizes", "offsets", "perm") else dtype
+        t = torch.empty(_shapes(c)[name], dtype=dt, device=device)
+        assert t.numel() * t.element_size() == nbytes, (name, t.shape, nbytes)
+        tensors[name] = t
+        setattr(c, name, _ptr(t))
+    return Index(c, tensors, dtype, bws)
+
+
+def workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def wave_index_build(K: torch.Tensor, V: torch.Tensor, n_sink: int, n_local: int, segment_len: int,
+                     clusters_per_segment: int, iters: int, seed: int,
+                     ws: Optional[torch.Tensor] = None, index: Optional[Index] = None) -> Index:
+    """K, V: [B, Hkv, N, d] device tensors (f32 or bf16).  Enqueues the build on
+    the current stream and returns the index (valid after a stream sync)."""
+    assert K.is_cuda and V.is_cuda and K.shape == V.shape and K.dtype == V.dtype
+    K, V = K.contiguous(), V.contiguous()
+    B, Hkv, N, d = K.shape
+    ix = index or alloc_index(K.dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
+                              clusters_per_segment, K.device)
+    if ws is None:
+        ws = workspace(ix.build_ws_bytes, K.device)
+    st = lib().wave_index_build(K.data_ptr(), V.data_ptr(), ctypes.byref(ix.c), iters, seed,
+                                ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_index_build")
+    ix._keepalive = (K, V, ws)
+    return ix
+
+
+def decode_workspace_bytes(ix: Index, Hq: int, topk_clusters: int) -> int:
+    c = wave_index()
+    ctypes.memmove(ctypes.byref(c), ctypes.byref(ix.c), ctypes.sizeof(wave_index))
+    sizes = (ctypes.c_size_t * WAVE_INDEX_BUFFERS)()
+    dws = ctypes.c_size_t(0)
+    st = lib().wave_index_plan(ctypes.byref(c), sizes, None, Hq, topk_clusters, ctypes.byref(dws))
+    if st != 0:
+        raise WaveError(st, "wave_index_plan")
+    return dws.value
+
+
+def wave_attention_decode(q: torch.Tensor, ix: Index, topk_clusters: int, n_sink: Optional[int] = None,
+                          n_local: Optional[int] = None, out: Optional[torch.Tensor] = None,
+                          lse: Optional[torch.Tensor] = None, selected: Optional[torch.Tensor] = None,
+                          ws: Optional[torch.Tensor] = None, want_selected: bool = False):
+    """q: [B, Hq, d] device tensor of the index's dtype.  Returns (out [B,Hq,d]
+    f32, lse [B,Hq] f32, selected [B,Hq,topk] i32 or None)."""
+    assert q.is_cuda and q.dtype == ix.dtype
+    q = q.contiguous()
+    B, Hq, d = q.shape
+    n_sink = ix.n_sink if n_sink is None else n_sink
+    n_local = ix.n_local if n_local is None else n_local
+    if out is None:
+        out = torch.empty(B, Hq, d, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    if selected is None and want_selected:
+        selected = torch.empty(B, Hq, max(topk_clusters, 1), dtype=torch.int32, device=q.device)
+    if ws is None:
+        ws = workspace(decode_workspace_bytes(ix, Hq, topk_clusters), q.device)
+    st = lib().wave_attention_decode(q.data_ptr(), ctypes.byref(ix.c), Hq, topk_clusters, n_sink,
+                                     n_local, out.data_ptr(), lse.data_ptr(),
+                                     selected.data_ptr() if selected is not None and topk_clusters > 0 else None,
+                                     ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_attention_decode")
+    return out, lse, selected
+
+
+def wave_init_indices(seed: int, b: int, h: int, s: int, L_s: int, k_s: int) -> List[int]:
+    out = (ctypes.c_int32 * max(k_s, 1))()
+    st = lib().wave_init_indices(seed, b, h, s, L_s, k_s, out)
+    if st != 0:
+        raise WaveError(st, "wave_init_indices")
+    return list(out[:k_s])
+
+
+def wave_kmeans_assign_step(xhat: torch.Tensor, chat: torch.Tensor) -> torch.Tensor:
+    """xhat [L_s, d], chat [k_s, d] device tensors of one dtype -> assign [L_s] i32."""
+    assert xhat.is_cuda and chat.is_cuda and xhat.dtype == chat.dtype
+    xhat, chat = xhat.contiguous(), chat.contiguous()
+    L_s, d = xhat.shape
+    k_s = chat.shape[0]
+    assign = torch.empty(L_s, dtype=torch.int32, device=xhat.device)
+    ws = workspace(4 * L_s + 1024, xhat.device)
+    st = lib().wave_kmeans_assign_step(xhat.data_ptr(), chat.data_ptr(), _dtype_code(xhat.dtype), L_s,
+                                       k_s, d, assign.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_kmeans_assign_step")
+    return assign
+
+
+def wave_profile_enable(on: bool) -> None:
+    st = lib().wave_profile_enable(1 if on else 0)
+    if st != 0:
+        raise WaveError(st, "wave_profile_enable")
+
+
+def wave_profile_read() -> Dict[str, Tuple[float, int]]:
+    """{kernel name: (total ms, launches)} since the last read."""
+    cap = 64
+    names = (ctypes.c_char_p * cap)()
+    ms = (ctypes.c_float * cap)()
+    cnt = (ctypes.c_int * cap)()
+    n = lib().wave_profile_read(names, ms, cnt, cap)
+    if n < 0:
+        raise WaveError(6, "wave_profile_read")
+    return {names[i].decode(): (ms[i], cnt[i]) for i in range(min(n, cap))}
+
+
+def index_from_arrays(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
+                      segment_len: int, clusters_per_segment: int, arrays: Dict[str, torch.Tensor],
+                      device="cuda") -> Index:
+    """Imports an index from host arrays (the index is plain data: importing it
+    is copying its nine arrays)."""
+    ix = alloc_index(dtype, B, Hkv, d, N, n_sink, n_local, segment_len, clusters_per_segment, device)
+    for name in BUFFER_NAMES:
+        if ix.t[name].numel():
+            ix.t[name].copy_(arrays[name].reshape(ix.t[name].shape).to(ix.t[name].dtype))
+    return ix

@@ -1,0 +1,278 @@
+// C-ABI entry points of the wave-index library: planning, argument checks,
+// dispatch to the build and decode launch code, the host-side seed-point hook
+// and the event profiler.
+#include <stdio.h>
+#include <string.h>
+
+#include "wave_common.h"
+
+namespace wave {
+
+// ----------------------------------------------------------------------------
+// Profiler: brackets every launch with HIP events on the launch's own stream.
+// ----------------------------------------------------------------------------
+bool g_profile_on = false;
+
+namespace {
+constexpr int kMaxPending = 8192;
+constexpr int kMaxNames = 64;
+struct Pending {
+  const char* name;
+  hipEvent_t start, stop;
+};
+Pending g_pending[kMaxPending];
+int g_npending = 0;
+int g_pool_ready = 0;
+hipEvent_t g_pool[2 * kMaxPending];
+const char* g_names[kMaxNames];
+float g_ms[kMaxNames];
+int g_count[kMaxNames];
+int g_nnames = 0;
+bool g_profile_error = false;
+
+void drain() {
+  for (int i = 0; i < g_npending; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_pending[i].stop) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_pending[i].start, g_pending[i].stop) != hipSuccess) {
+      g_profile_error = true;
+      continue;
+    }
+    int k = 0;
+    while (k < g_nnames && g_names[k] != g_pending[i].name && strcmp(g_names[k], g_pending[i].name)) ++k;
+    if (k == g_nnames) {
+      if (g_nnames == kMaxNames) continue;
+      g_names[g_nnames] = g_pending[i].name;
+      g_ms[g_nnames] = 0.f;
+      g_count[g_nnames] = 0;
+      ++g_nnames;
+    }
+    g_ms[k] += ms;
+    g_count[k] += 1;
+  }
+  g_npending = 0;
+}
+}  // namespace
+
+void profile_before(const char* name, hipStream_t st) {
+  if (g_npending == kMaxPending) drain();
+  Pending& p = g_pending[g_npending];
+  p.name = name;
+  p.start = g_pool[2 * g_npending];
+  p.stop = g_pool[2 * g_npending + 1];
+  if (hipEventRecord(p.start, st) != hipSuccess) g_profile_error = true;
+}
+void profile_after(hipStream_t st) {
+  if (hipEventRecord(g_pending[g_npending].stop, st) != hipSuccess) g_profile_error = true;
+  ++g_npending;
+}
+
+// ----------------------------------------------------------------------------
+// Planning
+// ----------------------------------------------------------------------------
+static wave_status check_dims(const wave_index* ix) {
+  if (!ix) return WAVE_ERR_ARG;
+  if (ix->dtype != WAVE_F32 && ix->dtype != WAVE_BF16) return WAVE_ERR_DTYPE;
+  if (ix->B < 1 || ix->Hkv < 1 || ix->N < 1 || ix->n_sink < 0 || ix->n_local < 0) return WAVE_ERR_ARG;
+  if (ix->segment_len < 1 || ix->clusters_per_segment < 1) return WAVE_ERR_ARG;
+  if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
+  if (ix->clusters_per_segment > 4096) return WAVE_ERR_SHAPE;
+  return WAVE_OK;
+}
+
+struct Derived {
+  int ns, local_start, N_idx, S, m, p;
+};
+static Derived derive(const wave_index& ix) {
+  Derived d;
+  d.ns = ix.n_sink < ix.N ? ix.n_sink : ix.N;
+  const long long ls = (long long)ix.N - ix.n_local;
+  d.local_start = ls > d.ns ? (int)ls : d.ns;
+  d.N_idx = d.local_start - d.ns;
+  d.p = d.ns + (ix.N - d.local_start);
+  const int L = ix.segment_len, k = ix.clusters_per_segment;
+  d.S = (d.N_idx + L - 1) / L;
+  const int full = d.N_idx / L, tail = d.N_idx - full * L;
+  d.m = full * (k < L ? k : L) + (tail > 0 ? (k < tail ? k : tail) : 0);
+  return d;
+}
+
+static bool planned_fields_match(const wave_index& ix) {
+  const Derived d = derive(ix);
+  return ix.S == d.S && ix.m == d.m && ix.N_idx == d.N_idx && ix.p == d.p;
+}
+
+BuildGeom build_geometry(const wave_index& ix);  // wave_build.hip
+
+}  // namespace wave
+
+using namespace wave;
+
+extern "C" {
+
+wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
+                            size_t* build_workspace_bytes, int Hq, int topk_clusters,
+                            size_t* decode_workspace_bytes) {
+  wave_status st = check_dims(ix);
+  if (st != WAVE_OK) return st;
+  if (!bytes) return WAVE_ERR_ARG;
+  const Derived d = derive(*ix);
+  if ((long long)ix->B * ix->Hkv * ((long long)d.m + 1) >= (1ll << 31)) return WAVE_ERR_SHAPE;
+  ix->S = d.S;
+  ix->m = d.m;
+  ix->N_idx = d.N_idx;
+  ix->p = d.p;
+  const size_t es = ix->dtype == WAVE_BF16 ? 2 : 4;
+  const size_t units = (size_t)ix->B * ix->Hkv;
+  bytes[0] = units * d.m * ix->d * es;
+  bytes[1] = units * d.m * ix->d * es;
+  bytes[2] = units * d.m * sizeof(int32_t);
+  bytes[3] = units * ((size_t)d.m + 1) * sizeof(int32_t);
+  bytes[4] = units * d.N_idx * sizeof(int32_t);
+  bytes[5] = units * d.N_idx * ix->d * es;
+  bytes[6] = bytes[5];
+  bytes[7] = units * d.p * ix->d * es;
+  bytes[8] = bytes[7];
+  if (build_workspace_bytes) *build_workspace_bytes = build_geometry(*ix).total;
+  if (decode_workspace_bytes) {
+    if (Hq < ix->Hkv || Hq % ix->Hkv != 0 || Hq / ix->Hkv > 8) return WAVE_ERR_SHAPE;
+    if (topk_clusters < 0) return WAVE_ERR_ARG;
+    *decode_workspace_bytes = decode_geometry(*ix, Hq, topk_clusters).total;
+  }
+  return WAVE_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static wave_status check_index_buffers(const wave_index& ix) {
+  if (ix.m > 0) {
+    if (!ix.centroids || !ix.vsum || !ix.sizes || !ix.offsets) return WAVE_ERR_ARG;
+    if (!ix.perm || !ix.k_perm || !ix.v_perm) return WAVE_ERR_ARG;
+    if (!aligned16(ix.centroids) || !aligned16(ix.vsum) || !aligned16(ix.k_perm) || !aligned16(ix.v_perm))
+      return WAVE_ERR_ARG;
+  }
+  if (ix.p > 0) {
+    if (!ix.k_steady || !ix.v_steady) return WAVE_ERR_ARG;
+    if (!aligned16(ix.k_steady) || !aligned16(ix.v_steady)) return WAVE_ERR_ARG;
+  }
+  return WAVE_OK;
+}
+
+wave_status wave_index_build(const void* K, const void* V, wave_index* ix, int iters, uint64_t seed,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  wave_status st = check_dims(ix);
+  if (st != WAVE_OK) return st;
+  if (!K || !V || iters < 1) return WAVE_ERR_ARG;
+  if (!aligned16(K) || !aligned16(V)) return WAVE_ERR_ARG;
+  if (!planned_fields_match(*ix)) return WAVE_ERR_SHAPE;
+  st = check_index_buffers(*ix);
+  if (st != WAVE_OK) return st;
+  const BuildGeom g = build_geometry(*ix);
+  if (g.total > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total))
+    return WAVE_ERR_WORKSPACE;
+  return launch_build(K, V, *ix, iters, seed, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+wave_status wave_attention_decode(const void* q, const wave_index* ix, int Hq, int topk_clusters,
+                                  int n_sink, int n_local, float* out, float* lse, int32_t* selected,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  wave_status st = check_dims(ix);
+  if (st != WAVE_OK) return st;
+  if (!q || !out || !lse || topk_clusters < 0) return WAVE_ERR_ARG;
+  if (!aligned16(q)) return WAVE_ERR_ARG;
+  if (Hq < ix->Hkv || Hq % ix->Hkv != 0 || Hq / ix->Hkv > 8) return WAVE_ERR_SHAPE;
+  if (!planned_fields_match(*ix)) return WAVE_ERR_SHAPE;
+  if (n_sink != ix->n_sink || n_local != ix->n_local) return WAVE_ERR_STEADY_MISMATCH;
+  st = check_index_buffers(*ix);
+  if (st != WAVE_OK) return st;
+  const DecodeGeom g = decode_geometry(*ix, Hq, topk_clusters);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total)
+    return WAVE_ERR_WORKSPACE;
+  return launch_decode(q, *ix, Hq, topk_clusters, out, lse, selected, workspace,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+wave_status wave_init_indices(uint64_t seed, int b, int h, int s, int L_s, int k_s, int32_t* out) {
+  if (!out || L_s < 1 || k_s < 1 || k_s > L_s) return WAVE_ERR_ARG;
+  // Fisher-Yates on a sparse image of the array: only positions that were
+  // swapped differ from the identity, and at most k_s of them exist.
+  struct Moved { int pos, val; };
+  Moved* moved = new Moved[k_s];
+  int nmoved = 0;
+  uint64_t st = init_stream_state(seed, b, h, s);
+  for (int i = 0; i < k_s; ++i) {
+    const uint64_t draw = splitmix64_next(st);
+    const int j = i + (int)(draw % (uint64_t)(L_s - i));
+    // value currently at j and at i
+    int vj = j, vi = i, at_j = -1;
+    for (int t = 0; t < nmoved; ++t) {
+      if (moved[t].pos == j) { vj = moved[t].val; at_j = t; }
+      if (moved[t].pos == i) vi = moved[t].val;
+    }
+    out[i] = vj;
+    if (j != i) {
+      if (at_j >= 0) moved[at_j].val = vi;
+      else { moved[nmoved].pos = j; moved[nmoved].val = vi; ++nmoved; }
+    }
+  }
+  delete[] moved;
+  return WAVE_OK;
+}
+
+wave_status wave_kmeans_assign_step(const void* xhat, const void* chat, int dtype, int L_s, int k_s,
+                                    int d, int32_t* assign, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+  if (!xhat || !chat || !assign) return WAVE_ERR_ARG;
+  if (dtype != WAVE_F32 && dtype != WAVE_BF16) return WAVE_ERR_DTYPE;
+  if (d != 64 && d != 128) return WAVE_ERR_SHAPE;
+  if (L_s < 1 || k_s < 1 || k_s > 4096 || k_s > L_s) return WAVE_ERR_SHAPE;
+  if (!aligned16(xhat) || !aligned16(chat)) return WAVE_ERR_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+      workspace_bytes < (size_t)4 * L_s + 1024)
+    return WAVE_ERR_WORKSPACE;
+  return launch_assign_step(xhat, chat, dtype, L_s, k_s, d, assign, workspace,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+wave_status wave_profile_enable(int on) {
+  if (on && !g_pool_ready) {
+    for (int i = 0; i < 2 * kMaxPending; ++i)
+      if (hipEventCreate(&g_pool[i]) != hipSuccess) return WAVE_ERR_HIP;
+    g_pool_ready = 1;
+  }
+  if (!on && g_profile_on) drain();
+  g_profile_on = on != 0;
+  return WAVE_OK;
+}
+
+int wave_profile_read(const char** names, float* total_ms, int* launches, int cap) {
+  drain();
+  if (g_profile_error) {
+    g_profile_error = false;
+    g_nnames = 0;
+    return -1;
+  }
+  const int n = g_nnames;
+  for (int i = 0; i < n && i < cap; ++i) {
+    if (names) names[i] = g_names[i];
+    if (total_ms) total_ms[i] = g_ms[i];
+    if (launches) launches[i] = g_count[i];
+  }
+  g_nnames = 0;
+  return n;
+}
+
+const char* wave_status_string(wave_status st) {
+  switch (st) {
+    case WAVE_OK: return "ok";
+    case WAVE_ERR_ARG: return "invalid argument";
+    case WAVE_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case WAVE_ERR_DTYPE: return "unsupported dtype";
+    case WAVE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case WAVE_ERR_STEADY_MISMATCH: return "n_sink/n_local differ from the index";
+    case WAVE_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,794 @@
+// Index construction of the wave index: segmented spherical k-means over the
+// keys of every (sequence, KV head) unit and the meta index / cluster-contiguous
+// KV layout that results (paper: "Index Organization", "Lightweight Index
+// Construction and Updates"; value sums and sizes from the estimation section).
+//
+// Per segment of L tokens:
+//   mean        fp64 mean of the segment's keys
+//   normalise   xhat = quant((K - mean) / |K - mean|)             (fp64, one rounding)
+//   init        k seeded distinct points of the segment become the first centroids
+//   T times:    assign  (bf16 MFMA similarities, fp32 accumulate; running best and
+//                        second best per point; near-ties flagged)
+//               refine  (flagged points re-decided with fp64 similarities)
+//               sort    (stable counting sort of the segment's points by cluster)
+//               update  (centroid = quant(member sum / |member sum|), fp64)
+//   finalize    sizes, offsets, mean of raw keys, value sums, permuted K/V rows
+#include "wave_common.h"
+
+namespace wave {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+constexpr float kNegHuge = -3.0e38f;
+// Two similarities closer than this are re-decided in fp64.  It covers the fp32
+// accumulation error of a unit-vector dot product (<= (d + 1) * 2^-24 < 8e-6) on
+// both values plus the 5 low mantissa bits the MFMA path overwrites with the row
+// code (<= 2^-18 relative each).
+constexpr float kAssignGuard = 4.0e-5f;
+
+struct SegInfo {
+  int unit, s, seg_start, L_s, k_s;
+};
+__device__ __forceinline__ SegInfo seg_info(int sg, int S, int L, int kk, int N_idx) {
+  SegInfo r;
+  r.unit = sg / S;
+  r.s = sg - r.unit * S;
+  r.seg_start = r.s * L;
+  r.L_s = min(L, N_idx - r.seg_start);
+  r.k_s = min(kk, r.L_s);
+  return r;
+}
+
+// ============================================================================
+// Segment mean (fp64).  One workgroup per segment; fixed summation order.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void seg_mean_kernel(const T* __restrict__ K, double* __restrict__ mean,
+                                                       int32_t* __restrict__ flag_count, int S, int L,
+                                                       int kk, int N, int N_idx, int n_sink) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sg = blockIdx.x;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  if (sg == 0 && threadIdx.x == 0) *flag_count = 0;
+  const T* Ku = K + ((size_t)si.unit * N + n_sink + si.seg_start) * D + sub * EPC;
+  double acc[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
+  for (int i = grp; i < si.L_s; i += GROUPS) {
+    float f[EPC];
+    unpack<T>(load16(Ku + (size_t)i * D), f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+  }
+  __shared__ double red[GROUPS][D];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) red[grp][sub * EPC + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    double s = 0.0;
+    for (int g = 0; g < GROUPS; ++g) s += red[g][threadIdx.x];
+    mean[(size_t)sg * D + threadIdx.x] = s / (double)si.L_s;
+  }
+}
+
+// ============================================================================
+// Centre, normalise, round to the storage type.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void normalise_kernel(const T* __restrict__ K,
+                                                        const double* __restrict__ mean,
+                                                        T* __restrict__ xhat, int S, int L, int N,
+                                                        int N_idx, int n_sink, int rows_total) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  for (int row = blockIdx.x * GROUPS + grp; row < rows_total; row += gridDim.x * GROUPS) {
+    const int unit = row / N_idx, pos = row - unit * N_idx;
+    const int s = pos / L;
+    const double* mu = mean + ((size_t)unit * S + s) * D + sub * EPC;
+    float f[EPC];
+    unpack<T>(load16(K + ((size_t)unit * N + n_sink + pos) * D + sub * EPC), f);
+    double x[EPC], n2 = 0.0;
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      x[e] = (double)f[e] - mu[e];
+      n2 = fma(x[e], x[e], n2);
+    }
+    n2 = group_sum_f64<LPR>(n2);
+    const double nrm = sqrt(n2);
+    const double dv = nrm > 0.0 ? nrm : 1.0;
+    T o[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(x[e] / dv);
+    store16(xhat + (size_t)row * D + sub * EPC, *reinterpret_cast<uint4*>(o));
+  }
+}
+
+// ============================================================================
+// Seeded initial centroids: a Fisher-Yates shuffle kept as a sparse list of the
+// positions that differ from the identity (at most k of them).  Wave 0 of the
+// workgroup runs the k sequential draws, its lanes searching the list together;
+// then the whole workgroup copies the chosen rows.
+// ============================================================================
+constexpr int KMAX = 4096;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
+                                                   int S, int L, int kk, int N_idx, int Hkv,
+                                                   uint64_t seed) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sg = blockIdx.x;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  __shared__ int mpos[KMAX], mval[KMAX], chosen[KMAX];
+  const int lane = threadIdx.x & 63;
+  if (threadIdx.x < 64) {
+    uint64_t st = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s);
+    int nmoved = 0;
+    for (int i = 0; i < si.k_s; ++i) {
+      const uint64_t draw = splitmix64_next(st);
+      const int j = i + (int)(draw % (uint64_t)(si.L_s - i));
+      int at_j = -1, at_i = -1;
+      for (int t = lane; t < nmoved; t += 64) {
+        const int p = mpos[t];
+        if (p == j) at_j = t;
+        if (p == i) at_i = t;
+      }
+      // each position occurs at most once in the list: a max over lanes finds it
+      for (int off = 32; off >= 1; off >>= 1) {
+        at_j = max(at_j, __shfl_xor(at_j, off));
+        at_i = max(at_i, __shfl_xor(at_i, off));
+      }
+      const int vj = at_j >= 0 ? mval[at_j] : j;
+      const int vi = at_i >= 0 ? mval[at_i] : i;
+      __builtin_amdgcn_wave_barrier();
+      if (lane == 0) {
+        chosen[i] = vj;
+        if (j != i) {
+          if (at_j >= 0) {
+            mval[at_j] = vi;
+          } else {
+            mpos[nmoved] = j;
+            mval[nmoved] = vi;
+          }
+        }
+      }
+      if (j != i && at_j < 0) ++nmoved;
+      __threadfence_block();
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  __syncthreads();
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const T* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D + sub * EPC;
+  T* Cs = chat + (size_t)sg * kk * D + sub * EPC;
+  for (int c = grp; c < si.k_s; c += GROUPS) store16(Cs + (size_t)c * D, load16(X + (size_t)chosen[c] * D));
+}
+
+// ============================================================================
+// Assign, MFMA path (bf16).  A workgroup of 4 waves takes 4 * 32 * NF points of
+// one segment.  Each wave keeps its points as B operands (K x N = 16 x 32 per
+// instruction) in registers for the whole kernel and streams the centroids,
+// 32 at a time, through a padded LDS tile as A operands (M x K = 32 x 16), so
+// D[centroid][point] accumulates in v_mfma_f32_32x32x16_bf16 and a lane holds
+// 16 centroid rows of ONE point: the running best / second best never leave the
+// lane.  The centroid row inside the tile is written over the 5 low mantissa
+// bits of the similarity so one v_max carries value and index.
+// ============================================================================
+template <int D, int NF>
+__global__ __launch_bounds__(256) void assign_mfma_kernel(
+    const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
+    int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
+    int wgs_per_seg) {
+  constexpr int KS = D / 16;            // MFMA k-steps per tile
+  constexpr int PW = 32 * NF;           // points per wave
+  constexpr int PWG = 4 * PW;           // points per workgroup
+  constexpr int ROWB = D * 2 + 16;      // LDS row pitch: 16 B pad keeps 16 lanes on 64 distinct banks
+  constexpr int CPR = D / 8;            // 16-byte chunks per centroid row
+  constexpr int CPT = 32 * CPR / 256;   // chunks each thread moves per tile
+  __shared__ __attribute__((aligned(16))) char lds[2][32 * ROWB];
+
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int sg = wg / wgs_per_seg, piece = wg - sg * wgs_per_seg;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int p0 = piece * PWG;
+  if (p0 >= si.L_s) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
+  const bf16_t* Cs = chat + (size_t)sg * kk * D;
+
+  uint4 bfrag[NF][KS];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    const int row = min(p0 + wave * PW + 32 * f + col, si.L_s - 1);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) bfrag[f][s] = load16(X + (size_t)row * D + (2 * s + half) * 8);
+  }
+  float best[NF], second[NF];
+  int btile[NF];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    best[f] = kNegHuge;
+    second[f] = kNegHuge;
+    btile[f] = 0;
+  }
+  // row of the 32-centroid tile held in accumulator register v of this lane
+  int rowcode[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) rowcode[v] = 8 * (v / 4) + 4 * half + (v % 4);
+
+  const int ntiles = (si.k_s + 31) / 32;
+  uint4 stage[CPT];
+  auto gload = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + 256 * i, row = id / CPR, ch = id - row * CPR;
+      const int crow = min(32 * t + row, si.k_s - 1);
+      stage[i] = load16(Cs + (size_t)crow * D + ch * 8);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + 256 * i, row = id / CPR, ch = id - row * CPR;
+      store16(&lds[buf][row * ROWB + ch * 16], stage[i]);
+    }
+  };
+  gload(0);
+  sstore(0);
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    if (t + 1 < ntiles) gload(t + 1);
+    floatx16 acc[NF];
+    const char* tile = lds[t & 1];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, load16(tile + col * ROWB + (2 * s + half) * 16));
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, bfrag[f][s]);
+        if (s == 0) {
+          const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                                 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, zero, 0, 0, 0);
+        } else {
+          acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, acc[f], 0, 0, 0);
+        }
+      }
+    }
+    const bool tail = 32 * t + 32 > si.k_s;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      const float before = best[f];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float key = __uint_as_float((__float_as_uint(acc[f][v]) & ~31u) | (uint32_t)rowcode[v]);
+        if (tail && 32 * t + rowcode[v] >= si.k_s) key = kNegHuge;
+        second[f] = __builtin_amdgcn_fmed3f(best[f], second[f], key);
+        best[f] = fmaxf(best[f], key);
+      }
+      btile[f] = (best[f] != before) ? t : btile[f];
+    }
+    if (t + 1 < ntiles) sstore((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // lanes l and l ^ 32 hold the same points over disjoint centroid rows
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    const float ob = __shfl_xor(best[f], 32), os = __shfl_xor(second[f], 32);
+    const int ot = __shfl_xor(btile[f], 32);
+    const float nsec = fmaxf(fminf(best[f], ob), fmaxf(second[f], os));
+    if (ob > best[f]) {
+      best[f] = ob;
+      btile[f] = ot;
+    }
+    second[f] = nsec;
+    const int point = p0 + wave * PW + 32 * f + col;
+    if (half == 0 && point < si.L_s) {
+      const size_t gp = (size_t)si.unit * N_idx + si.seg_start + point;
+      assign[gp] = btile[f] * 32 + (int)(__float_as_uint(best[f]) & 31u);
+      if (best[f] - second[f] < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+    }
+  }
+}
+
+// ============================================================================
+// Assign, plain path (any storage type): one point per thread, fp32 FMA chain,
+// centroids broadcast from LDS.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void assign_plain_kernel(
+    const T* __restrict__ xhat, const T* __restrict__ chat, int32_t* __restrict__ assign,
+    int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
+    int wgs_per_seg) {
+  constexpr int CT = 16;  // centroids per LDS tile
+  __shared__ __attribute__((aligned(16))) float cs[CT][D];
+  const int sg = blockIdx.x / wgs_per_seg, piece = blockIdx.x - sg * wgs_per_seg;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int p0 = piece * 256;
+  if (p0 >= si.L_s) return;
+  const int point = p0 + threadIdx.x;
+  const T* xr = xhat + ((size_t)si.unit * N_idx + si.seg_start + min(point, si.L_s - 1)) * D;
+  const T* Cs = chat + (size_t)sg * kk * D;
+  float x[D];
+#pragma unroll
+  for (int e = 0; e < D; ++e) x[e] = to_f32(xr[e]);
+  float best = kNegHuge, second = kNegHuge;
+  int bidx = 0;
+  for (int c0 = 0; c0 < si.k_s; c0 += CT) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < CT * D; i += 256) {
+      const int r = i / D, e = i - r * D;
+      cs[r][e] = to_f32(Cs[(size_t)min(c0 + r, si.k_s - 1) * D + e]);
+    }
+    __syncthreads();
+    const int nc = min(CT, si.k_s - c0);
+    for (int r = 0; r < nc; ++r) {
+      float a = 0.f;
+#pragma unroll
+      for (int e = 0; e < D; ++e) a = fmaf(x[e], cs[r][e], a);
+      if (a > best) {
+        second = best;
+        best = a;
+        bidx = c0 + r;
+      } else {
+        second = fmaxf(second, a);
+      }
+    }
+  }
+  if (point < si.L_s) {
+    const size_t gp = (size_t)si.unit * N_idx + si.seg_start + point;
+    assign[gp] = bidx;
+    if (best - second < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+  }
+}
+
+// ============================================================================
+// Refine: every flagged point gets its argmax from fp64 similarities (exact for
+// the stored operands up to fp64 rounding), ties to the lowest centroid.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void refine_kernel(const T* __restrict__ xhat, const T* __restrict__ chat,
+                                                     int32_t* __restrict__ assign,
+                                                     const int32_t* __restrict__ flag_list,
+                                                     const int32_t* __restrict__ flag_count, int S,
+                                                     int L, int kk, int N_idx) {
+  __shared__ double xs[D];
+  __shared__ double bval[4];
+  __shared__ int bidx[4];
+  const int n = *flag_count;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int it = blockIdx.x; it < n; it += gridDim.x) {
+    const int gp = flag_list[it];
+    const int unit = gp / N_idx, pos = gp - unit * N_idx;
+    const int s = pos / L;
+    const int L_s = min(L, N_idx - s * L), k_s = min(kk, L_s);
+    const T* Cs = chat + ((size_t)unit * S + s) * kk * D;
+    __syncthreads();
+    if (threadIdx.x < D) xs[threadIdx.x] = to_f64(xhat[(size_t)gp * D + threadIdx.x]);
+    __syncthreads();
+    double bv = -1.0e300;
+    int bi = 0x7fffffff;
+    for (int c = threadIdx.x; c < k_s; c += 256) {
+      const T* row = Cs + (size_t)c * D;
+      double a = 0.0;
+      for (int e = 0; e < D; ++e) a = fma(xs[e], to_f64(row[e]), a);
+      if (a > bv) {  // c ascends within a thread, so strict > keeps the lowest index
+        bv = a;
+        bi = c;
+      }
+    }
+    for (int off = 32; off >= 1; off >>= 1) {
+      const double ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      if (ov > bv || (ov == bv && oi < bi)) {
+        bv = ov;
+        bi = oi;
+      }
+    }
+    if (lane == 0) {
+      bval[wave] = bv;
+      bidx[wave] = bi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (bval[w] > bv || (bval[w] == bv && bidx[w] < bi)) {
+          bv = bval[w];
+          bi = bidx[w];
+        }
+      assign[gp] = bi;
+    }
+  }
+}
+
+// ============================================================================
+// Stable counting sort of one segment's points by cluster.  Wave w owns the
+// w-th contiguous stripe of the segment and a private row of counters, so the
+// scatter keeps positions ascending inside every cluster.
+// ============================================================================
+constexpr int SORT_HIST_INTS = 11264;  // LDS budget for the per-wave counters
+
+__global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ assign,
+                                                    int32_t* __restrict__ order,
+                                                    int32_t* __restrict__ count,
+                                                    int32_t* __restrict__ start,
+                                                    int32_t* __restrict__ flag_count, int S, int L,
+                                                    int kk, int N_idx, int key_bits) {
+  extern __shared__ int hist[];  // [W][kk], then kk ints of scan space
+  const int sg = blockIdx.x;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int W = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (sg == 0 && tid == 0) *flag_count = 0;  // the refine pass before this one has consumed it
+  const int32_t* a = assign + (size_t)si.unit * N_idx + si.seg_start;
+  int32_t* ord = order + (size_t)si.unit * N_idx + si.seg_start;
+  int* tot = hist + W * kk;
+  for (int i = tid; i < W * kk; i += blockDim.x) hist[i] = 0;
+  __syncthreads();
+  const int stripe = (si.L_s + W - 1) / W;
+  const int s0 = min(si.L_s, wave * stripe), s1 = min(si.L_s, s0 + stripe);
+  for (int i = s0 + lane; i < s1; i += 64) atomicAdd(&hist[wave * kk + a[i]], 1);
+  __syncthreads();
+  // per cluster: exclusive scan over the waves, total into tot[]
+  for (int c = tid; c < kk; c += blockDim.x) {
+    int run = 0;
+    for (int w = 0; w < W; ++w) {
+      const int t = hist[w * kk + c];
+      hist[w * kk + c] = run;
+      run += t;
+    }
+    tot[c] = run;
+  }
+  __syncthreads();
+  // exclusive scan of the totals over clusters (one wave, chunks of 64)
+  if (wave == 0) {
+    int carry = 0;
+    for (int c0 = 0; c0 < kk; c0 += 64) {
+      const int c = c0 + lane;
+      const int v = c < kk ? tot[c] : 0;
+      int inc = v;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+      }
+      if (c < kk) {
+        count[(size_t)sg * kk + c] = v;
+        start[(size_t)sg * kk + c] = carry + inc - v;
+        tot[c] = carry + inc - v;
+      }
+      carry += __shfl(inc, 63);
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < W * kk; i += blockDim.x) hist[i] += tot[i % kk];
+  __syncthreads();
+  // scatter, 64 points of the stripe at a time
+  for (int i0 = s0; i0 < s1; i0 += 64) {
+    const int i = i0 + lane;
+    const bool on = i < s1;
+    const int key = on ? a[i] : -1;
+    // lanes holding the same key
+    uint64_t peers = __ballot(on);
+    for (int bit = 0; bit < key_bits; ++bit) {
+      const uint64_t bal = __ballot((key >> bit) & 1);
+      peers &= ((key >> bit) & 1) ? bal : ~bal;
+    }
+    const uint64_t below = peers & ((1ull << lane) - 1ull);
+    const int rank = __popcll(below), cnt = __popcll(peers);
+    if (on) {
+      const int base = hist[wave * kk + key];
+      ord[base + rank] = i;
+      __builtin_amdgcn_wave_barrier();
+      if (rank == cnt - 1) hist[wave * kk + key] = base + cnt;
+    }
+    __threadfence_block();
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// ============================================================================
+// Update: one group of LPR lanes per cluster sums its members' xhat in fp64.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
+                                                     const int32_t* __restrict__ order,
+                                                     const int32_t* __restrict__ count,
+                                                     const int32_t* __restrict__ start, int S, int L,
+                                                     int kk, int N_idx, int nclusters) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int gc = blockIdx.x * GROUPS + grp;  // sg * kk + c
+  if (gc >= nclusters) return;
+  const int sg = gc / kk, c = gc - sg * kk;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  if (c >= si.k_s) return;
+  const int n = count[gc], st = start[gc];
+  if (n == 0) return;  // an empty cluster keeps its centroid
+  const int32_t* ord = order + (size_t)si.unit * N_idx + si.seg_start + st;
+  const T* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D + sub * EPC;
+  double acc[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
+  int i = 0;
+  for (; i + 4 <= n; i += 4) {
+    uint4 raw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) raw[u] = load16(X + (size_t)ord[i + u] * D);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float f[EPC];
+      unpack<T>(raw[u], f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+    }
+  }
+  for (; i < n; ++i) {
+    float f[EPC];
+    unpack<T>(load16(X + (size_t)ord[i] * D), f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+  }
+  double n2 = 0.0;
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) n2 = fma(acc[e], acc[e], n2);
+  n2 = group_sum_f64<LPR>(n2);
+  const double nrm = sqrt(n2);
+  if (!(nrm > 0.0)) return;  // members cancel: keep the centroid
+  T o[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(acc[e] / nrm);
+  store16(chat + (size_t)gc * D + sub * EPC, *reinterpret_cast<uint4*>(o));
+}
+
+// ============================================================================
+// Finalize: sizes, offsets, mean of raw keys, value sums, permuted rows.
+// ============================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(256) void finalize_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ order,
+    const int32_t* __restrict__ count, const int32_t* __restrict__ start, T* __restrict__ centroids,
+    T* __restrict__ vsum, int32_t* __restrict__ sizes, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, T* __restrict__ k_perm, T* __restrict__ v_perm, int S, int L, int kk,
+    int N, int N_idx, int n_sink, int m, int nclusters) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int gc = blockIdx.x * GROUPS + grp;
+  if (gc >= nclusters) return;
+  const int sg = gc / kk, c = gc - sg * kk;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  if (c >= si.k_s) return;
+  const int n = count[gc], st = start[gc];
+  const int cid = si.s * kk + c;  // only the last segment can have fewer than kk clusters
+  const size_t urow = (size_t)si.unit * N_idx;
+  const int row0 = si.seg_start + st;
+  if (sub == 0) {
+    sizes[(size_t)si.unit * m + cid] = n;
+    offsets[(size_t)si.unit * (m + 1) + cid] = row0;
+    if (cid == m - 1) offsets[(size_t)si.unit * (m + 1) + m] = N_idx;
+  }
+  const int32_t* ord = order + urow + si.seg_start + st;
+  const T* Ku = K + ((size_t)si.unit * N + n_sink + si.seg_start) * D + sub * EPC;
+  const T* Vu = V + ((size_t)si.unit * N + n_sink + si.seg_start) * D + sub * EPC;
+  double ka[EPC], va[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) ka[e] = va[e] = 0.0;
+  for (int i = 0; i < n; i += 2) {
+    const int i1 = min(i + 1, n - 1);
+    const int pa = ord[i], pb = ord[i1];
+    const uint4 k0 = load16(Ku + (size_t)pa * D), v0 = load16(Vu + (size_t)pa * D);
+    const uint4 k1 = load16(Ku + (size_t)pb * D), v1 = load16(Vu + (size_t)pb * D);
+    float f[EPC];
+    store16(k_perm + (urow + row0 + i) * D + sub * EPC, k0);
+    store16(v_perm + (urow + row0 + i) * D + sub * EPC, v0);
+    if (sub == 0) perm[urow + row0 + i] = n_sink + si.seg_start + pa;
+    unpack<T>(k0, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
+    unpack<T>(v0, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) va[e] += (double)f[e];
+    if (i + 1 < n) {
+      store16(k_perm + (urow + row0 + i + 1) * D + sub * EPC, k1);
+      store16(v_perm + (urow + row0 + i + 1) * D + sub * EPC, v1);
+      if (sub == 0) perm[urow + row0 + i + 1] = n_sink + si.seg_start + pb;
+      unpack<T>(k1, f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
+      unpack<T>(v1, f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) va[e] += (double)f[e];
+    }
+  }
+  T oc[EPC], ov[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) {
+    oc[e] = quant_store<T>(n > 0 ? ka[e] / (double)n : 0.0);
+    ov[e] = quant_store<T>(va[e]);
+  }
+  store16(centroids + ((size_t)si.unit * m + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(oc));
+  store16(vsum + ((size_t)si.unit * m + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(ov));
+}
+
+// Steady rows: the first ns and the last (N - local_start) tokens of every unit.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void steady_copy_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                          T* __restrict__ ks, T* __restrict__ vs, int N,
+                                                          int ns, int local_start, int p,
+                                                          int rows_total) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  for (int row = blockIdx.x * GROUPS + grp; row < rows_total; row += gridDim.x * GROUPS) {
+    const int unit = row / p, i = row - unit * p;
+    const int src = i < ns ? i : local_start + (i - ns);
+    store16(ks + (size_t)row * D + sub * EPC, load16(K + ((size_t)unit * N + src) * D + sub * EPC));
+    store16(vs + (size_t)row * D + sub * EPC, load16(V + ((size_t)unit * N + src) * D + sub * EPC));
+  }
+}
+
+__global__ void zero_int_kernel(int32_t* p) { *p = 0; }
+
+// ============================================================================
+// Host
+// ============================================================================
+static int min_kL(const wave_index& ix) {
+  return ix.clusters_per_segment < ix.segment_len ? ix.clusters_per_segment : ix.segment_len;
+}
+
+BuildGeom build_geometry(const wave_index& ix) {
+  BuildGeom g{};
+  g.units = ix.B * ix.Hkv;
+  g.segs = g.units * ix.S;
+  if (ix.m == 0) {
+    g.total = 0;
+    return g;
+  }
+  const size_t es = ix.dtype == WAVE_BF16 ? 2 : 4;
+  const size_t pts = (size_t)g.units * ix.N_idx;
+  const size_t ncl = (size_t)g.segs * min_kL(ix);
+  size_t o = 0;
+  g.off_xhat = o;   o = align_up(o + pts * ix.d * es);
+  g.off_chat = o;   o = align_up(o + ncl * ix.d * es);
+  g.off_assign = o; o = align_up(o + pts * sizeof(int32_t));
+  g.off_order = o;  o = align_up(o + pts * sizeof(int32_t));
+  g.off_count = o;  o = align_up(o + 2 * ncl * sizeof(int32_t));   // count, then start
+  g.off_flag = o;   o = align_up(o + pts * sizeof(int32_t));
+  g.off_nflag = o;  o = align_up(o + 256);
+  g.off_init = o;   o = align_up(o + (size_t)g.segs * ix.d * sizeof(double));  // segment means
+  g.total = o;
+  return g;
+}
+
+static int key_bits_for(int kk) {
+  int b = 1;
+  while ((1 << b) < kk) ++b;
+  return b;
+}
+
+template <typename T, int D>
+static void launch_assign(const T* xhat, const T* chat, int32_t* assign, int32_t* flag, int32_t* nflag,
+                          int S, int L, int kk, int N_idx, int segs, hipStream_t st) {
+  const int Lmax = L < N_idx ? L : N_idx;
+  if constexpr (sizeof(T) == 2) {
+    constexpr int NF = 4, PWG = 4 * 32 * NF;
+    const int wps = (Lmax + PWG - 1) / PWG;
+    WAVE_LAUNCH("assign_mfma", (assign_mfma_kernel<D, NF>), segs * wps, 256, 0, st, xhat, chat, assign,
+                flag, nflag, S, L, kk, N_idx, wps);
+  } else {
+    const int wps = (Lmax + 255) / 256;
+    WAVE_LAUNCH("assign_plain", (assign_plain_kernel<T, D>), segs * wps, 256, 0, st, xhat, chat,
+                assign, flag, nflag, S, L, kk, N_idx, wps);
+  }
+}
+
+template <typename T, int D>
+static wave_status build_td(const void* K_, const void* V_, const wave_index& ix, int iters,
+                            uint64_t seed, void* ws, hipStream_t st) {
+  const T* K = static_cast<const T*>(K_);
+  const T* V = static_cast<const T*>(V_);
+  const int units = ix.B * ix.Hkv;
+  const int ns = ix.n_sink < ix.N ? ix.n_sink : ix.N;
+  const int local_start = ns + ix.N_idx;
+  if (ix.p > 0) {
+    const int rows = units * ix.p;
+    const int grid = (rows + 15) / 16 < 65536 ? (rows + 15) / 16 : 65536;
+    WAVE_LAUNCH("steady_copy", (steady_copy_kernel<T, D>), grid, 256, 0, st, K, V,
+                static_cast<T*>(ix.k_steady), static_cast<T*>(ix.v_steady), ix.N, ns, local_start, ix.p,
+                rows);
+  }
+  if (ix.m == 0) return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+
+  const BuildGeom g = build_geometry(ix);
+  char* w = static_cast<char*>(ws);
+  T* xhat = reinterpret_cast<T*>(w + g.off_xhat);
+  T* chat = reinterpret_cast<T*>(w + g.off_chat);
+  int32_t* assign = reinterpret_cast<int32_t*>(w + g.off_assign);
+  int32_t* order = reinterpret_cast<int32_t*>(w + g.off_order);
+  const int kk = min_kL(ix);
+  const int ncl = g.segs * kk;
+  int32_t* count = reinterpret_cast<int32_t*>(w + g.off_count);
+  int32_t* start = count + ncl;
+  int32_t* flag = reinterpret_cast<int32_t*>(w + g.off_flag);
+  int32_t* nflag = reinterpret_cast<int32_t*>(w + g.off_nflag);
+  double* mean = reinterpret_cast<double*>(w + g.off_init);
+  const int S = ix.S, L = ix.segment_len, N_idx = ix.N_idx;
+  constexpr int GROUPS = 256 / (D / Elem<T>::EPC);
+
+  WAVE_LAUNCH("seg_mean", (seg_mean_kernel<T, D>), g.segs, 256, 0, st, K, mean, nflag, S, L, kk, ix.N,
+              N_idx, ns);
+  {
+    const long long rows = (long long)units * N_idx;
+    const long long want = (rows + GROUPS - 1) / GROUPS;
+    const int grid = (int)(want < 262144 ? want : 262144);
+    WAVE_LAUNCH("normalise", (normalise_kernel<T, D>), grid, 256, 0, st, K, mean, xhat, S, L, ix.N,
+                N_idx, ns, (int)rows);
+  }
+  WAVE_LAUNCH("init", (init_kernel<T, D>), g.segs, 256, 0, st, xhat, chat, S, L, kk, N_idx, ix.Hkv,
+              seed);
+
+  int W = SORT_HIST_INTS / kk;
+  if (W > 16) W = 16;
+  if (W < 1) W = 1;
+  const size_t sort_lds = ((size_t)W * kk + kk) * sizeof(int);
+  const int kb = key_bits_for(kk);
+  const int cl_grid = (ncl + GROUPS - 1) / GROUPS;
+  for (int t = 0; t < iters; ++t) {
+    launch_assign<T, D>(xhat, chat, assign, flag, nflag, S, L, kk, N_idx, g.segs, st);
+    WAVE_LAUNCH("refine", (refine_kernel<T, D>), 1024, 256, 0, st, xhat, chat, assign, flag, nflag, S,
+                L, kk, N_idx);
+    WAVE_LAUNCH("sort", sort_kernel, g.segs, 64 * W, sort_lds, st, assign, order, count, start, nflag,
+                S, L, kk, N_idx, kb);
+    if (t + 1 < iters)
+      WAVE_LAUNCH("update", (update_kernel<T, D>), cl_grid, 256, 0, st, xhat, chat, order, count,
+                  start, S, L, kk, N_idx, ncl);
+  }
+  WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
+              static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,
+              static_cast<T*>(ix.k_perm), static_cast<T*>(ix.v_perm), S, L, kk, ix.N, N_idx, ns, ix.m,
+              ncl);
+  return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+}
+
+wave_status launch_build(const void* K, const void* V, const wave_index& ix, int iters, uint64_t seed,
+                         void* ws, hipStream_t st) {
+  if (ix.dtype == WAVE_BF16) {
+    if (ix.d == 128) return build_td<bf16_t, 128>(K, V, ix, iters, seed, ws, st);
+    if (ix.d == 64) return build_td<bf16_t, 64>(K, V, ix, iters, seed, ws, st);
+  } else {
+    if (ix.d == 128) return build_td<float, 128>(K, V, ix, iters, seed, ws, st);
+    if (ix.d == 64) return build_td<float, 64>(K, V, ix, iters, seed, ws, st);
+  }
+  return WAVE_ERR_SHAPE;
+}
+
+template <typename T, int D>
+static wave_status assign_step_td(const void* xhat, const void* chat, int L_s, int k_s, int32_t* assign,
+                                  void* ws, hipStream_t st) {
+  int32_t* nflag = static_cast<int32_t*>(ws);
+  int32_t* flag = nflag + 64;
+  hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, nflag);
+  // one unit, one segment: S = 1, L = N_idx = L_s, kk = k_s
+  launch_assign<T, D>(static_cast<const T*>(xhat), static_cast<const T*>(chat), assign, flag, nflag, 1,
+                      L_s, k_s, L_s, 1, st);
+  WAVE_LAUNCH("refine", (refine_kernel<T, D>), 256, 256, 0, st, static_cast<const T*>(xhat),
+              static_cast<const T*>(chat), assign, flag, nflag, 1, L_s, k_s, L_s);
+  return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+}
+
+wave_status launch_assign_step(const void* xhat, const void* chat, int dtype, int L_s, int k_s, int d,
+                               int32_t* assign, void* ws, hipStream_t st) {
+  if (dtype == WAVE_BF16) {
+    if (d == 128) return assign_step_td<bf16_t, 128>(xhat, chat, L_s, k_s, assign, ws, st);
+    if (d == 64) return assign_step_td<bf16_t, 64>(xhat, chat, L_s, k_s, assign, ws, st);
+  } else {
+    if (d == 128) return assign_step_td<float, 128>(xhat, chat, L_s, k_s, assign, ws, st);
+    if (d == 64) return assign_step_td<float, 64>(xhat, chat, L_s, k_s, assign, ws, st);
+  }
+  return WAVE_ERR_SHAPE;
+}
+
+}  // namespace wave

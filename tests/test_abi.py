@@ -1,0 +1,128 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/wave.h
+declares, plans like the oracle lays segments out, refuses bad arguments before
+any launch, and draws the same seed points as the oracle.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import wave_oracle as wo
+from paper_2505_02922_amd import binding as wb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "wave.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wave_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(wb.EXPORTS), names
+    L = wb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_struct_layout_matches_header():
+    # 14 int32 fields then 9 pointers
+    assert ctypes.sizeof(wb.wave_index) == 14 * 4 + 9 * 8
+    assert wb.wave_index.centroids.offset == 56
+
+
+@pytest.mark.parametrize("N,ns,nl,L,k", [(4096, 4, 64, 2048, 128), (32768, 4, 1024, 8192, 512),
+                                           (122880, 4, 1024, 8192, 512), (1048576, 4, 1024, 8192, 512),
+                                           (50, 4, 64, 2048, 128), (100, 4, 64, 2048, 128),
+                                           (700, 0, 0, 256, 300), (513, 1, 0, 256, 16)])
+def test_plan_matches_oracle_layout(N, ns, nl, L, k):
+    c, sizes, bws, dws = wb.wave_index_plan(torch.bfloat16, 2, 3, 128, N, ns, nl, L, k, Hq=12,
+                                            topk_clusters=7)
+    p = wo.make_plan(N, ns, nl, L, k)
+    assert (c.S, c.m, c.N_idx, c.p) == (p.S, p.m, p.N_idx, p.steady_positions.size)
+    u = 6
+    assert sizes == [u * p.m * 128 * 2, u * p.m * 128 * 2, u * p.m * 4, u * (p.m + 1) * 4,
+                     u * p.N_idx * 4, u * p.N_idx * 128 * 2, u * p.N_idx * 128 * 2,
+                     u * c.p * 128 * 2, u * c.p * 128 * 2]
+    assert dws > 0 and (bws > 0) == (p.m > 0)
+
+
+def test_status_strings():
+    for code in range(7):
+        assert len(wb.lib().wave_status_string(code)) > 0
+
+
+def _plan_struct(**kw):
+    args = dict(dtype=torch.bfloat16, B=1, Hkv=2, d=128, N=5000, n_sink=4, n_local=64,
+                segment_len=1024, clusters_per_segment=64)
+    args.update(kw)
+    return wb.wave_index_plan(**args)
+
+
+def test_plan_rejects_bad_shapes():
+    for kw, code in [(dict(d=96), 2), (dict(clusters_per_segment=5000), 2), (dict(B=0), 1),
+                     (dict(segment_len=0), 1), (dict(n_sink=-1), 1)]:
+        with pytest.raises(wb.WaveError) as e:
+            _plan_struct(**kw)
+        assert e.value.status == code, kw
+    with pytest.raises(wb.WaveError) as e:
+        _plan_struct(Hq=5, topk_clusters=3)      # 5 query heads over 2 KV heads
+    assert e.value.status == 2
+    with pytest.raises(wb.WaveError) as e:
+        _plan_struct(Hq=18, topk_clusters=3)     # G = 9 > 8
+    assert e.value.status == 2
+    with pytest.raises(wb.WaveError):
+        wb.wave_index_plan(torch.float16, 1, 1, 128, 100, 0, 0, 10, 2)
+
+
+def test_entry_points_refuse_bad_arguments_on_the_host():
+    """All of these must return before anything is launched (no GPU here)."""
+    L = wb.lib()
+    c, sizes, bws, dws = _plan_struct(Hq=8, topk_clusters=4)
+    fake = ctypes.c_void_p(0x1000)    # never dereferenced: checks fail first
+    # null K
+    assert L.wave_index_build(None, fake, ctypes.byref(c), 10, 0, fake, bws, None) == 1
+    # iters < 1
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 0, 0, fake, bws, None) == 1
+    # index buffers missing
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 10, 0, fake, bws, None) == 1
+    for name in wb.BUFFER_NAMES:
+        setattr(c, name, 0x1000)
+    # workspace too small / misaligned / null
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 10, 0, fake, bws - 1, None) == 4
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 10, 0, ctypes.c_void_p(0x1010), bws, None) == 4
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 10, 0, None, bws, None) == 4
+    # planned fields tampered with
+    c.m += 1
+    assert L.wave_index_build(fake, fake, ctypes.byref(c), 10, 0, fake, bws, None) == 2
+    c.m -= 1
+    # decode: steady mismatch, bad Hq, small workspace, negative topk
+    dec = lambda Hq, topk, ns, nl, wsb: L.wave_attention_decode(fake, ctypes.byref(c), Hq, topk, ns, nl,
+                                                                fake, fake, None, fake, wsb, None)
+    assert dec(8, 4, 4, 65, dws) == 5
+    assert dec(8, 4, 5, 64, dws) == 5
+    assert dec(7, 4, 4, 64, dws) == 2
+    assert dec(8, -1, 4, 64, dws) == 1
+    assert dec(8, 4, 4, 64, dws - 1) == 4
+    # a larger topk needs a larger workspace than the one planned for topk = 4
+    assert dec(8, 60, 4, 64, dws) == 4
+    # assign-step hook
+    assert L.wave_kmeans_assign_step(fake, fake, 1, 100, 200, 128, fake, fake, 1 << 20, None) == 2
+    assert L.wave_kmeans_assign_step(fake, fake, 7, 100, 10, 128, fake, fake, 1 << 20, None) == 3
+    assert L.wave_kmeans_assign_step(fake, fake, 1, 100, 10, 128, fake, fake, 100, None) == 4
+
+
+def test_init_indices_match_the_oracle():
+    grid = [(0, 0, 0, 0, 2048, 128), (0, 0, 0, 1, 1980, 128), (7, 3, 5, 11, 8192, 512),
+            (2 ** 63 + 5, 15, 7, 14, 7164, 512), (1, 0, 0, 0, 40, 40), (9, 2, 1, 0, 1, 1),
+            (123456789, 63, 3, 7, 300, 299), (5, 0, 1, 2, 8192, 1)]
+    for seed, b, h, s, L_s, k_s in grid:
+        got = wb.wave_init_indices(seed, b, h, s, L_s, k_s)
+        want = wo.init_indices(seed, b, h, s, L_s, k_s).tolist()
+        assert got == want, (seed, b, h, s, L_s, k_s)
+    with pytest.raises(wb.WaveError):
+        wb.wave_init_indices(0, 0, 0, 0, 10, 11)

@@ -1,0 +1,208 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import wave_oracle as wo
+from paper_2505_02922_amd import binding as wb
+from paper_2505_02922_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+WL = synth.WORKLOADS
+
+
+def _small(base, **kw):
+    return synth.scaled(WL[base], **kw)
+
+
+CASES = {
+    # the tiny single-head f32 workload as defined
+    "tiny_f32": WL["tiny_f32"],
+    # bf16, GQA 4:1, d = 128, two full segments and a ragged tail, several score/gather tiles
+    "bf16_g4": _small("llama8b_32k", name="bf16_g4", N=5000, Hq=8, Hkv=2, segment_len=2048,
+                      clusters_per_segment=128, n_local=200, n_components=256, iters=4,
+                      retrieve_frac=0.05),
+    # GQA 7:1 with heavy-tailed channels, two sequences
+    "bf16_g7": _small("qwen7b_64k_b64", name="bf16_g7", B=2, N=3000, Hq=7, Hkv=1, segment_len=1024,
+                      clusters_per_segment=64, n_local=100, n_components=128, iters=3,
+                      retrieve_frac=0.08),
+    # d = 64 in bf16 (8 lanes per row) and G = 2
+    "bf16_d64": _small("llama8b_32k", name="bf16_d64", d=64, N=2500, Hq=4, Hkv=2, segment_len=1024,
+                       clusters_per_segment=100, n_local=50, n_components=128, iters=3,
+                       retrieve_frac=0.1),
+    # d = 128 in f32 (32 lanes per row)
+    "f32_d128": _small("tiny_f32", name="f32_d128", d=128, N=1500, Hq=2, Hkv=1, segment_len=512,
+                       clusters_per_segment=32, n_local=30, iters=3, retrieve_abs=9),
+}
+
+
+def _inputs(wl, query_set=0):
+    K, V = synth.make_kv(wl)
+    q = synth.make_queries(wl, query_set)
+    return K, V, q
+
+
+def _decode_and_check(wl, ix_gpu, index_ref, q, r, what):
+    out, lse, sel = wb.wave_attention_decode(q.cuda(), ix_gpu, r, want_selected=True)
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    sel = sel.cpu().numpy() if sel is not None else None
+    qn = q.double().numpy()
+    swaps = 0
+    for b in range(wl.B):
+        for hq in range(wl.Hq):
+            parts = {}
+            o, l, s = wo.decode_unit(qn[b, hq], index_ref[(b, hq // wl.G)], r, parts)
+            tag = f"{what} b={b} hq={hq} r={r}"
+            pu.check_outputs(out[b, hq], lse[b, hq:hq + 1], o, np.array([l]), wl.dtype, tag)
+            if r > 0:
+                swaps += pu.check_selected(sel[b, hq], s, parts["z"], tag)
+    return swaps
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_decode_on_oracle_index(case):
+    """Decode kernels alone: the index is the oracle's, copied to the device."""
+    wl = CASES[case]
+    K, V, q = _inputs(wl)
+    index_ref = pu.oracle_build(wl, K, V)
+    arrays = pu.oracle_index_arrays(wl, index_ref)
+    ix = wb.index_from_arrays(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
+                              wl.segment_len, wl.clusters_per_segment, arrays)
+    m = ix.m
+    for r in sorted({0, 1, pu.retrieve_count(wl), m // 2, m, m + 3}):
+        _decode_and_check(wl, ix, index_ref, q, r, case)
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_assign_step_teacher_forced(case):
+    """One assign step on the oracle's normalised keys and centroids of every
+    k-means round of the first segment."""
+    wl = CASES[case]
+    K, V, _ = _inputs(wl)
+    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+    for s in (0, plan.S - 1):
+        lo, Ls, ks = plan.seg_start[s], plan.seg_len[s], plan.seg_k[s]
+        trace = []
+        wo.kmeans_segment(K[0, 0, lo:lo + Ls].double().numpy(), wo.init_indices(0, 0, 0, s, Ls, ks),
+                          wl.iters, wl.dtype, trace)
+        for t, (xhat, chat, a_ref) in enumerate(trace):
+            xg = torch.from_numpy(xhat).to(wl.torch_dtype()).cuda()
+            cg = torch.from_numpy(chat).to(wl.torch_dtype()).cuda()
+            a = wb.wave_kmeans_assign_step(xg, cg)
+            torch.cuda.synchronize()
+            pu.check_assign(a.cpu().numpy(), xhat, chat, f"{case} seg {s} round {t}")
+
+
+def _compare_index(wl, ix, index_ref, what):
+    torch.cuda.synchronize()
+    got = {n: ix.t[n].float().cpu().numpy() if ix.t[n].is_floating_point() else ix.t[n].cpu().numpy()
+           for n in wb.BUFFER_NAMES}
+    ties = 0
+    for b in range(wl.B):
+        for h in range(wl.Hkv):
+            ref = index_ref[(b, h)]
+            tag = f"{what} b={b} h={h}"
+            # the partition: cluster of every indexed token, recovered from perm + offsets
+            a_gpu = np.empty(ref.plan.N_idx, dtype=np.int64)
+            sizes = got["sizes"][b, h]
+            offs = got["offsets"][b, h]
+            assert offs[0] == 0 and offs[-1] == ref.plan.N_idx, tag
+            assert np.array_equal(np.diff(offs), sizes), tag
+            perm = got["perm"][b, h]
+            assert sorted(perm.tolist()) == list(range(ref.plan.n_sink, ref.plan.local_start)), tag
+            a_gpu[perm - ref.plan.n_sink] = np.repeat(np.arange(ref.plan.m), sizes)
+            if not np.array_equal(a_gpu, ref.assign):
+                ties += int((a_gpu != ref.assign).sum())
+                continue    # a legal tie flipped: later rounds may differ; counted below
+            assert np.array_equal(sizes, ref.sizes), tag
+            assert np.array_equal(perm, ref.perm), tag
+            assert np.array_equal(got["k_perm"][b, h], ref.k_perm.astype(np.float32)), tag
+            assert np.array_equal(got["v_perm"][b, h], ref.v_perm.astype(np.float32)), tag
+            assert np.array_equal(got["centroids"][b, h], ref.centroids.astype(np.float32)), tag
+            assert np.array_equal(got["vsum"][b, h], ref.vsum.astype(np.float32)), tag
+            assert np.array_equal(got["k_steady"][b, h], ref.k_steady.astype(np.float32)), tag
+            assert np.array_equal(got["v_steady"][b, h], ref.v_steady.astype(np.float32)), tag
+    return ties
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_build_matches_oracle_then_decode(case):
+    """Whole path: GPU build, every index array against the oracle's, then GPU
+    decode on the GPU-built index against the oracle's decode on its own."""
+    wl = CASES[case]
+    K, V, q = _inputs(wl)
+    index_ref = pu.oracle_build(wl, K, V)
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    ties = _compare_index(wl, ix, index_ref, case)
+    assert ties == 0, f"{case}: {ties} points assigned differently from the oracle"
+    _decode_and_check(wl, ix, index_ref, q, pu.retrieve_count(wl), case)
+
+
+def test_all_retrieved_is_full_attention():
+    wl = CASES["bf16_g4"]
+    K, V, q = _inputs(wl, 1)
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, 2, 5)
+    out, lse, _ = wb.wave_attention_decode(q.cuda(), ix, ix.m)
+    torch.cuda.synchronize()
+    for hq in range(wl.Hq):
+        o, l = wo.full_attention(q[0, hq].double().numpy(), K[0, hq // wl.G].double().numpy(),
+                                 V[0, hq // wl.G].double().numpy())
+        pu.check_outputs(out[0, hq].cpu().numpy(), lse[0, hq:hq + 1].cpu().numpy(), o, np.array([l]),
+                         wl.dtype, f"full hq={hq}")
+
+
+@pytest.mark.parametrize("N,n_sink,n_local,L,k", [
+    (60, 4, 64, 256, 16),      # N <= p: no index at all, exact attention over everything
+    (68, 4, 64, 256, 16),      # N == p
+    (69, 4, 64, 256, 16),      # one indexed token
+    (100, 4, 64, 256, 64),     # one short segment, k capped by its length (singleton clusters)
+    (600, 0, 0, 256, 8),       # no steady zone
+    (513, 1, 0, 256, 16),      # last segment of a single token
+])
+def test_degenerate_shapes(N, n_sink, n_local, L, k):
+    wl = _small("llama8b_32k", name="deg", N=N, Hq=4, Hkv=2, n_sink=n_sink, n_local=n_local,
+                segment_len=L, clusters_per_segment=k, n_components=16, iters=3)
+    K, V, q = _inputs(wl)
+    index_ref = pu.oracle_build(wl, K, V)
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), n_sink, n_local, L, k, wl.iters, 0)
+    assert _compare_index(wl, ix, index_ref, "deg") == 0
+    for r in (0, 2, 1000):
+        _decode_and_check(wl, ix, index_ref, q, r, f"deg N={N}")
+
+
+def test_duplicate_keys_and_empty_clusters():
+    """Every key of a component identical: many exact ties in assign (lowest
+    centroid wins, the others stay empty) and in the centroid scores."""
+    wl = _small("llama8b_32k", name="dups", N=1200, Hq=4, Hkv=1, n_sink=2, n_local=10,
+                segment_len=512, clusters_per_segment=48, n_components=20, iters=4, sigma=0.0,
+                rope_base=None)
+    K, V, q = _inputs(wl)
+    index_ref = pu.oracle_build(wl, K, V)
+    assert (index_ref[(0, 0)].sizes == 0).any()
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    assert _compare_index(wl, ix, index_ref, "dups") == 0
+    for r in (0, 3, 10, 40):
+        _decode_and_check(wl, ix, index_ref, q, r, "dups")
+
+
+def test_errors_surface_as_status_codes():
+    wl = CASES["bf16_d64"]
+    K, V, q = _inputs(wl)
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, 1, 0)
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_attention_decode(q.cuda(), ix, 4, n_sink=wl.n_sink + 1)
+    assert e.value.status == 5
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_attention_decode(q.cuda(), ix, 4, ws=wb.workspace(256))
+    assert e.value.status == 4
+    torch.cuda.synchronize()
