@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the wave-index hot path on one MI355X.
+
+One "step" is one decode call of the whole batch (all sequences, all query
+heads of one layer) over an index that was built once, on device, before the
+timed region; the build itself is timed separately and reported in the same
+JSON line.  Inputs (K, V, 16 rotating query sets) are generated on the GPU and
+are resident in HBM when timing starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Prints ONE JSON line ("Measurement").
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+N_QUERY_SETS = 16
+
+
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_120k_b16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: every (sequence, KV head) unit is independent and "
+              "this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2505_02922_amd import binding as wb
+    from paper_2505_02922_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    wb.lib()   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.WORKLOADS[args.workload]
+    es = 2 if wl.dtype == "bf16" else 4
+
+    # ---------------- inputs, resident in HBM ----------------
+    K, V = synth.make_kv(wl, device=dev)
+    queries = [synth.make_queries(wl, i, device=dev) for i in range(N_QUERY_SETS)]
+    torch.cuda.synchronize()
+
+    # ---------------- index build ----------------
+    ix = wb.alloc_index(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
+                        wl.segment_len, wl.clusters_per_segment, dev)
+    bws = wb.workspace(ix.build_ws_bytes, dev)
+
+    def build():
+        wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
+                            wl.iters, 0, ws=bws, index=ix)
+
+    build()
+    torch.cuda.synchronize()
+    build_ms = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        build()
+        e1.record()
+        torch.cuda.synchronize()
+        build_ms.append(e0.elapsed_time(e1))
+    wb.wave_profile_enable(True)
+    build()
+    build_prof = wb.wave_profile_read()
+    wb.wave_profile_enable(False)
+    plan_full = ix.N_idx // wl.segment_len
+    tail = ix.N_idx - plan_full * wl.segment_len
+    kk = min(wl.clusters_per_segment, wl.segment_len)
+    assign_flops = 2.0 * wl.d * wl.iters * wl.B * wl.Hkv * (
+        plan_full * wl.segment_len * kk + tail * min(kk, tail))
+    assign_name = "assign_mfma" if wl.dtype == "bf16" else "assign_plain"
+    assign_ms, assign_n = build_prof.get(assign_name, (0.0, 0))
+    build_info = {
+        "ms": round(_median(build_ms), 3),
+        "assign_flops": assign_flops,
+        "assign_ms_per_launch": round(assign_ms / max(assign_n, 1), 4),
+        "assign_tflops": round(assign_flops / max(assign_ms, 1e-9) / 1e9, 2),
+        "assign_frac_of_bf16_peak": round(assign_flops / max(assign_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "assign_share_of_build": round(assign_ms / max(sum(v[0] for v in build_prof.values()), 1e-9), 3),
+        "kernels_ms": {k: round(v[0], 3) for k, v in sorted(build_prof.items())},
+    }
+    del bws
+    torch.cuda.empty_cache()
+
+    # ---------------- decode ----------------
+    from tests import parity_util as pu
+    r = pu.retrieve_count(wl)
+    dws = wb.workspace(wb.decode_workspace_bytes(ix, wl.Hq, r), dev)
+    out = torch.empty(wl.B, wl.Hq, wl.d, dtype=torch.float32, device=dev)
+    lse = torch.empty(wl.B, wl.Hq, dtype=torch.float32, device=dev)
+    sel = torch.empty(wl.B, wl.Hq, max(r, 1), dtype=torch.int32, device=dev)
+
+    def step(i):
+        wb.wave_attention_decode(queries[i % N_QUERY_SETS], ix, r, out=out, lse=lse, selected=sel, ws=dws)
+
+    # retrieved tokens per query set (for the algorithmic byte count)
+    sizes = ix.sizes.to(torch.int64)                     # [B, Hkv, m]
+    retrieved_tokens = []
+    for i in range(N_QUERY_SETS):
+        step(i)
+        torch.cuda.synchronize()
+        ids = sel.to(torch.int64)                        # [B, Hq, r], -1 padded
+        sz = sizes.repeat_interleave(wl.G, dim=1)        # [B, Hq, m]
+        tok = torch.where(ids >= 0, sz.gather(2, ids.clamp(min=0)), torch.zeros_like(ids)).sum()
+        retrieved_tokens.append(int(tok))
+    mean_tokens = sum(retrieved_tokens) / len(retrieved_tokens)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # per-kernel durations, same loop with the library's event profiler on
+    wb.wave_profile_enable(True)
+    for i in range(args.profile_steps):
+        step(i)
+    dec_prof = wb.wave_profile_read()
+    wb.wave_profile_enable(False)
+
+    units = wl.B * wl.Hkv
+    row = wl.d * es
+    bytes_k = {
+        "score": units * ix.m * row + units * ix.m * 4,
+        "estimate": units * ix.m * row + units * ix.m * 4,
+        "steady": 2 * units * ix.p * row,
+        "gather": 2 * mean_tokens * row,
+        "select": 0, "merge": 0,
+    }
+    step_bytes = sum(bytes_k.values())
+    kern = {k: v[0] / max(v[1], 1) for k, v in dec_prof.items()}      # ms per launch
+    dominant = max(kern, key=kern.get)
+    dom_gbs = bytes_k.get(dominant, 0) / (kern[dominant] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(wl.name, {}).get(dominant)
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+                "traffic": traffic, "bytes_per_launch": int(bytes_k.get(dominant, 0)),
+                "ms_per_launch": round(kern[dominant], 5)}
+    decode_info = {
+        "algorithmic_bytes_per_step": int(step_bytes),
+        "step_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "retrieved_tokens_per_step": round(mean_tokens, 1),
+        "kernels_ms_per_launch": {k: round(v, 5) for k, v in sorted(kern.items())},
+        "kernels_GBps": {k: round(bytes_k.get(k, 0) / (v * 1e-3) / 1e9, 1) for k, v in sorted(kern.items())
+                         if bytes_k.get(k, 0)},
+        "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
+    }
+
+    # ---------------- CPU baseline: the oracle on a bounded sample ----------------
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import wave_oracle as wo
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        sample_units = [(0, h) for h in range(min(wl.Hkv, 2 if wl.N > 200000 else 4))]
+        Kh = {u: K[u[0], u[1]].double().cpu().numpy() for u in sample_units}
+        Vh = {u: V[u[0], u[1]].double().cpu().numpy() for u in sample_units}
+        plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+        t0 = time.perf_counter()
+        ref = {u: wo.build_unit(Kh[u], Vh[u], plan, wl.iters, 0, u[0], u[1], wl.dtype)
+               for u in sample_units}
+        t_build = time.perf_counter() - t0
+        nsets = 4
+        qh = [queries[i].double().cpu().numpy() for i in range(nsets)]
+        heads = [(u, u[1] * wl.G + g) for u in sample_units for g in range(wl.G)]
+        t0 = time.perf_counter()
+        ref_out = {}
+        for i in range(nsets):
+            for (u, hq) in heads:
+                ref_out[(i, u[0], hq)] = wo.decode_unit(qh[i][u[0], hq], ref[u], r)
+        t_dec = time.perf_counter() - t0
+        per_head = t_dec / (nsets * len(heads))
+        cpu = {"value": round(1.0 / (per_head * wl.B * wl.Hq), 4), "unit": "steps/s", "cores": cores,
+               "kind": "oracle",
+               "sample": f"{len(heads)} of {wl.B * wl.Hq} (sequence, query head) units x {nsets} "
+                         f"query sets, scaled linearly to the whole batch; index of "
+                         f"{len(sample_units)} of {units} units built by the oracle first",
+               "oracle_build_s_per_unit": round(t_build / len(sample_units), 3),
+               "oracle_build_s_whole_batch_extrapolated": round(t_build / len(sample_units) * units, 1),
+               "oracle_decode_ms_per_head": round(per_head * 1e3, 3)}
+        # parity of the benchmarked configuration on the sampled units
+        worst, lworst, same_sel, same_index = 0.0, 0.0, True, True
+        for u in sample_units:
+            same_index &= bool(np.array_equal(ix.sizes[u[0], u[1]].cpu().numpy(), ref[u].sizes) and
+                               np.array_equal(ix.perm[u[0], u[1]].cpu().numpy(), ref[u].perm))
+        for i in range(nsets):
+            step(i)
+            torch.cuda.synchronize()
+            o_g, l_g, s_g = out.cpu().numpy(), lse.cpu().numpy(), sel.cpu().numpy()
+            for (u, hq) in heads:
+                o, l, s = ref_out[(i, u[0], hq)]
+                worst = max(worst, float(np.abs(o_g[u[0], hq] - o).max()))
+                lworst = max(lworst, abs(float(l_g[u[0], hq]) - l))
+                same_sel &= bool(np.array_equal(s_g[u[0], hq][s_g[u[0], hq] >= 0], s))
+        parity = {"sampled_heads": len(heads), "query_sets": nsets, "index_equal": same_index,
+                  "selected_equal": same_sel, "out_max_abs_err": worst, "lse_max_abs_err": lworst}
+
+    line = {
+        "metric": "decode attention steps/sec at 120K ctx" if wl.name == "llama8b_120k_b16"
+                  else f"decode attention steps/sec ({wl.name})",
+        "value": round(1e3 / ms_per_step, 2), "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "Hq": wl.Hq, "Hkv": wl.Hkv, "d": wl.d, "N": wl.N,
+                   "segment_len": wl.segment_len, "clusters_per_segment": wl.clusters_per_segment,
+                   "iters": wl.iters, "m": ix.m, "topk_clusters": r, "n_sink": wl.n_sink,
+                   "n_local": wl.n_local},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "decode": decode_info,
+        "build": build_info,
+        "parity": parity,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

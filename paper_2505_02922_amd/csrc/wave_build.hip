@@ -631,6 +631,10 @@ __global__ __launch_bounds__(256) void steady_copy_kernel(const T* __restrict__ 
 }
 
 __global__ void zero_int_kernel(int32_t* p) { *p = 0; }
+__global__ void fill_int_kernel(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
 
 // ============================================================================
 // Host
@@ -700,7 +704,12 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
                 static_cast<T*>(ix.k_steady), static_cast<T*>(ix.v_steady), ix.N, ns, local_start, ix.p,
                 rows);
   }
-  if (ix.m == 0) return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+  if (ix.m == 0) {
+    // nothing to cluster: the offsets array is the single entry offsets[0] = 0 per unit
+    if (ix.offsets)
+      WAVE_LAUNCH("fill", fill_int_kernel, (units + 255) / 256, 256, 0, st, ix.offsets, units, 0);
+    return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+  }
 
   const BuildGeom g = build_geometry(ix);
   char* w = static_cast<char*>(ws);

@@ -769,6 +769,11 @@ __global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part
   if (e == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
 }
 
+__global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 // ============================================================================
 // Host: geometry and launches
 // ============================================================================
@@ -839,6 +844,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                 static_cast<const T*>(ix.vsum), ix.sizes, z, bitmap, zref, ix.Hkv, m, g.mwords,
                 g.est_chunks, g.est_rows, g.slots, g.gather_chunks + g.steady_chunks, scale_log2,
                 part);
+  }
+  if (m == 0 && selected && topk > 0) {
+    const size_t n = (size_t)heads * topk;  // no clusters exist: nothing is selected
+    WAVE_LAUNCH("fill", fill_i32_kernel, (unsigned)((n + 255) / 256), 256, 0, st, selected, n, -1);
   }
   if (g.steady_chunks > 0)
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
