@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--workload", default="llama8b_120k_b16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--only", choices=["all", "build", "decode"], default="all",
+                    help="build: stop after the index build (for profiler runs); "
+                         "decode: build once untimed, then only the decode phase")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: every (sequence, KV head) unit is independent and "
@@ -78,17 +81,19 @@ def main() -> int:
     build()
     torch.cuda.synchronize()
     build_ms = []
-    for _ in range(3):
+    for _ in range(3 if args.only != "decode" else 0):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         build()
         e1.record()
         torch.cuda.synchronize()
         build_ms.append(e0.elapsed_time(e1))
-    wb.wave_profile_enable(True)
-    build()
-    build_prof = wb.wave_profile_read()
-    wb.wave_profile_enable(False)
+    build_prof = {}
+    if args.only != "decode":
+        wb.wave_profile_enable(True)
+        build()
+        build_prof = wb.wave_profile_read()
+        wb.wave_profile_enable(False)
     plan_full = ix.N_idx // wl.segment_len
     tail = ix.N_idx - plan_full * wl.segment_len
     kk = min(wl.clusters_per_segment, wl.segment_len)
@@ -97,7 +102,7 @@ def main() -> int:
     assign_name = "assign_mfma" if wl.dtype == "bf16" else "assign_plain"
     assign_ms, assign_n = build_prof.get(assign_name, (0.0, 0))
     build_info = {
-        "ms": round(_median(build_ms), 3),
+        "ms": round(_median(build_ms), 3) if build_ms else None,
         "assign_flops": assign_flops,
         "assign_ms_per_launch": round(assign_ms / max(assign_n, 1), 4),
         "assign_tflops": round(assign_flops / max(assign_ms, 1e-9) / 1e9, 2),
@@ -107,6 +112,9 @@ def main() -> int:
     }
     del bws
     torch.cuda.empty_cache()
+    if args.only == "build":
+        print(json.dumps({"workload": wl.name, "build": build_info}))
+        return 0
 
     # ---------------- decode ----------------
     from tests import parity_util as pu

@@ -13,6 +13,8 @@
 //               sort    (stable counting sort of the segment's points by cluster)
 //               update  (centroid = quant(member sum / |member sum|), fp64)
 //   finalize    sizes, offsets, mean of raw keys, value sums, permuted K/V rows
+#include <stdlib.h>
+
 #include "wave_common.h"
 
 namespace wave {
@@ -22,9 +24,9 @@ typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr float kNegHuge = -3.0e38f;
 // Two similarities closer than this are re-decided in fp64.  It covers the fp32
-// accumulation error of a unit-vector dot product (<= (d + 1) * 2^-24 < 8e-6) on
-// both values plus the 5 low mantissa bits the MFMA path overwrites with the row
-// code (<= 2^-18 relative each).
+// accumulation error of a unit-vector dot product (<= (d + 1) * 2^-24 < 8e-6; in the
+// MFMA path the sums run near 2, so 8 steps of 2^-23) on both values plus the 5 low
+// mantissa bits the MFMA path overwrites with the row code (<= 2^-18 relative each).
 constexpr float kAssignGuard = 4.0e-5f;
 
 struct SegInfo {
@@ -166,26 +168,61 @@ __global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T
 }
 
 // ============================================================================
-// Assign, MFMA path (bf16).  A workgroup of 4 waves takes 4 * 32 * NF points of
-// one segment.  Each wave keeps its points as B operands (K x N = 16 x 32 per
+// Assign, MFMA path (bf16).  A workgroup of NW waves takes NW * 32 * NF points
+// of one segment.  Each wave keeps its points as B operands (K x N = 16 x 32 per
 // instruction) in registers for the whole kernel and streams the centroids,
 // 32 at a time, through a padded LDS tile as A operands (M x K = 32 x 16), so
 // D[centroid][point] accumulates in v_mfma_f32_32x32x16_bf16 and a lane holds
 // 16 centroid rows of ONE point: the running best / second best never leave the
-// lane.  The centroid row inside the tile is written over the 5 low mantissa
-// bits of the similarity so one v_max carries value and index.
+// lane.  Four of the five bits of the centroid's row inside the tile are written
+// over low mantissa bits of the similarity (the fifth is the lane's half), so
+// one v_med3 pair carries value and index: 3 VALU instructions per similarity.
 // ============================================================================
-template <int D, int NF>
-__global__ __launch_bounds__(256) void assign_mfma_kernel(
+// Similarities of unit vectors lie in [-1, 1]; the accumulators start at
+// kAssignBias so every value is a positive float, whose bit pattern orders like
+// a signed integer: max and median then run on the integer pipes, free of the
+// NaN handling a float max drags in.
+constexpr float kAssignBias = 2.0f;
+
+__device__ __forceinline__ int med3_i32(int a, int b, int c) {
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+template <int NF, bool TAIL>
+__device__ __forceinline__ void assign_epilogue(const floatx16 (&acc)[NF], int (&best)[NF],
+                                                int (&second)[NF], int (&btile)[NF], int t, int half,
+                                                int k_s) {
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    const int before = best[f];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      constexpr uint32_t kClear = ~27u;               // bits 0,1,3,4 carry the row code
+      const uint32_t code = 8u * (v / 4) + (v % 4);   // row = code | 4 * half
+      int key = (int)((__float_as_uint(acc[f][v]) & kClear) | code);
+      if (TAIL && 32 * t + (int)code + 4 * half >= k_s) key = 0;
+      second[f] = med3_i32(best[f], second[f], key);
+      best[f] = max(best[f], key);
+    }
+    btile[f] = (best[f] != before) ? t : btile[f];
+  }
+}
+
+template <int D, int NF, int NW>
+__global__ __launch_bounds__(64 * NW) void assign_mfma_kernel(
     const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
     int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
     int wgs_per_seg) {
   constexpr int KS = D / 16;            // MFMA k-steps per tile
   constexpr int PW = 32 * NF;           // points per wave
-  constexpr int PWG = 4 * PW;           // points per workgroup
+  constexpr int PWG = NW * PW;          // points per workgroup
+  constexpr int NT = 64 * NW;           // threads
   constexpr int ROWB = D * 2 + 16;      // LDS row pitch: 16 B pad keeps 16 lanes on 64 distinct banks
   constexpr int CPR = D / 8;            // 16-byte chunks per centroid row
-  constexpr int CPT = 32 * CPR / 256;   // chunks each thread moves per tile
+  constexpr int CHUNKS = 32 * CPR;      // chunks per tile
+  constexpr int CPT = (CHUNKS + NT - 1) / NT;  // chunks each thread moves per tile
   __shared__ __attribute__((aligned(16))) char lds[2][32 * ROWB];
 
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
@@ -205,42 +242,34 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) bfrag[f][s] = load16(X + (size_t)row * D + (2 * s + half) * 8);
   }
-  float best[NF], second[NF];
-  int btile[NF];
+  int best[NF], second[NF], btile[NF];  // biased similarities as integers; 0 is below all of them
 #pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    best[f] = kNegHuge;
-    second[f] = kNegHuge;
-    btile[f] = 0;
-  }
-  // row of the 32-centroid tile held in accumulator register v of this lane
-  int rowcode[16];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) rowcode[v] = 8 * (v / 4) + 4 * half + (v % 4);
+  for (int f = 0; f < NF; ++f) best[f] = second[f] = btile[f] = 0;
 
   const int ntiles = (si.k_s + 31) / 32;
-  uint4 stage[CPT];
-  auto gload = [&](int t) {
+  // Centroid tiles travel global -> registers -> LDS.  Two register stages keep
+  // the loads two tiles ahead of the MFMAs that consume them.
+  uint4 stage[2][CPT];
+  auto gload = [&](int t, uint4 (&st)[CPT]) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      const int id = tid + 256 * i, row = id / CPR, ch = id - row * CPR;
-      const int crow = min(32 * t + row, si.k_s - 1);
-      stage[i] = load16(Cs + (size_t)crow * D + ch * 8);
+      const int id = tid + NT * i, row = id / CPR, ch = id - row * CPR;
+      if (CHUNKS % NT == 0 || id < CHUNKS) {
+        const int crow = min(32 * t + row, si.k_s - 1);
+        st[i] = load16(Cs + (size_t)crow * D + ch * 8);
+      }
     }
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](int buf, const uint4 (&st)[CPT]) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      const int id = tid + 256 * i, row = id / CPR, ch = id - row * CPR;
-      store16(&lds[buf][row * ROWB + ch * 16], stage[i]);
+      const int id = tid + NT * i, row = id / CPR, ch = id - row * CPR;
+      if (CHUNKS % NT == 0 || id < CHUNKS) store16(&lds[buf][row * ROWB + ch * 16], st[i]);
     }
   };
-  gload(0);
-  sstore(0);
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
-    if (t + 1 < ntiles) gload(t + 1);
+  auto tile_step = [&](int t, uint4 (&st_next)[CPT], uint4 (&st_load)[CPT]) {
+    // st_next holds tile t + 1 (requested one step ago); st_load receives tile t + 2
+    if (t + 2 < ntiles) gload(t + 2, st_load);
     floatx16 acc[NF];
     const char* tile = lds[t & 1];
 #pragma unroll
@@ -250,47 +279,48 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(
       for (int f = 0; f < NF; ++f) {
         const bf16x8 bv = __builtin_bit_cast(bf16x8, bfrag[f][s]);
         if (s == 0) {
-          const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
-                                 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, zero, 0, 0, 0);
+          constexpr float B0 = kAssignBias;
+          const floatx16 bias = {B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0};
+          acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, bias, 0, 0, 0);
         } else {
           acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, acc[f], 0, 0, 0);
         }
       }
     }
-    const bool tail = 32 * t + 32 > si.k_s;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      const float before = best[f];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float key = __uint_as_float((__float_as_uint(acc[f][v]) & ~31u) | (uint32_t)rowcode[v]);
-        if (tail && 32 * t + rowcode[v] >= si.k_s) key = kNegHuge;
-        second[f] = __builtin_amdgcn_fmed3f(best[f], second[f], key);
-        best[f] = fmaxf(best[f], key);
-      }
-      btile[f] = (best[f] != before) ? t : btile[f];
-    }
-    if (t + 1 < ntiles) sstore((t + 1) & 1);
+    if (32 * t + 32 > si.k_s)
+      assign_epilogue<NF, true>(acc, best, second, btile, t, half, si.k_s);
+    else
+      assign_epilogue<NF, false>(acc, best, second, btile, t, half, si.k_s);
+    if (t + 1 < ntiles) sstore((t + 1) & 1, st_next);
     __syncthreads();
+  };
+  gload(0, stage[0]);
+  if (ntiles > 1) gload(1, stage[1]);
+  sstore(0, stage[0]);
+  __syncthreads();
+  for (int t = 0; t < ntiles; t += 2) {
+    tile_step(t, stage[1], stage[0]);
+    if (t + 1 < ntiles) tile_step(t + 1, stage[0], stage[1]);
   }
 
   // lanes l and l ^ 32 hold the same points over disjoint centroid rows
 #pragma unroll
   for (int f = 0; f < NF; ++f) {
-    const float ob = __shfl_xor(best[f], 32), os = __shfl_xor(second[f], 32);
-    const int ot = __shfl_xor(btile[f], 32);
-    const float nsec = fmaxf(fminf(best[f], ob), fmaxf(second[f], os));
+    int brow = (best[f] & 27) | (4 * half);
+    const int ob = __shfl_xor(best[f], 32), os = __shfl_xor(second[f], 32);
+    const int ot = __shfl_xor(btile[f], 32), orow = __shfl_xor(brow, 32);
+    const int nsec = max(min(best[f], ob), max(second[f], os));
     if (ob > best[f]) {
       best[f] = ob;
       btile[f] = ot;
+      brow = orow;
     }
-    second[f] = nsec;
     const int point = p0 + wave * PW + 32 * f + col;
     if (half == 0 && point < si.L_s) {
       const size_t gp = (size_t)si.unit * N_idx + si.seg_start + point;
-      assign[gp] = btile[f] * 32 + (int)(__float_as_uint(best[f]) & 31u);
-      if (best[f] - second[f] < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+      assign[gp] = btile[f] * 32 + brow;
+      const float gap = __int_as_float(best[f]) - (nsec > 0 ? __int_as_float(nsec) : 0.f);
+      if (gap < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
     }
   }
 }
@@ -678,10 +708,26 @@ static void launch_assign(const T* xhat, const T* chat, int32_t* assign, int32_t
                           int S, int L, int kk, int N_idx, int segs, hipStream_t st) {
   const int Lmax = L < N_idx ? L : N_idx;
   if constexpr (sizeof(T) == 2) {
-    constexpr int NF = 4, PWG = 4 * 32 * NF;
-    const int wps = (Lmax + PWG - 1) / PWG;
-    WAVE_LAUNCH("assign_mfma", (assign_mfma_kernel<D, NF>), segs * wps, 256, 0, st, xhat, chat, assign,
-                flag, nflag, S, L, kk, N_idx, wps);
+    // tuning knob while the kernel shape is being chosen: WAVE_ASSIGN=<NF><NW>
+    static int variant = -1;
+    if (variant < 0) {
+      const char* e = getenv("WAVE_ASSIGN");
+      variant = e ? atoi(e) : 108;
+    }
+#define WAVE_ASSIGN_CASE(nf, nw)                                                                     \
+  case nf * 100 + nw: {                                                                               \
+    constexpr int PWG = nw * 32 * nf;                                                                \
+    const int wps = (Lmax + PWG - 1) / PWG;                                                          \
+    WAVE_LAUNCH("assign_mfma", (assign_mfma_kernel<D, nf, nw>), segs * wps, 64 * nw, 0, st, xhat,    \
+                chat, assign, flag, nflag, S, L, kk, N_idx, wps);                                    \
+    break;                                                                                           \
+  }
+    switch (variant) {
+      WAVE_ASSIGN_CASE(1, 4) WAVE_ASSIGN_CASE(1, 8) WAVE_ASSIGN_CASE(1, 16) WAVE_ASSIGN_CASE(2, 4)
+      WAVE_ASSIGN_CASE(2, 8) WAVE_ASSIGN_CASE(2, 16) WAVE_ASSIGN_CASE(4, 4) WAVE_ASSIGN_CASE(4, 8)
+      default: break;
+    }
+#undef WAVE_ASSIGN_CASE
   } else {
     const int wps = (Lmax + 255) / 256;
     WAVE_LAUNCH("assign_plain", (assign_plain_kernel<T, D>), segs * wps, 256, 0, st, xhat, chat,
