@@ -178,6 +178,7 @@ struct DecodeGeom {
   int slots;                       // partial results per query head
   int mwords;                      // 32-bit words of the selection bitmap per query head
   int rcap;                        // entries of the selected-id list per query head
+  int fused;                       // selection and retrieval fused into one workgroup per head
   size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);

@@ -96,9 +96,9 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
 //    the selected clusters, their ids ascending, the running token count of the
 //    selected clusters, and the reference score for the estimation zone.
 // ============================================================================
-constexpr int SEL_THREADS = 512;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int CAND_CAP = 1024;
+constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
+__device__ long long g_sel_prof[16];
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t u = __float_as_uint(f);
@@ -108,8 +108,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// Exclusive prefix sum of one int per thread across the workgroup; returns the
-// thread's prefix and the total through `total`.  scratch: SEL_WAVES + 1 ints.
+// Exclusive prefix sum of one int per thread across a workgroup of NT threads;
+// returns the thread's prefix and the total.  scratch: NT / 64 ints.
+template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int* scratch, int& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = v;
@@ -123,7 +124,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int* scratch, int& total) 
   __syncthreads();
   int base = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < SEL_WAVES; ++w) {
+  for (int w = 0; w < NT / 64; ++w) {
     const int s = scratch[w];
     if (w < wave) base += s;
     tot += s;
@@ -132,19 +133,25 @@ __device__ __forceinline__ int block_excl_scan(int v, int* scratch, int& total) 
   return base + inc - v;
 }
 
+template <int NT>
 __device__ __forceinline__ int block_sum_i(int v, int* scratch) {
   int t;
-  block_excl_scan(v, scratch, t);
+  block_excl_scan<NT>(v, scratch, t);
   return t;
 }
 
-template <typename T, int D>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+// NT threads per query head; with VPT > 0 every thread keeps VPT scores in
+// registers (m <= NT * VPT) and all passes run on them, with VPT == 0 the
+// scores are re-read from memory in every pass.
+template <typename T, int D, int NT, int VPT>
+__global__ __launch_bounds__(NT) void select_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
-    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap, float* __restrict__ zref_out,
-    int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected) {
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected) {
+  constexpr int NW = NT / 64;
   const int bh = blockIdx.x;  // b * Hq + hq
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
   const int unit = b * Hkv + hq / G;
@@ -153,32 +160,54 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
   const int32_t* off = offsets + (size_t)unit * (m + 1);
   int32_t* ids = sel_ids + (size_t)bh * rcap;
   int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
+  int32_t* srow = sel_row + (size_t)bh * rcap;
   uint32_t* bits = bitmap + (size_t)bh * mwords;
   int32_t* usel = user_selected ? user_selected + (size_t)bh * usel_stride : nullptr;
-  int32_t* srow = sel_row + (size_t)bh * rcap;
 
   __shared__ int hist[256];
-  __shared__ int scan_scratch[SEL_WAVES + 1];
-  __shared__ float fred[SEL_WAVES];
+  __shared__ int scan_scratch[NW];
+  __shared__ float fred[NW];
   __shared__ int cand_id[CAND_CAP];
   __shared__ double cand_z[CAND_CAP];
   __shared__ int sh_i[4];
   __shared__ float sh_f[2];
 
+  float zc[VPT > 0 ? VPT : 1];
+  if constexpr (VPT > 0) {
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+      const int i = k * NT + tid;
+      zc[k] = i < m ? zz[i] : -INFINITY;
+    }
+  }
+  // fn(i, v) runs for every i in [0, round_up(m, NT)), v = -inf past the end;
+  // all lanes of a wave make the same calls, so fn may use wave-wide operations.
+  auto scan = [&](auto fn) {
+    if constexpr (VPT > 0) {
+#pragma unroll
+      for (int k = 0; k < VPT; ++k)
+        if (k * NT < m) fn(k * NT + tid, zc[k]);
+    } else {
+      for (int base = 0; base < m; base += NT) {
+        const int i = base + tid;
+        fn(i, i < m ? zz[i] : -INFINITY);
+      }
+    }
+  };
+
   // ---- valid count and maximum -------------------------------------------
   int nv = 0;
   float zmax = -INFINITY;
-  for (int i = tid; i < m; i += SEL_THREADS) {
-    const float v = zz[i];
+  scan([&](int, float v) {
     nv += (v > -INFINITY) ? 1 : 0;
     zmax = fmaxf(zmax, v);
-  }
+  });
   zmax = wave_max(zmax);
   if (lane == 0) fred[wave] = zmax;
-  const int nvalid = block_sum_i(nv, scan_scratch);  // contains the barriers that publish fred
+  const int nvalid = block_sum_i<NT>(nv, scan_scratch);  // its barriers publish fred
   zmax = fred[0];
 #pragma unroll
-  for (int w = 1; w < SEL_WAVES; ++w) zmax = fmaxf(zmax, fred[w]);
+  for (int w = 1; w < NW; ++w) zmax = fmaxf(zmax, fred[w]);
   const int r_eff = min(r, nvalid);
 
   // mode 0: nothing selected; 1: every valid cluster; 2: threshold + exact band; 3: fp32 rule
@@ -198,14 +227,27 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
       const int shift = 24 - 8 * pass;
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
-      for (int i = tid; i < m; i += SEL_THREADS) {
-        const uint32_t k = order_key(zz[i]);
-        if ((k & pmask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
-      }
+      scan([&](int, float v) {
+        const uint32_t k = order_key(v);
+        const bool in = (k & pmask) == prefix;
+        const int dgt = (k >> shift) & 255;
+        // scores crowd into few leading digits: when the whole wave agrees, one
+        // lane adds for all (same-address LDS atomics would serialise)
+        const uint64_t act = __ballot(in);
+        if (act) {
+          const int first = __shfl(dgt, __ffsll((long long)act) - 1);
+          const uint64_t same = __ballot(in && dgt == first);
+          if (same == act) {
+            if (lane == __ffsll((long long)act) - 1) atomicAdd(&hist[first], __popcll(act));
+          } else if (in) {
+            atomicAdd(&hist[dgt], 1);
+          }
+        }
+      });
       __syncthreads();
       // thread t (< 256) learns how many keys have a digit above t
-      int above = 0;
       if (tid < 256) {
+        int above = 0;
         for (int dgt = tid + 1; dgt < 256; ++dgt) above += hist[dgt];
         const int here = hist[tid];
         if (above < remaining && remaining <= above + here) {
@@ -224,7 +266,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
 
     // ---- error bound of an fp32-accumulated score ---------------------------
     float qn2 = 0.f;
-    for (int i = tid; i < D; i += SEL_THREADS) {
+    for (int i = tid; i < D; i += NT) {
       const float v = to_f32(q[(size_t)bh * D + i]);
       qn2 += v * v;
     }
@@ -234,7 +276,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     __syncthreads();
     if (tid == 0) {
       float s = 0.f;
-      for (int w = 0; w < SEL_WAVES; ++w) s += fred[w];
+      for (int w = 0; w < NW; ++w) s += fred[w];
       float c2 = 0.f;
       for (int i = 0; i < cn2_chunks; ++i) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
       // |fp32 score - exact| <= (chunk chain + reduction tree + slack) * 2^-24 * |q| |C|
@@ -249,16 +291,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
 
     // ---- classify: sure-in above the band, candidates inside it --------------
     int n_hi = 0;
-    for (int i = tid; i < m; i += SEL_THREADS) {
-      const float v = zz[i];
+    scan([&](int i, float v) {
       if (v > hi) {
         ++n_hi;
       } else if (v >= lo) {
         const int slot = atomicAdd(&sh_i[2], 1);
         if (slot < CAND_CAP) cand_id[slot] = i;
       }
-    }
-    n_hi = block_sum_i(n_hi, scan_scratch);
+    });
+    n_hi = block_sum_i<NT>(n_hi, scan_scratch);
     n_cand = sh_i[2];
     need = r_eff - n_hi;
     if (n_cand > CAND_CAP) {
@@ -269,14 +310,14 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
       mode = 2;
       // exact fp64 scores of the candidates
       const T* Cu = C + (size_t)unit * m * D;
-      for (int i = tid; i < n_cand; i += SEL_THREADS) {
+      for (int i = tid; i < n_cand; i += NT) {
         const T* row = Cu + (size_t)cand_id[i] * D;
         double acc = 0.0;
         for (int e = 0; e < D; ++e) acc = fma(to_f64(q[(size_t)bh * D + e]), to_f64(row[e]), acc);
         cand_z[i] = acc;
       }
       __syncthreads();
-      for (int i = tid; i < n_cand; i += SEL_THREADS) {
+      for (int i = tid; i < n_cand; i += NT) {
         const double zi = cand_z[i];
         const int idi = cand_id[i];
         int rank = 0;
@@ -291,64 +332,59 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
   }
 
   // ---- bitmap of the selected clusters ---------------------------------------
-  // Each thread owns whole 32-cluster words, so no atomics are needed except
-  // for the few band candidates added afterwards.
-  int eq_before = 0;
-  if (mode == 3) {
-    // exclusive count of score == tau before each thread's word range
+  if (mode != 3) {
+    // 64 consecutive clusters sit in the 64 lanes of a wave: a ballot is two bitmap words
+    scan([&](int i, float v) {
+      const bool on = mode == 1 ? (v > -INFINITY) : (mode == 2 ? (v > hi) : false);
+      const uint64_t mk = __ballot(on);
+      const int w = (i - lane) >> 5;
+      if (lane == 0 && w < mwords) bits[w] = (uint32_t)mk;
+      if (lane == 32 && w + 1 < mwords) bits[w + 1] = (uint32_t)(mk >> 32);
+    });
+    __syncthreads();
+    if (mode == 2) {
+      for (int i = tid; i < n_cand; i += NT) {
+        const int id = cand_id[i];
+        if (id >= 0) atomicOr(&bits[id >> 5], 1u << (id & 31));
+      }
+      __syncthreads();
+    }
+  } else {
+    // fp32 rule: every score above tau, and of those equal to tau the need_eq
+    // lowest ids.  Each thread owns a contiguous range of words so that "lowest
+    // ids" is an exclusive count over the threads.
+    const int words_per = (mwords + NT - 1) / NT;
+    const int w0 = min(mwords, tid * words_per), w1 = min(mwords, w0 + words_per);
     int cnt = 0;
-    const int words_per = (mwords + SEL_THREADS - 1) / SEL_THREADS;
-    const int w0 = tid * words_per, w1 = min(mwords, w0 + words_per);
     for (int w = w0; w < w1; ++w)
       for (int j = 0; j < 32; ++j) {
         const int i = w * 32 + j;
         if (i < m && zz[i] == tau) ++cnt;
       }
     int tot;
-    eq_before = block_excl_scan(cnt, scan_scratch, tot);
-  }
-  {
-    const int words_per = (mwords + SEL_THREADS - 1) / SEL_THREADS;
-    const int w0 = tid * words_per, w1 = min(mwords, w0 + words_per);
-    int eq_seen = eq_before;
+    int eq_seen = block_excl_scan<NT>(cnt, scan_scratch, tot);
     for (int w = w0; w < w1; ++w) {
       uint32_t word = 0;
-      if (mode != 0) {
-        for (int j = 0; j < 32; ++j) {
-          const int i = w * 32 + j;
-          if (i >= m) break;
-          const float v = zz[i];
-          bool on;
-          if (mode == 1) {
-            on = v > -INFINITY;
-          } else if (mode == 2) {
-            on = v > hi;
-          } else {
-            on = v > tau;
-            if (v == tau) {
-              on = eq_seen < need_eq;
-              ++eq_seen;
-            }
-          }
-          word |= on ? (1u << j) : 0u;
+      for (int j = 0; j < 32; ++j) {
+        const int i = w * 32 + j;
+        if (i >= m) break;
+        const float v = zz[i];
+        bool on = v > tau;
+        if (v == tau) {
+          on = eq_seen < need_eq;
+          ++eq_seen;
         }
+        word |= on ? (1u << j) : 0u;
       }
       bits[w] = word;
-    }
-  }
-  __syncthreads();
-  if (mode == 2) {
-    for (int i = tid; i < n_cand; i += SEL_THREADS) {
-      const int id = cand_id[i];
-      if (id >= 0) atomicOr(&bits[id >> 5], 1u << (id & 31));
     }
     __syncthreads();
   }
 
   // ---- ascending id list and running token counts -----------------------------
   {
-    const int words_per = (mwords + SEL_THREADS - 1) / SEL_THREADS;
-    const int w0 = tid * words_per, w1 = min(mwords, w0 + words_per);
+    const int words_per = (mwords + NT - 1) / NT;
+    const int w0 = min(mwords, tid * words_per), w1 = min(mwords, w0 + words_per);
     int cnt = 0, tok = 0;
     for (int w = w0; w < w1; ++w) {
       uint32_t word = bits[w];
@@ -361,8 +397,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
       }
     }
     int nsel, ntok;
-    int pos = block_excl_scan(cnt, scan_scratch, nsel);
-    int tpos = block_excl_scan(tok, scan_scratch, ntok);
+    int pos = block_excl_scan<NT>(cnt, scan_scratch, nsel);
+    int tpos = block_excl_scan<NT>(tok, scan_scratch, ntok);
     for (int w = w0; w < w1; ++w) {
       uint32_t word = bits[w];
       while (word) {
@@ -379,9 +415,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         ++pos;
       }
     }
-    for (int i = nsel + tid; i < rcap; i += SEL_THREADS) ids[i] = -1;
+    for (int i = nsel + tid; i < rcap; i += NT) ids[i] = -1;
     if (usel)
-      for (int i = nsel + tid; i < usel_stride; i += SEL_THREADS) usel[i] = -1;
+      for (int i = nsel + tid; i < usel_stride; i += NT) usel[i] = -1;
     if (tid == 0) {
       nsel = min(nsel, rcap);
       pref[nsel] = ntok;
@@ -392,6 +428,399 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
       zref_out[bh] = ref;
     }
   }
+}
+
+// ----------------------------------------------------------------------------
+// Selection with all m scores of a head held in registers (m <= NT * VPT).
+// Thread tid keeps clusters k * NT + tid, so the 64 lanes of a wave hold 64
+// consecutive clusters for every k: a ballot is two words of the bitmap, and
+// popcounts of ballots give counts and ranks without atomics.
+//   1. threshold: bisection on the order-preserving integer key for the
+//      r-th largest score (one ballot/popcount sweep and one barrier per bit);
+//   2. guard band around it, fp64 ranking of the few scores inside;
+//   3. ids and running token counts in ascending id order from a small table of
+//      per-(k, wave) counts.
+// ----------------------------------------------------------------------------
+// skeys: LDS for NT * ceil(m / NT) keys when LDSK.  If stage_cap > 0 the first rows
+// and running token counts of the first stage_cap selected clusters are also left
+// in the LDS arrays s_row / s_pref (s_pref gets nsel + 1 entries when nsel <=
+// stage_cap).  Returns the number of selected clusters; *ntok_out their tokens.
+template <typename T, int D, int NT, int VPT, bool LDSK>
+__device__ __forceinline__ int select_core(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, int bh, uint32_t* skeys, int* s_pref, int* s_row,
+    int stage_cap, int* ntok_out) {
+  constexpr int NW = NT / 64;
+  constexpr int TBL = VPT * NW;  // (k, wave) pairs in ascending cluster order
+  static_assert(TBL <= NT && TBL >= 2 * NW, "one table entry per thread; scratch for extrema");
+  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+  const int unit = b * Hkv + hq / G;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* zz = z + (size_t)bh * m;
+  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  int32_t* ids = sel_ids + (size_t)bh * rcap;
+  int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
+  int32_t* srow = sel_row + (size_t)bh * rcap;
+  uint32_t* bits = bitmap + (size_t)bh * mwords;
+  int32_t* usel = user_selected ? user_selected + (size_t)bh * usel_stride : nullptr;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+
+  __shared__ int scan_scratch[NW];
+  __shared__ int tbl_cnt[TBL];
+  __shared__ int cand_id[CAND_CAP];
+  __shared__ double cand_z[CAND_CAP];
+  __shared__ int cnt3[3];
+  __shared__ int sh_i[4];
+  __shared__ float sh_f[2];
+
+  // ---- this thread's scores as order-preserving integer keys -------------------
+  // Error bound inputs first, so that their loads overlap with the key loads:
+  // |fp32 score - exact| <= (chunk chain + reduction tree + slack) * 2^-24 * |q| |C|
+  float guard_in = 0.f;
+  if (wave == NW - 1) {
+    float qn2 = 0.f;
+    for (int i = lane; i < D; i += 64) {
+      const float v = to_f32(q[(size_t)bh * D + i]);
+      qn2 += v * v;
+    }
+    float c2 = 0.f;
+    for (int i = lane; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
+    qn2 = wave_sum_f(qn2);
+    c2 = wave_max(c2);
+    const float steps = (float)(Elem<T>::EPC + 6 + 4);
+    guard_in = 2.0f * steps * 5.9604645e-8f * sqrtf(qn2) * sqrtf(c2);
+  }
+  // With LDSK the keys live in LDS and every sweep is a short rolled loop (the
+  // code of this kernel runs once per workgroup, so unrolled sweeps over many
+  // registers cost more in instruction fetch than they save); without, they
+  // stay in VPT registers per thread (for m too large for LDS).
+  constexpr uint32_t kKeyNegInf = 0x007fffffu;  // order_key(-inf): below every finite score
+  uint32_t kreg[LDSK ? 1 : VPT];
+  const int nk = (m + NT - 1) / NT;  // sweeps; <= VPT
+  if constexpr (LDSK) {
+    for (int k0 = 0; k0 < nk; k0 += 8) {  // eight loads in flight per thread
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = (k0 + u) * NT + tid;
+        v[u] = i < m ? zz[i] : -INFINITY;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (k0 + u < nk) skeys[(k0 + u) * NT + tid] = order_key(v[u] + 0.0f);  // + 0.0f folds -0 into +0
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+      const int i = k * NT + tid;
+      kreg[k] = i < m ? order_key(zz[i] + 0.0f) : kKeyNegInf;
+    }
+  }
+  // fn(k, key of cluster k * NT + tid) for every sweep; wave-uniform trip count
+  auto for_k = [&](auto fn) {
+    if constexpr (LDSK) {
+      for (int k = 0; k < nk; ++k) fn(k, skeys[k * NT + tid]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < VPT; ++k) fn(k, kreg[k]);
+    }
+  };
+
+  // ---- valid count, maximum, |q|^2, max |C|^2 ----------------------------------
+  int nv = 0;
+  uint32_t kmax = kKeyNegInf, kmin = 0xffffffffu;  // over the valid scores
+  for_k([&](int, uint32_t ky) {
+    nv += __popcll(__ballot(ky > kKeyNegInf));
+    kmax = max(kmax, ky);
+    kmin = min(kmin, ky > kKeyNegInf ? ky : 0xffffffffu);
+  });
+  for (int o = 32; o >= 1; o >>= 1) {
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+  }
+  if (lane == 0) {
+    scan_scratch[wave] = nv;
+    tbl_cnt[wave] = (int)kmax;       // tbl_cnt doubles as scratch for the two extrema
+    tbl_cnt[NW + wave] = (int)kmin;
+  }
+  if (tid < 3) cnt3[tid] = 0;
+  if (wave == NW - 1) sh_f[0] = guard_in;
+  __syncthreads();
+  int nvalid = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) nvalid += scan_scratch[w];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    kmax = max(kmax, (uint32_t)tbl_cnt[w]);
+    kmin = min(kmin, (uint32_t)tbl_cnt[NW + w]);
+  }
+  const float zmax = key_to_float(kmax);
+  const float guard = sh_f[0];
+  const int r_eff = min(r, nvalid);
+
+  // mode 0: nothing selected; 1: every valid cluster; 2: threshold + exact band; 3: fp32 rule
+  int mode;
+  uint32_t ktau = 0, klo_band = 0, khi_band = 0;
+  float hi = 0.f;
+  int need_eq = 0, n_cand = 0, need = 0;
+  if (r_eff == 0) {
+    mode = 0;
+  } else if (r_eff == nvalid) {
+    mode = 1;
+  } else {
+    // ---- threshold: largest key t with count(key >= t) >= r_eff ----------------
+    // Stage 1, whole workgroup: halve the VALUE interval [klo, khi) (midpoint of
+    // the two floats) until few scores are left inside; one ballot sweep and one
+    // barrier per step.  Stage 2, one wave: the survivors sit in LDS and the
+    // search finishes on integer keys without any barrier.
+    uint32_t klo = kmin;       // count(>= klo) = nvalid >= r_eff
+    uint32_t khi = kmax + 1;   // count(>= khi) = 0 < r_eff
+    int cnt_lo = nvalid, cnt_hi = 0;
+    int it = 0;
+    while (khi - klo > 1 && cnt_lo - cnt_hi > SURV_CAP) {
+      uint32_t mid = order_key(0.5f * key_to_float(klo) + 0.5f * key_to_float(khi - 1) + 0.0f);
+      if (mid <= klo || mid >= khi) mid = klo + ((khi - klo) >> 1);
+      int c = 0;
+      for_k([&](int, uint32_t ky) { c += __popcll(__ballot(ky >= mid)); });
+      const int slot = it % 3;
+      if (lane == 0) atomicAdd(&cnt3[slot], c);
+      if (tid == 0) cnt3[(it + 1) % 3] = 0;
+      __syncthreads();
+      const int total = cnt3[slot];
+      if (total >= r_eff) {
+        klo = mid;
+        cnt_lo = total;
+      } else {
+        khi = mid;
+        cnt_hi = total;
+      }
+      ++it;
+    }
+      if (khi - klo > 1) {
+      // survivors: klo <= key < khi, at most SURV_CAP of them
+      __syncthreads();
+      if (tid == 0) sh_i[2] = 0;
+      __syncthreads();
+      for_k([&](int, uint32_t ky) {
+        if (ky >= klo && ky < khi) {
+          const int slot = atomicAdd(&sh_i[2], 1);
+          if (slot < SURV_CAP) cand_id[slot] = (int)ky;  // cnt_lo - cnt_hi <= SURV_CAP entries
+        }
+      });
+      __syncthreads();
+      if (wave == 0) {
+        constexpr int PER = SURV_CAP / 64;
+        const int ns = min(sh_i[2], SURV_CAP);
+        uint32_t sk[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) sk[j] = lane + 64 * j < ns ? (uint32_t)cand_id[lane + 64 * j] : 0u;
+        uint32_t a = klo, e = khi;  // invariant: cnt_hi + count(sk >= a) >= r_eff > cnt_hi + count(sk >= e)
+        int ce = 0;
+        while (e - a > 1) {
+          const uint32_t mid = a + ((e - a) >> 1);
+          int c = 0;
+#pragma unroll
+          for (int j = 0; j < PER; ++j) c += __popcll(__ballot(sk[j] >= mid));
+          if (cnt_hi + c >= r_eff) {
+            a = mid;
+          } else {
+            e = mid;
+            ce = c;
+          }
+        }
+        if (lane == 0) {
+          sh_i[0] = (int)a;
+          sh_i[1] = cnt_hi + ce;
+        }
+      }
+      __syncthreads();
+      klo = (uint32_t)sh_i[0];
+      cnt_hi = sh_i[1];
+    }
+      ktau = klo;
+    const float tau = key_to_float(ktau);
+    need_eq = r_eff - cnt_hi;  // count(key > tau) = count(key >= khi) = cnt_hi
+    hi = tau + guard;
+    klo_band = order_key((tau - guard) + 0.0f);
+    khi_band = order_key(hi + 0.0f);
+    __syncthreads();
+    if (tid == 0) sh_i[2] = 0;
+    __syncthreads();
+
+    // ---- classify: sure-in above the band, candidates inside it --------------
+    int n_hi = 0;
+    for_k([&](int k, uint32_t ky) {
+      n_hi += __popcll(__ballot(ky > khi_band));
+      if (ky >= klo_band && ky <= khi_band) {
+        const int slot = atomicAdd(&sh_i[2], 1);
+        if (slot < CAND_CAP) cand_id[slot] = k * NT + tid;
+      }
+    });
+    if (lane == 0) scan_scratch[wave] = n_hi;
+    __syncthreads();
+    n_hi = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) n_hi += scan_scratch[w];
+    n_cand = sh_i[2];
+    need = r_eff - n_hi;
+    if (n_cand > CAND_CAP) {
+      mode = 3;  // too many near-equal scores: keep the fp32 ranking
+    } else if (n_cand == need) {
+      mode = 2;  // the whole band is taken; no ranking needed
+    } else {
+      mode = 2;
+      const T* Cu = C + (size_t)unit * m * D;
+      for (int i = tid; i < n_cand; i += NT) {
+        const T* rowp = Cu + (size_t)cand_id[i] * D;
+        double acc = 0.0;
+        for (int e = 0; e < D; ++e) acc = fma(to_f64(q[(size_t)bh * D + e]), to_f64(rowp[e]), acc);
+        cand_z[i] = acc;
+      }
+      __syncthreads();
+      constexpr int NR = (CAND_CAP + NT - 1) / NT;
+      bool drop[NR];
+#pragma unroll
+      for (int rr = 0; rr < NR; ++rr) {
+        const int i = tid + rr * NT;
+        drop[rr] = false;
+        if (i < n_cand) {
+          const double zi = cand_z[i];
+          const int idi = cand_id[i];
+          int rank = 0;
+          for (int j = 0; j < n_cand; ++j) {
+            const double zj = cand_z[j];
+            rank += (zj > zi || (zj == zi && cand_id[j] < idi)) ? 1 : 0;
+          }
+          drop[rr] = rank >= need;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int rr = 0; rr < NR; ++rr)
+        if (drop[rr]) cand_id[tid + rr * NT] = -1 - cand_id[tid + rr * NT];  // dropped
+      __syncthreads();
+    }
+  }
+
+  // ---- which of this thread's clusters are selected ------------------------------
+  // bit k of `sel`; mode 3 needs the rank among equal scores in id order.
+  uint64_t sel = 0;
+  if (mode == 1) {
+    for_k([&](int k, uint32_t ky) { sel |= (uint64_t)(ky > kKeyNegInf ? 1 : 0) << k; });
+  } else if (mode == 2) {
+    for_k([&](int k, uint32_t ky) {
+      bool on = ky > khi_band;
+      if (!on && ky >= klo_band) {  // in the band: look the decision up
+        const int me = k * NT + tid;
+        for (int j = 0; j < n_cand; ++j) on |= cand_id[j] == me;
+      }
+      sel |= (uint64_t)(on ? 1 : 0) << k;
+    });
+  } else if (mode == 3) {
+    if (tid < TBL) tbl_cnt[tid] = 0;  // sweeps beyond nk stay empty
+    __syncthreads();
+    for_k([&](int k, uint32_t ky) {
+      const uint64_t eq = __ballot(ky == ktau);
+      if (lane == 0) tbl_cnt[k * NW + wave] = __popcll(eq);
+    });
+    __syncthreads();
+    int tot;
+    const int base = block_excl_scan<NT>(tid < TBL ? tbl_cnt[tid] : 0, scan_scratch, tot);
+    __syncthreads();
+    if (tid < TBL) tbl_cnt[tid] = base;
+    __syncthreads();
+    for_k([&](int k, uint32_t ky) {
+      const uint64_t eq = __ballot(ky == ktau);
+      const int rank = tbl_cnt[k * NW + wave] + __popcll(eq & lt_mask);
+      const bool on = ky > ktau || (ky == ktau && rank < need_eq);
+      sel |= (uint64_t)(on ? 1 : 0) << k;
+    });
+    __syncthreads();
+  }
+
+  // ---- bitmap and ascending id list ------------------------------------------------
+  if (tid < TBL) tbl_cnt[tid] = 0;  // sweeps beyond nk stay empty
+  __syncthreads();
+  for_k([&](int k, uint32_t) {
+    const uint64_t mk = __ballot((sel >> k) & 1ull);
+    const int w = (k * NT + wave * 64) >> 5;
+    if (lane == 0) {
+      if (w < mwords) bits[w] = (uint32_t)mk;
+      tbl_cnt[k * NW + wave] = __popcll(mk);
+    }
+    if (lane == 32 && w + 1 < mwords) bits[w + 1] = (uint32_t)(mk >> 32);
+  });
+  __syncthreads();
+  int nsel;
+  const int cbase = block_excl_scan<NT>(tid < TBL ? tbl_cnt[tid] : 0, scan_scratch, nsel);
+  __syncthreads();
+  if (tid < TBL) tbl_cnt[tid] = cbase;
+  __syncthreads();
+  for_k([&](int k, uint32_t) {
+    const bool on = (sel >> k) & 1ull;
+    const uint64_t mk = __ballot(on);
+    const int pos = tbl_cnt[k * NW + wave] + __popcll(mk & lt_mask);
+    if (on && pos < rcap) {  // pos < rcap always holds for a consistent selection
+      ids[pos] = k * NT + tid;
+      if (usel) usel[pos] = k * NT + tid;
+    }
+  });
+  nsel = min(nsel, rcap);
+  __syncthreads();  // ids[] written by other waves are read below
+
+  // ---- first row and running token count of every selected cluster -------------------
+  int carry = 0;
+  for (int base = 0; base < nsel; base += NT) {
+    const int t = base + tid;
+    int r0 = 0, size = 0;
+    if (t < nsel) {
+      const int c = ids[t];
+      r0 = off[c];
+      size = off[c + 1] - r0;
+      srow[t] = r0;
+      if (t < stage_cap) s_row[t] = r0;
+    }
+    int tot;
+    const int ex = block_excl_scan<NT>(size, scan_scratch, tot);
+    if (t < nsel) {
+      pref[t] = carry + ex;
+      if (t < stage_cap) s_pref[t] = carry + ex;
+    }
+    carry += tot;
+  }
+  for (int i = nsel + tid; i < rcap; i += NT) ids[i] = -1;
+  if (usel)
+    for (int i = nsel + tid; i < usel_stride; i += NT) usel[i] = -1;
+  if (tid == 0) {
+    pref[nsel] = carry;
+    if (nsel < stage_cap) s_pref[nsel] = carry;
+    nsel_out[bh] = nsel;
+    // reference score of the estimation zone: every estimated cluster scores <= it
+    float ref = 0.f;
+    if (nvalid > 0) ref = (mode == 2 || mode == 3) ? fminf(hi, zmax) : zmax;
+    zref_out[bh] = ref;
+  }
+  *ntok_out = carry;
+  return nsel;
+}
+
+template <typename T, int D, int NT, int VPT, bool LDSK>
+__global__ __launch_bounds__(NT) void select_cached_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected) {
+  extern __shared__ uint32_t dyn_keys[];  // NT * ceil(m / NT) keys when LDSK
+  int ntok;
+  select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                                   usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
+                                   user_selected, blockIdx.x, dyn_keys, nullptr, nullptr, 0, &ntok);
 }
 
 // ============================================================================
@@ -469,7 +898,7 @@ struct AttnState {
 // Merge the per-group states of a 256-thread workgroup and write one partial
 // result (max, sum, acc[D]) per head.  part_base points at head 0's slot;
 // consecutive heads are head_stride floats apart.
-template <typename T, int D, int NG>
+template <typename T, int D, int NG, int NWV = 4>
 __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, float* smem,
                                                        float* part_base, size_t head_stride) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC;
@@ -489,7 +918,7 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
       st.mx[g] = mn;
     }
   }
-  // across the 4 waves through LDS: smem[wave][g][D + 2]
+  // across the NWV waves through LDS: smem[wave][g][D + 2]
   constexpr int STR = D + 2;
   if (lane < LPR) {
 #pragma unroll
@@ -504,11 +933,11 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < NG * STR; idx += 256) {
+  for (int idx = threadIdx.x; idx < NG * STR; idx += 64 * NWV) {
     const int g = idx / STR, e = idx - g * STR;
-    float m4[4], mn = kNegBig;
+    float m4[NWV], mn = kNegBig;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NWV; ++w) {
       m4[w] = smem[(size_t)(w * NG + g) * STR];
       mn = fmaxf(mn, m4[w]);
     }
@@ -518,7 +947,7 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
     } else {
       v = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) v += smem[(size_t)(w * NG + g) * STR + e] * exp2f(m4[w] - mn);
+      for (int w = 0; w < NWV; ++w) v += smem[(size_t)(w * NG + g) * STR + e] * exp2f(m4[w] - mn);
     }
     part_base[(size_t)g * head_stride + e] = v;
   }
@@ -604,6 +1033,89 @@ __global__ __launch_bounds__(256) void gather_kernel(
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
 }
 
+// ----------------------------------------------------------------------------
+// Selection and retrieval zone of one query head in ONE workgroup: with many
+// heads in flight (>= 2 per CU) the latency-bound selection of one workgroup
+// overlaps with the streaming of its neighbours, the selected ranges never
+// leave LDS, and the head produces a single partial result.
+// ----------------------------------------------------------------------------
+constexpr int FUSED_STAGE = 2048;  // selected clusters whose ranges stay in LDS
+
+template <typename T, int D, int NT, int VPT, bool LDSK>
+__global__ __launch_bounds__(NT) void select_gather_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
+    int N_idx, int slots, float scale_log2, float* __restrict__ part) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
+  constexpr int GROUPS = NWV * RPW, U = 4, TILE = NT;
+  extern __shared__ uint32_t dyn_keys[];
+  __shared__ int s_pref[FUSED_STAGE + 1];
+  __shared__ int s_row[FUSED_STAGE];
+  __shared__ int rowidx[TILE];
+  __shared__ float smem[NWV * (D + 2)];
+  __shared__ int sh_n[2];
+
+  const int bh = xcd_logical_block(blockIdx.x, gridDim.x);
+  int ntok;
+  const int nsel = select_core<T, D, NT, VPT, LDSK>(
+      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
+      sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, bh, dyn_keys, s_pref, s_row,
+      FUSED_STAGE, &ntok);
+  if (threadIdx.x == 0) {
+    sh_n[0] = nsel;
+    sh_n[1] = ntok;
+  }
+  __syncthreads();  // publishes s_pref / s_row (and the global copies) to every wave
+  const int nsel_all = sh_n[0], total = sh_n[1];
+
+  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+  const int unit = b * Hkv + hq / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  const bool staged = nsel_all <= FUSED_STAGE;
+  const int32_t* pref = staged ? s_pref : sel_pref + (size_t)bh * (rcap + 1);
+  const int32_t* srow = staged ? s_row : sel_row + (size_t)bh * rcap;
+
+  AttnState<T, D, 1> st;
+  st.init(q + (size_t)bh * D, sub, scale_log2);
+  const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
+  const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
+  for (int base = 0; base < total; base += TILE) {
+    const int n = min(TILE, total - base);
+    __syncthreads();
+    if ((int)threadIdx.x < n) {
+      const int t = base + threadIdx.x;
+      int a = 0, e = nsel_all;  // largest a with pref[a] <= t
+      while (e - a > 1) {
+        const int mid = (a + e) >> 1;
+        if (pref[mid] <= t) a = mid; else e = mid;
+      }
+      rowidx[threadIdx.x] = srow[a] + (t - pref[a]);
+    }
+    __syncthreads();
+    for (int i = grp; i < n; i += GROUPS * U) {
+      uint4 kraw[U], vraw[U];
+      bool valid[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int ii = i + u * GROUPS;
+        valid[u] = ii < n;
+        const int row = rowidx[valid[u] ? ii : i];
+        kraw[u] = load16(Ku + (size_t)row * D);
+        vraw[u] = load16(Vu + (size_t)row * D);
+      }
+      st.template rows<U, LPR>(kraw, vraw, valid);
+    }
+  }
+  __syncthreads();
+  merge_groups_and_store<T, D, 1, NWV>(st, smem, part + (size_t)bh * slots * (D + 2), 0);
+}
+
+
 // ============================================================================
 // 3b. Steady zone: sink + local rows of one unit, shared by its G query heads.
 // ============================================================================
@@ -652,61 +1164,90 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
 //     w_c = exp(q.C_c / sqrt(d)) taken relative to a fixed reference so that
 //     partial sums of different workgroups add up directly.
 // ============================================================================
+constexpr int EST_ROWS = 512;  // clusters per workgroup
+
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void est_kernel(const T* __restrict__ vsum,
                                                   const int32_t* __restrict__ sizes,
                                                   const float* __restrict__ z,
                                                   const uint32_t* __restrict__ bitmap,
                                                   const float* __restrict__ zref, int Hkv, int m,
-                                                  int mwords, int chunks, int rows_per_chunk,
-                                                  int slots, int slot0, float scale_log2,
-                                                  float* __restrict__ part) {
+                                                  int mwords, int chunks, int slots, int slot0,
+                                                  float scale_log2, float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
+  constexpr int STR = D + 2;
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
   const int unit = wg / chunks, chunk = wg - unit * chunks;
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
-  __shared__ float smem[4 * G * (D + 2)];
+  __shared__ __attribute__((aligned(16))) float wts[EST_ROWS * G];  // [cluster][head]
+  __shared__ float smem[4 * G * STR];
+  __shared__ float lred[4][G];
 
   const int bh0 = b * Hq + h * G;
-  float ref2[G], l[G], acc[G][EPC];
+  const int c0 = chunk * EST_ROWS, nrows = min(EST_ROWS, m - c0);
+  const int32_t* su = sizes + (size_t)unit * m + c0;
+
+  // Phase 1: weights of this range for the G heads (coalesced over clusters).
+  float lsum[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    ref2[g] = zref[bh0 + g] * scale_log2;
-    l[g] = 0.f;
+    const size_t bh = bh0 + g;
+    const float ref2 = zref[bh] * scale_log2;
+    const float* zz = z + bh * m + c0;
+    const uint32_t* bw = bitmap + bh * mwords;
+    float ls = 0.f;
+    for (int i = threadIdx.x; i < nrows; i += 256) {
+      const int c = c0 + i, sz = su[i];
+      const bool use = sz > 0 && !((bw[c >> 5] >> (c & 31)) & 1u);
+      const float w = use ? exp2f(fmaf(zz[i], scale_log2, -ref2)) : 0.f;
+      wts[i * G + g] = w;
+      ls = fmaf((float)sz, w, ls);
+    }
+    lsum[g] = wave_sum_f(ls);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) lred[wave][g] = lsum[g];
+  }
+  __syncthreads();
+
+  // Phase 2: stream the value sums once; all G heads consume each row.
+  float acc[G][EPC];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
-  }
-  const T* Vu = vsum + (size_t)unit * m * D + sub * EPC;
-  const int32_t* su = sizes + (size_t)unit * m;
-  const int c0 = chunk * rows_per_chunk, c1 = min(m, c0 + rows_per_chunk);
-
-  for (int c = c0 + grp; c < c1; c += GROUPS * U) {
+  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+  for (int c = grp; c < nrows; c += GROUPS * U) {
     uint4 raw[U];
-    int sz[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int cc = min(c + u * GROUPS, c1 - 1);
-      raw[u] = load16(Vu + (size_t)cc * D);
-      sz[u] = (c + u * GROUPS < c1) ? su[cc] : 0;
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int cc = min(c + u * GROUPS, c1 - 1);
-      float vf[EPC];
+      const int cc = c + u * GROUPS;
+      float vf[EPC], w[G];
       unpack<T>(raw[u], vf);
+      if (cc < nrows) {
+        if constexpr (G % 4 == 0) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const size_t bh = bh0 + g;
-        const uint32_t word = bitmap[bh * mwords + (cc >> 5)];
-        const bool use = sz[u] > 0 && !((word >> (cc & 31)) & 1u);
-        const float zc = z[bh * m + cc];
-        const float w = use ? exp2f(fmaf(zc, scale_log2, -ref2[g])) : 0.f;
-        l[g] = fmaf((float)sz[u], w, l[g]);
+          for (int g4 = 0; g4 < G; g4 += 4) {
+            const float4 t = *reinterpret_cast<const float4*>(&wts[cc * G + g4]);
+            w[g4] = t.x; w[g4 + 1] = t.y; w[g4 + 2] = t.z; w[g4 + 3] = t.w;
+          }
+        } else {
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(w, vf[e], acc[g][e]);
+          for (int g = 0; g < G; ++g) w[g] = wts[cc * G + g];
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < G; ++g) w[g] = 0.f;
       }
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(w[g], vf[e], acc[g][e]);
     }
   }
   // all groups share the reference: plain sums
@@ -714,19 +1255,16 @@ __global__ __launch_bounds__(256) void est_kernel(const T* __restrict__ vsum,
   for (int off = LPR; off < 64; off <<= 1) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      l[g] += __shfl_xor(l[g], off);
 #pragma unroll
       for (int e = 0; e < EPC; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
     }
   }
-  constexpr int STR = D + 2;
   if (lane < LPR) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float* dst = smem + (size_t)(wave * G + g) * STR;
 #pragma unroll
       for (int e = 0; e < EPC; ++e) dst[2 + sub * EPC + e] = acc[g][e];
-      if (sub == 0) dst[1] = l[g];
     }
   }
   __syncthreads();
@@ -735,6 +1273,8 @@ __global__ __launch_bounds__(256) void est_kernel(const T* __restrict__ vsum,
     float v;
     if (e == 0) {
       v = zref[bh0 + g] * scale_log2;
+    } else if (e == 1) {
+      v = lred[0][g] + lred[1][g] + lred[2][g] + lred[3][g];
     } else {
       v = 0.f;
 #pragma unroll
@@ -750,21 +1290,46 @@ __global__ __launch_bounds__(256) void est_kernel(const T* __restrict__ vsum,
 template <int D>
 __global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part, int slots,
                                                   float* __restrict__ out, float* __restrict__ lse) {
-  constexpr int STR = D + 2;
+  constexpr int STR = D + 2, TILE = 256;
   const int bh = blockIdx.x, e = threadIdx.x;
   const float* p = part + (size_t)bh * slots * STR;
-  float M = kNegBig;
-  for (int s = 0; s < slots; ++s)
-    if (p[(size_t)s * STR + 1] > 0.f) M = fmaxf(M, p[(size_t)s * STR]);
-  float Z = 0.f, A = 0.f;
-  for (int s = 0; s < slots; ++s) {
-    const float ls = p[(size_t)s * STR + 1];
-    if (ls > 0.f) {
-      const float w = exp2f(p[(size_t)s * STR] - M);
-      Z = fmaf(ls, w, Z);
-      A = fmaf(p[(size_t)s * STR + 2 + e], w, A);
+  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
+  __shared__ float red[2];
+  // global maximum over the non-empty slots (independent loads, all in flight)
+  float mloc = kNegBig;
+  for (int s = e; s < slots; s += D)
+    if (p[(size_t)s * STR + 1] > 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  mloc = wave_max(mloc);
+  if ((e & 63) == 0) red[e >> 6] = mloc;
+  __syncthreads();
+  const float M = D > 64 ? fmaxf(red[0], red[1]) : red[0];
+  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
+  for (int base = 0; base < slots; base += TILE) {
+    const int n = min(TILE, slots - base);
+    __syncthreads();
+    for (int s = e; s < n; s += D) {
+      const float ls = p[(size_t)(base + s) * STR + 1];
+      const float w = ls > 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+      wgt[s] = w;
+      zloc = fmaf(ls, w, zloc);
     }
+    __syncthreads();
+    const float* pe = p + (size_t)base * STR + 2 + e;
+    int s = 0;
+    for (; s + 4 <= n; s += 4) {
+      A0 = fmaf(pe[(size_t)(s + 0) * STR], wgt[s + 0], A0);
+      A1 = fmaf(pe[(size_t)(s + 1) * STR], wgt[s + 1], A1);
+      A2 = fmaf(pe[(size_t)(s + 2) * STR], wgt[s + 2], A2);
+      A3 = fmaf(pe[(size_t)(s + 3) * STR], wgt[s + 3], A3);
+    }
+    for (; s < n; ++s) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
   }
+  zloc = wave_sum_f(zloc);
+  __syncthreads();
+  if ((e & 63) == 0) red[e >> 6] = zloc;
+  __syncthreads();
+  const float Z = D > 64 ? red[0] + red[1] : red[0];
+  const float A = (A0 + A1) + (A2 + A3);
   out[(size_t)bh * D + e] = Z > 0.f ? A / Z : 0.f;
   if (e == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
 }
@@ -780,10 +1345,10 @@ __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   DecodeGeom g{};
   const int m = ix.m, units = ix.B * ix.Hkv, heads = ix.B * Hq, D = ix.d;
-  g.score_rows = 512;
+  g.score_rows = 256;
   g.score_chunks = m > 0 ? (m + g.score_rows - 1) / g.score_rows : 0;
-  g.est_rows = 512;
-  g.est_chunks = g.score_chunks;
+  g.est_rows = EST_ROWS;
+  g.est_chunks = m > 0 ? (m + EST_ROWS - 1) / EST_ROWS : 0;
   g.steady_rows = 256;
   g.steady_chunks = ix.p > 0 ? (ix.p + g.steady_rows - 1) / g.steady_rows : 0;
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
@@ -793,6 +1358,10 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   if (gc < 1) gc = 1;
   if (gc > 256) gc = 256;
   g.gather_chunks = (m > 0 && r > 0) ? gc : 0;
+  // With at least ~1.5 query heads per CU, selection and retrieval of a head run
+  // fused in one workgroup and leave one partial result.
+  g.fused = (m > 0 && r > 0 && heads >= 384 && m <= 512 * 32) ? 1 : 0;
+  if (g.fused) g.gather_chunks = 1;
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks;
   if (g.slots < 1) g.slots = 1;
   g.mwords = (m + 31) / 32;
@@ -833,17 +1402,32 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     WAVE_LAUNCH("score", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
                 g.score_rows);
-    WAVE_LAUNCH("select", (select_kernel<T, D>), heads, SEL_THREADS, 0, st, q,
-                static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv,
-                m, r, g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected);
-    if (g.gather_chunks > 0)
-      WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
-                  static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow,
-                  nsel, Hq, ix.Hkv, ix.N_idx, g.rcap, g.gather_chunks, g.slots, scale_log2, part);
+#define WAVE_SELECT_ARGS                                                                           \
+  q, static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, r,    \
+      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected
+    const size_t key_lds = sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512);
+    if (g.fused) {
+      WAVE_LAUNCH("select_gather", (select_gather_kernel<T, D, 512, 32, true>), heads, 512, key_lds,
+                  st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
+                  static_cast<const T*>(ix.v_perm), ix.N_idx, g.slots, scale_log2, part);
+    } else {
+      if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
+        WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
+                    WAVE_SELECT_ARGS);
+      else if (m <= 1024 * 64)  // keys in registers
+        WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024, 0, st,
+                    WAVE_SELECT_ARGS);
+      else
+        WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SELECT_ARGS);
+      if (g.gather_chunks > 0)
+        WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
+                    static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow,
+                    nsel, Hq, ix.Hkv, ix.N_idx, g.rcap, g.gather_chunks, g.slots, scale_log2, part);
+    }
+#undef WAVE_SELECT_ARGS
     WAVE_LAUNCH("estimate", (est_kernel<T, D, G>), units * g.est_chunks, 256, 0, st,
                 static_cast<const T*>(ix.vsum), ix.sizes, z, bitmap, zref, ix.Hkv, m, g.mwords,
-                g.est_chunks, g.est_rows, g.slots, g.gather_chunks + g.steady_chunks, scale_log2,
-                part);
+                g.est_chunks, g.slots, g.gather_chunks + g.steady_chunks, scale_log2, part);
   }
   if (m == 0 && selected && topk > 0) {
     const size_t n = (size_t)heads * topk;  // no clusters exist: nothing is selected

@@ -35,6 +35,10 @@ CASES = {
     "bf16_d64": _small("llama8b_32k", name="bf16_d64", d=64, N=2500, Hq=4, Hkv=2, segment_len=1024,
                        clusters_per_segment=100, n_local=50, n_components=128, iters=3,
                        retrieve_frac=0.1),
+    # 384 query heads: selection and retrieval run fused in one workgroup per head
+    "bf16_many_heads": _small("llama8b_32k", name="bf16_many_heads", B=48, N=1300, Hq=8, Hkv=2,
+                              segment_len=512, clusters_per_segment=32, n_local=40, n_components=64,
+                              iters=3, retrieve_frac=0.1),
     # d = 128 in f32 (32 lanes per row)
     "f32_d128": _small("tiny_f32", name="f32_d128", d=128, N=1500, Hq=2, Hkv=1, segment_len=512,
                        clusters_per_segment=32, n_local=30, iters=3, retrieve_abs=9),
@@ -206,3 +210,57 @@ def test_errors_surface_as_status_codes():
         wb.wave_attention_decode(q.cuda(), ix, 4, ws=wb.workspace(256))
     assert e.value.status == 4
     torch.cuda.synchronize()
+
+
+def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
+    """A random index that no k-means produced: sizes 0..3, centroids and value
+    sums consistent with the member rows.  Decode only reads the arrays."""
+    g = np.random.default_rng(seed)
+    sizes = g.integers(0, 4, m)
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(offsets[-1])
+    Kp = wo.quant(g.standard_normal((n, d)), dtype)
+    Vp = wo.quant(g.standard_normal((n, d)), dtype)
+    C = np.zeros((m, d))
+    VS = np.zeros((m, d))
+    for c in np.nonzero(sizes)[0]:
+        C[c] = Kp[offsets[c]:offsets[c + 1]].mean(0)
+        VS[c] = Vp[offsets[c]:offsets[c + 1]].sum(0)
+    if dup_scores:   # many clusters with the very same centroid: exact score ties
+        C[::7] = C[7]
+    Ks = wo.quant(g.standard_normal((n_steady, d)), dtype)
+    Vs = wo.quant(g.standard_normal((n_steady, d)), dtype)
+    return dict(centroids=wo.quant(C, dtype), vsum=wo.quant(VS, dtype), sizes=sizes, offsets=offsets,
+                perm=np.arange(n), k_perm=Kp, v_perm=Vp, k_steady=Ks, v_steady=Vs), n
+
+
+@pytest.mark.parametrize("m,dup", [(3000, True), (20000, False), (40000, True), (70000, False)])
+def test_decode_many_clusters_hand_index(m, dup):
+    """Every size class of the selection kernel (scores in registers with 512 or
+    1024 threads, and the streaming fallback), with and without exact score ties."""
+    d, dtype, p, Hq, Hkv = 128, "bf16", 8, 2, 1
+    arrs, n = _hand_index(m, d, dtype, p, seed=m, dup_scores=dup)
+    # Dimensions whose plan has exactly m clusters: segments of 4 tokens with one
+    # cluster each.  The hand index then fills sizes/offsets as it likes (0..3 rows
+    # per cluster); rows beyond its n are padding that no offset points at.
+    L = 4
+    c, sizes_b, bws, dws = wb.wave_index_plan(torch.bfloat16, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1)
+    assert c.m == m
+    # rows of k_perm/v_perm are allocated for N_idx = 4 m >= n; pad the hand rows
+    pad = c.N_idx - n
+    arrs["k_perm"] = np.concatenate([arrs["k_perm"], np.zeros((pad, d))])
+    arrs["v_perm"] = np.concatenate([arrs["v_perm"], np.zeros((pad, d))])
+    arrs["perm"] = np.arange(c.N_idx)
+    tens = {k: torch.from_numpy(np.asarray(v)[None, None].astype(
+        np.int32 if k in ("sizes", "offsets", "perm") else np.float32)) for k, v in arrs.items()}
+    ix = wb.index_from_arrays(torch.bfloat16, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1, tens)
+    plan = wo.make_plan(4 * m + p, 4, p - 4, L, 1)
+    ref = wo.UnitIndex(plan, dtype, arrs["centroids"], arrs["vsum"], arrs["sizes"], arrs["offsets"],
+                       arrs["perm"], arrs["k_perm"], arrs["v_perm"], arrs["k_steady"],
+                       arrs["v_steady"], np.zeros(0, dtype=np.int64))
+    g = np.random.default_rng(5)
+    q = torch.from_numpy(wo.quant(g.standard_normal((1, Hq, d)) * 2.0, dtype).astype(np.float32)
+                         ).to(torch.bfloat16)
+    wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d)
+    for r in (0, 5, 300, m):
+        _decode_and_check(wl, ix, {(0, 0): ref}, q, r, f"hand m={m}")
