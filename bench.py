@@ -161,14 +161,14 @@ def main() -> int:
 
     units = wl.B * wl.Hkv
     row = wl.d * es
-    bytes_k = {
-        "score": units * ix.m * row + units * ix.m * 4,
-        "estimate": units * ix.m * row + units * ix.m * 4,
-        "steady": 2 * units * ix.p * row,
-        "gather": 2 * mean_tokens * row,
-        "select": 0, "merge": 0,
+    meta = 2 * (units * ix.m * row) + units * ix.m * 4      # C and VS once per KV head, sizes
+    steady_b = 2 * units * ix.p * row
+    gather_b = 2 * mean_tokens * row
+    bytes_k = {                      # algorithmic bytes by kernel (either launch split)
+        "meta_index": meta, "steady": steady_b, "gather": gather_b, "select_gather": gather_b,
+        "select_gather_steady": gather_b + steady_b, "select": 0, "merge": 0,
     }
-    step_bytes = sum(bytes_k.values())
+    step_bytes = meta + steady_b + gather_b
     kern = {k: v[0] / max(v[1], 1) for k, v in dec_prof.items()}      # ms per launch
     dominant = max(kern, key=kern.get)
     dom_gbs = bytes_k.get(dominant, 0) / (kern[dominant] * 1e-3) / 1e9

@@ -17,74 +17,199 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 
 // ============================================================================
-// 1. Centroid scoring: z[b, hq, c] = q[b, hq] . C[b, hkv, c], empty clusters -inf.
-//    One workgroup streams a contiguous range of one unit's centroids for all G
-//    query heads of that KV head.  It also reports the largest squared centroid
-//    norm of its range (the selection step turns it into an error bound).
+// 1. Meta-index pass: one workgroup takes DENSE_ROWS clusters of one unit for
+//    all G query heads of that KV head and makes a single trip over their
+//    centroids and value sums.
+//      A  z[b, hq, c] = q[b, hq] . C[b, hkv, c]  (empty clusters -inf), written
+//         for the selection step and kept in LDS; it also reports a bound on the
+//         largest squared centroid norm of its range (selection's error bound);
+//      B  estimation weights of ALL its clusters, w_c = exp(z_c / sqrt(d)) taken
+//         relative to the largest score of the range, and sum_c s_c w_c;
+//      C  sum_c w_c VS_c.
+//    The result is one partial (max, sum, acc[d]) per head and range.  Clusters
+//    that a head later selects are taken out again by the selection kernel, which
+//    writes the same terms with a minus sign (the terms are bounded by the final
+//    normaliser, so the cancellation costs about one fp32 ulp of the output).
 // ============================================================================
+constexpr int DENSE_ROWS = 256;
+
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, const T* __restrict__ C,
+__global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, const T* __restrict__ C,
+                                                    const T* __restrict__ vsum,
                                                     const int32_t* __restrict__ sizes,
                                                     float* __restrict__ z, float* __restrict__ cn2part,
-                                                    int Hkv, int m, int chunks, int rows_per_chunk) {
+                                                    int Hkv, int m, int chunks, int slots, int slot0,
+                                                    float scale_log2, float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
+  constexpr int STR = D + 2;
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
   const int unit = wg / chunks, chunk = wg - unit * chunks;
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  const int bh0 = b * Hq + h * G;
+  __shared__ __attribute__((aligned(16))) float zw[DENSE_ROWS * G];  // [cluster][head]: z, then w
+  __shared__ float smem[4 * G * STR];
+  __shared__ float red[4][2 * G + 1];
+  __shared__ float zref_s[G];
 
-  float qf[G][EPC];
+  const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
+  const int32_t* su = sizes + (size_t)unit * m + c0;
+
+  // ---- A: scores ---------------------------------------------------------------
+  {
+    float qf[G][EPC];
+#pragma unroll
+    for (int g = 0; g < G; ++g) unpack<T>(load16(q + ((size_t)(bh0 + g) * D + sub * EPC)), qf[g]);
+    const T* Cu = C + ((size_t)unit * m + c0) * D + sub * EPC;
+    float cn2 = 0.f;  // per-lane maximum of its chunk's squared sum; summed over lanes below
+    for (int c = grp; c < nrows; c += GROUPS * U) {
+      uint4 raw[U];
+      int sz[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int cc = min(c + u * GROUPS, nrows - 1);
+        raw[u] = load16(Cu + (size_t)cc * D);
+        sz[u] = su[cc];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int cc = c + u * GROUPS;
+        float cf[EPC];
+        unpack<T>(raw[u], cf);
+        float n2 = 0.f, sc[G];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) n2 = fmaf(cf[e], cf[e], n2);
+        cn2 = fmaxf(cn2, n2);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float a = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) a = fmaf(qf[g][e], cf[e], a);
+          sc[g] = group_sum<LPR>(a);
+        }
+        float mine = sc[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) mine = (sub == g) ? sc[g] : mine;
+        if (cc < nrows && sub < G) {
+          const float v = sz[u] > 0 ? mine : -INFINITY;
+          z[(size_t)(bh0 + sub) * m + c0 + cc] = v;
+          zw[cc * G + sub] = v;
+        }
+      }
+    }
+    // sum over the LPR lanes of a row of per-lane maxima >= maximum over rows of the row sums
+    cn2 = group_sum<LPR>(cn2);
+    cn2 = wave_max(cn2);
+    if (lane == 0) red[wave][2 * G] = cn2;
+  }
+  __syncthreads();
+
+  // ---- B: weights relative to the range maximum -----------------------------------
+  float zmax[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mx = -INFINITY;
+    for (int i = threadIdx.x; i < nrows; i += 256) mx = fmaxf(mx, zw[i * G + g]);
+    zmax[g] = wave_max(mx);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) red[wave][g] = zmax[g];
+  }
+  __syncthreads();
+  float lsum[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const float mx = fmaxf(fmaxf(red[0][g], red[1][g]), fmaxf(red[2][g], red[3][g]));
+    zmax[g] = mx > -INFINITY ? mx : 0.f;   // a range of empty clusters only: every weight is 0
+    if (threadIdx.x == 0) zref_s[g] = zmax[g];
+    const float ref2 = zmax[g] * scale_log2;
+    float ls = 0.f;
+    for (int i = threadIdx.x; i < nrows; i += 256) {
+      const float w = exp2f(fmaf(zw[i * G + g], scale_log2, -ref2));  // exp2(-inf) = 0
+      zw[i * G + g] = w;
+      ls = fmaf((float)su[i], w, ls);
+    }
+    lsum[g] = wave_sum_f(ls);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) red[wave][G + g] = lsum[g];
+  }
+  if (threadIdx.x == 0)
+    cn2part[(size_t)unit * chunks + chunk] =
+        fmaxf(fmaxf(red[0][2 * G], red[1][2 * G]), fmaxf(red[2][2 * G], red[3][2 * G]));
+  __syncthreads();
+
+  // ---- C: value sums --------------------------------------------------------------
+  float acc[G][EPC];
 #pragma unroll
   for (int g = 0; g < G; ++g)
-    unpack<T>(load16(q + ((size_t)(b * Hq + h * G + g) * D + sub * EPC)), qf[g]);
-
-  const int c0 = chunk * rows_per_chunk;
-  const int c1 = min(m, c0 + rows_per_chunk);
-  const T* Cu = C + (size_t)unit * m * D + sub * EPC;
-  const int32_t* su = sizes + (size_t)unit * m;
-  float cn2 = 0.f;
-
-  for (int c = c0 + grp; c < c1; c += GROUPS * U) {
-    uint4 raw[U];
-    int sz[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int cc = min(c + u * GROUPS, c1 - 1);
-      raw[u] = load16(Cu + (size_t)cc * D);
-      sz[u] = su[cc];
-    }
+    for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
+  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+  for (int c = grp; c < nrows; c += GROUPS * U) {
+    uint4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int cc = c + u * GROUPS;
-      float cf[EPC];
-      unpack<T>(raw[u], cf);
-      float n2 = 0.f, s[G];
+      float vf[EPC], w[G];
+      unpack<T>(raw[u], vf);
+      if (cc < nrows) {
+        if constexpr (G % 4 == 0) {
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) n2 = fmaf(cf[e], cf[e], n2);
+          for (int g4 = 0; g4 < G; g4 += 4) {
+            const float4 t = *reinterpret_cast<const float4*>(&zw[cc * G + g4]);
+            w[g4] = t.x; w[g4 + 1] = t.y; w[g4 + 2] = t.z; w[g4 + 3] = t.w;
+          }
+        } else {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float a = 0.f;
+          for (int g = 0; g < G; ++g) w[g] = zw[cc * G + g];
+        }
+      } else {
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) a = fmaf(qf[g][e], cf[e], a);
-        s[g] = group_sum<LPR>(a);
+        for (int g = 0; g < G; ++g) w[g] = 0.f;
       }
-      n2 = group_sum<LPR>(n2);
-      cn2 = fmaxf(cn2, n2);
-      float mine = s[0];
 #pragma unroll
-      for (int g = 1; g < G; ++g) mine = (sub == g) ? s[g] : mine;
-      if (cc < c1 && sub < G)
-        z[(size_t)(b * Hq + h * G + sub) * m + cc] = sz[u] > 0 ? mine : -INFINITY;
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(w[g], vf[e], acc[g][e]);
     }
   }
-
-  __shared__ float red[4];
-  cn2 = wave_max(cn2);
-  if (lane == 0) red[wave] = cn2;
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
+    }
+  }
+  if (lane < LPR) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float* dst = smem + (size_t)(wave * G + g) * STR;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) dst[2 + sub * EPC + e] = acc[g][e];
+    }
+  }
   __syncthreads();
-  if (threadIdx.x == 0)
-    cn2part[(size_t)unit * chunks + chunk] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  for (int idx = threadIdx.x; idx < G * STR; idx += 256) {
+    const int g = idx / STR, e = idx - g * STR;
+    float v;
+    if (e == 0) {
+      v = zref_s[g] * scale_log2;
+    } else if (e == 1) {
+      v = red[0][G + g] + red[1][G + g] + red[2][G + g] + red[3][G + g];
+    } else {
+      v = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) v += smem[(size_t)(w * G + g) * STR + e];
+    }
+    part[((size_t)(bh0 + g) * slots + slot0 + chunk) * STR + e] = v;
+  }
 }
 
 // ============================================================================
@@ -98,7 +223,6 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
 // ============================================================================
 constexpr int CAND_CAP = 1024;
 constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
-__device__ long long g_sel_prof[16];
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t u = __float_as_uint(f);
@@ -140,6 +264,62 @@ __device__ __forceinline__ int block_sum_i(int v, int* scratch) {
   return t;
 }
 
+// The estimation terms of the clusters a head selected, with a minus sign: the
+// meta-index pass added them for every cluster, the selected ones are attended
+// exactly instead.  ids[0..nsel) are read from global memory (written by this
+// workgroup before a barrier).
+template <typename T, int D, int NT>
+__device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
+                                                 const int32_t* __restrict__ off,
+                                                 const float* __restrict__ zz,
+                                                 const int32_t* __restrict__ ids, int nsel,
+                                                 float zmax, float scale_log2,
+                                                 float* __restrict__ slot) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
+  constexpr int GROUPS = NWV * RPW, STR = D + 2;
+  __shared__ float scratch[NWV * STR];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  const float ref2 = zmax * scale_log2;
+  float l = 0.f, acc[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
+  for (int t = grp; t < nsel; t += GROUPS) {
+    const int c = ids[t];
+    const float w = exp2f(fmaf(zz[c], scale_log2, -ref2));
+    const int size = off[c + 1] - off[c];
+    float vf[EPC];
+    unpack<T>(load16(vsum_u + (size_t)c * D + sub * EPC), vf);
+    l = fmaf(-(float)size, w, l);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] = fmaf(-w, vf[e], acc[e]);
+  }
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) {
+    l += __shfl_xor(l, o);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] += __shfl_xor(acc[e], o);
+  }
+  if (lane < LPR) {
+    float* dst = scratch + (size_t)wave * STR;
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) dst[2 + sub * EPC + e] = acc[e];
+    if (sub == 0) dst[1] = l;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < STR; e += NT) {
+    float v;
+    if (e == 0) {
+      v = ref2;
+    } else {
+      v = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) v += scratch[(size_t)w * STR + e];
+    }
+    slot[e] = v;
+  }
+}
+
 // NT threads per query head; with VPT > 0 every thread keeps VPT scores in
 // registers (m <= NT * VPT) and all passes run on them, with VPT == 0 the
 // scores are re-read from memory in every pass.
@@ -150,7 +330,8 @@ __global__ __launch_bounds__(NT) void select_kernel(
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected) {
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot) {
   constexpr int NW = NT / 64;
   const int bh = blockIdx.x;  // b * Hq + hq
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
@@ -419,14 +600,17 @@ __global__ __launch_bounds__(NT) void select_kernel(
     if (usel)
       for (int i = nsel + tid; i < usel_stride; i += NT) usel[i] = -1;
     if (tid == 0) {
-      nsel = min(nsel, rcap);
-      pref[nsel] = ntok;
-      nsel_out[bh] = nsel;
+      pref[min(nsel, rcap)] = ntok;
+      nsel_out[bh] = min(nsel, rcap);
       // reference score of the estimation zone: every estimated cluster scores <= it
       float ref = 0.f;
       if (nvalid > 0) ref = (mode == 2 || mode == 3) ? fminf(hi, zmax) : zmax;
       zref_out[bh] = ref;
     }
+    __syncthreads();  // ids[] complete
+    negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, min(nsel, rcap),
+                               nvalid > 0 ? zmax : 0.f, scale_log2,
+                               part + ((size_t)bh * slots + neg_slot) * (D + 2));
   }
 }
 
@@ -452,8 +636,9 @@ __device__ __forceinline__ int select_core(
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected, int bh, uint32_t* skeys, int* s_pref, int* s_row,
-    int stage_cap, int* ntok_out) {
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int bh, uint32_t* skeys, int* s_pref,
+    int* s_row, int stage_cap, int* ntok_out) {
   constexpr int NW = NT / 64;
   constexpr int TBL = VPT * NW;  // (k, wave) pairs in ascending cluster order
   static_assert(TBL <= NT && TBL >= 2 * NW, "one table entry per thread; scratch for extrema");
@@ -747,12 +932,7 @@ __device__ __forceinline__ int select_core(
   __syncthreads();
   for_k([&](int k, uint32_t) {
     const uint64_t mk = __ballot((sel >> k) & 1ull);
-    const int w = (k * NT + wave * 64) >> 5;
-    if (lane == 0) {
-      if (w < mwords) bits[w] = (uint32_t)mk;
-      tbl_cnt[k * NW + wave] = __popcll(mk);
-    }
-    if (lane == 32 && w + 1 < mwords) bits[w + 1] = (uint32_t)(mk >> 32);
+    if (lane == 0) tbl_cnt[k * NW + wave] = __popcll(mk);
   });
   __syncthreads();
   int nsel;
@@ -804,6 +984,9 @@ __device__ __forceinline__ int select_core(
     if (nvalid > 0) ref = (mode == 2 || mode == 3) ? fminf(hi, zmax) : zmax;
     zref_out[bh] = ref;
   }
+  __syncthreads();
+  negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
+                             scale_log2, part + ((size_t)bh * slots + neg_slot) * (D + 2));
   *ntok_out = carry;
   return nsel;
 }
@@ -815,12 +998,14 @@ __global__ __launch_bounds__(NT) void select_cached_kernel(
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected) {
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot) {
   extern __shared__ uint32_t dyn_keys[];  // NT * ceil(m / NT) keys when LDSK
   int ntok;
   select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
                                    usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
-                                   user_selected, blockIdx.x, dyn_keys, nullptr, nullptr, 0, &ntok);
+                                   user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
+                                   dyn_keys, nullptr, nullptr, 0, &ntok);
 }
 
 // ============================================================================
@@ -1048,8 +1233,9 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
-    int N_idx, int slots, float scale_log2, float* __restrict__ part) {
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, const T* __restrict__ k_perm,
+    const T* __restrict__ v_perm, int N_idx) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
   constexpr int GROUPS = NWV * RPW, U = 4, TILE = NT;
   extern __shared__ uint32_t dyn_keys[];
@@ -1063,8 +1249,8 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   int ntok;
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
-      sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, bh, dyn_keys, s_pref, s_row,
-      FUSED_STAGE, &ntok);
+      sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, vsum, scale_log2, part, slots,
+      neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok);
   if (threadIdx.x == 0) {
     sh_n[0] = nsel;
     sh_n[1] = ntok;
@@ -1159,132 +1345,6 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
 }
 
 // ============================================================================
-// 3c. Estimation zone: every non-empty cluster that the head did not select
-//     adds s_c * w_c to the normaliser and w_c * VS_c to the numerator, with
-//     w_c = exp(q.C_c / sqrt(d)) taken relative to a fixed reference so that
-//     partial sums of different workgroups add up directly.
-// ============================================================================
-constexpr int EST_ROWS = 512;  // clusters per workgroup
-
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void est_kernel(const T* __restrict__ vsum,
-                                                  const int32_t* __restrict__ sizes,
-                                                  const float* __restrict__ z,
-                                                  const uint32_t* __restrict__ bitmap,
-                                                  const float* __restrict__ zref, int Hkv, int m,
-                                                  int mwords, int chunks, int slots, int slot0,
-                                                  float scale_log2, float* __restrict__ part) {
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
-  constexpr int STR = D + 2;
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int unit = wg / chunks, chunk = wg - unit * chunks;
-  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
-  __shared__ __attribute__((aligned(16))) float wts[EST_ROWS * G];  // [cluster][head]
-  __shared__ float smem[4 * G * STR];
-  __shared__ float lred[4][G];
-
-  const int bh0 = b * Hq + h * G;
-  const int c0 = chunk * EST_ROWS, nrows = min(EST_ROWS, m - c0);
-  const int32_t* su = sizes + (size_t)unit * m + c0;
-
-  // Phase 1: weights of this range for the G heads (coalesced over clusters).
-  float lsum[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const size_t bh = bh0 + g;
-    const float ref2 = zref[bh] * scale_log2;
-    const float* zz = z + bh * m + c0;
-    const uint32_t* bw = bitmap + bh * mwords;
-    float ls = 0.f;
-    for (int i = threadIdx.x; i < nrows; i += 256) {
-      const int c = c0 + i, sz = su[i];
-      const bool use = sz > 0 && !((bw[c >> 5] >> (c & 31)) & 1u);
-      const float w = use ? exp2f(fmaf(zz[i], scale_log2, -ref2)) : 0.f;
-      wts[i * G + g] = w;
-      ls = fmaf((float)sz, w, ls);
-    }
-    lsum[g] = wave_sum_f(ls);
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) lred[wave][g] = lsum[g];
-  }
-  __syncthreads();
-
-  // Phase 2: stream the value sums once; all G heads consume each row.
-  float acc[G][EPC];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
-  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
-  for (int c = grp; c < nrows; c += GROUPS * U) {
-    uint4 raw[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int cc = c + u * GROUPS;
-      float vf[EPC], w[G];
-      unpack<T>(raw[u], vf);
-      if (cc < nrows) {
-        if constexpr (G % 4 == 0) {
-#pragma unroll
-          for (int g4 = 0; g4 < G; g4 += 4) {
-            const float4 t = *reinterpret_cast<const float4*>(&wts[cc * G + g4]);
-            w[g4] = t.x; w[g4 + 1] = t.y; w[g4 + 2] = t.z; w[g4 + 3] = t.w;
-          }
-        } else {
-#pragma unroll
-          for (int g = 0; g < G; ++g) w[g] = wts[cc * G + g];
-        }
-      } else {
-#pragma unroll
-        for (int g = 0; g < G; ++g) w[g] = 0.f;
-      }
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(w[g], vf[e], acc[g][e]);
-    }
-  }
-  // all groups share the reference: plain sums
-#pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
-    }
-  }
-  if (lane < LPR) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float* dst = smem + (size_t)(wave * G + g) * STR;
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) dst[2 + sub * EPC + e] = acc[g][e];
-    }
-  }
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < G * STR; idx += 256) {
-    const int g = idx / STR, e = idx - g * STR;
-    float v;
-    if (e == 0) {
-      v = zref[bh0 + g] * scale_log2;
-    } else if (e == 1) {
-      v = lred[0][g] + lred[1][g] + lred[2][g] + lred[3][g];
-    } else {
-      v = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) v += smem[(size_t)(w * G + g) * STR + e];
-    }
-    part[((size_t)(bh0 + g) * slots + slot0 + chunk) * STR + e] = v;
-  }
-}
-
-// ============================================================================
 // 4. Merge: one normalisation over the partial results of the three zones.
 // ============================================================================
 template <int D>
@@ -1298,7 +1358,7 @@ __global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part
   // global maximum over the non-empty slots (independent loads, all in flight)
   float mloc = kNegBig;
   for (int s = e; s < slots; s += D)
-    if (p[(size_t)s * STR + 1] > 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
   mloc = wave_max(mloc);
   if ((e & 63) == 0) red[e >> 6] = mloc;
   __syncthreads();
@@ -1309,7 +1369,7 @@ __global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part
     __syncthreads();
     for (int s = e; s < n; s += D) {
       const float ls = p[(size_t)(base + s) * STR + 1];
-      const float w = ls > 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
       wgt[s] = w;
       zloc = fmaf(ls, w, zloc);
     }
@@ -1345,10 +1405,10 @@ __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   DecodeGeom g{};
   const int m = ix.m, units = ix.B * ix.Hkv, heads = ix.B * Hq, D = ix.d;
-  g.score_rows = 256;
-  g.score_chunks = m > 0 ? (m + g.score_rows - 1) / g.score_rows : 0;
-  g.est_rows = EST_ROWS;
-  g.est_chunks = m > 0 ? (m + EST_ROWS - 1) / EST_ROWS : 0;
+  g.score_rows = DENSE_ROWS;   // one meta-index workgroup covers this many clusters
+  g.score_chunks = m > 0 ? (m + DENSE_ROWS - 1) / DENSE_ROWS : 0;
+  g.est_rows = DENSE_ROWS;
+  g.est_chunks = g.score_chunks;
   g.steady_rows = 256;
   g.steady_chunks = ix.p > 0 ? (ix.p + g.steady_rows - 1) / g.steady_rows : 0;
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
@@ -1362,7 +1422,9 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   // fused in one workgroup and leave one partial result.
   g.fused = (m > 0 && r > 0 && heads >= 384 && m <= 512 * 32) ? 1 : 0;
   if (g.fused) g.gather_chunks = 1;
-  g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks;
+  // partial results per head: retrieval, steady, estimation of all clusters per
+  // range, and the selected clusters' estimation terms with a minus sign
+  g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0);
   if (g.slots < 1) g.slots = 1;
   g.mwords = (m + 31) / 32;
   size_t o = 0;
@@ -1399,17 +1461,19 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
 
   if (m > 0) {
-    WAVE_LAUNCH("score", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
-                static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
-                g.score_rows);
+    const int est_slot0 = g.gather_chunks + g.steady_chunks, neg_slot = est_slot0 + g.est_chunks;
+    WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
+                static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
+                ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part);
 #define WAVE_SELECT_ARGS                                                                           \
   q, static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, r,    \
-      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected
+      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected,                        \
+      static_cast<const T*>(ix.vsum), scale_log2, part, g.slots, neg_slot
     const size_t key_lds = sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512);
     if (g.fused) {
       WAVE_LAUNCH("select_gather", (select_gather_kernel<T, D, 512, 32, true>), heads, 512, key_lds,
                   st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
-                  static_cast<const T*>(ix.v_perm), ix.N_idx, g.slots, scale_log2, part);
+                  static_cast<const T*>(ix.v_perm), ix.N_idx);
     } else {
       if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
@@ -1425,9 +1489,6 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                     nsel, Hq, ix.Hkv, ix.N_idx, g.rcap, g.gather_chunks, g.slots, scale_log2, part);
     }
 #undef WAVE_SELECT_ARGS
-    WAVE_LAUNCH("estimate", (est_kernel<T, D, G>), units * g.est_chunks, 256, 0, st,
-                static_cast<const T*>(ix.vsum), ix.sizes, z, bitmap, zref, ix.Hkv, m, g.mwords,
-                g.est_chunks, g.slots, g.gather_chunks + g.steady_chunks, scale_log2, part);
   }
   if (m == 0 && selected && topk > 0) {
     const size_t n = (size_t)heads * topk;  // no clusters exist: nothing is selected
@@ -1438,7 +1499,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
   WAVE_LAUNCH("merge", (merge_kernel<D>), heads, D, 0, st, part,
-              g.gather_chunks + g.steady_chunks + g.est_chunks, out, lse);
+              g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0), out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
