@@ -151,6 +151,18 @@ wave_status wave_kmeans_assign_step(const void *xhat, const void *chat, int dtyp
                                     int d, int32_t *assign, void *workspace,
                                     size_t workspace_bytes, void *hip_stream);
 
+/* Calibration: plain streaming kernels over a buffer of known size, for the
+ * callers that measure (the benchmark and profiler runs): a profiler counter read
+ * for them gives the factor between its unit and bytes, and their rate is the
+ * bandwidth a simple kernel reaches on the machine.  src, dst DEVICE, 16-byte
+ * aligned, `bytes` a multiple of 16; `workgroups` of 256 threads stride over the
+ * buffer.  copy reads src and writes dst; read only reads src (sink: DEVICE, at
+ * least 4 bytes, practically never written). */
+wave_status wave_calibration_copy(void *dst, const void *src, size_t bytes, int workgroups,
+                                  void *hip_stream);
+wave_status wave_calibration_read(const void *src, size_t bytes, void *sink, int workgroups,
+                                  void *hip_stream);
+
 /* Profiler (the library's only global state).  While enabled, every kernel the
  * library launches is bracketed by HIP events on its stream.
  * wave_profile_read synchronises, adds up the elapsed time per kernel name

@@ -22,8 +22,8 @@ BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_pe
 STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
                 4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
 EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode", "wave_init_indices",
-           "wave_kmeans_assign_step", "wave_profile_enable", "wave_profile_read",
-           "wave_status_string")
+           "wave_kmeans_assign_step", "wave_calibration_copy", "wave_calibration_read",
+           "wave_profile_enable", "wave_profile_read", "wave_status_string")
 
 
 class wave_index(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
                                             vp, vp, vp, sz, vp]
         L.wave_init_indices.argtypes = [u64, i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
         L.wave_kmeans_assign_step.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.wave_calibration_copy.argtypes = [vp, vp, sz, i32, vp]
+        L.wave_calibration_read.argtypes = [vp, sz, vp, i32, vp]
         L.wave_profile_enable.argtypes = [i32]
         L.wave_profile_read.argtypes = [ctypes.POINTER(ctypes.c_char_p),
                                         ctypes.POINTER(ctypes.c_float),
@@ -239,6 +241,21 @@ def wave_kmeans_assign_step(xhat: torch.Tensor, chat: torch.Tensor) -> torch.Ten
     if st != 0:
         raise WaveError(st, "wave_kmeans_assign_step")
     return assign
+
+
+def wave_calibration_copy(dst: torch.Tensor, src: torch.Tensor, workgroups: int = 8192) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    st = lib().wave_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, workgroups, _stream())
+    if st != 0:
+        raise WaveError(st, "wave_calibration_copy")
+
+
+def wave_calibration_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int = 8192) -> None:
+    nbytes = src.numel() * src.element_size()
+    st = lib().wave_calibration_read(src.data_ptr(), nbytes, sink.data_ptr(), workgroups, _stream())
+    if st != 0:
+        raise WaveError(st, "wave_calibration_read")
 
 
 def wave_profile_enable(on: bool) -> None:

@@ -57,7 +57,74 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
   const int32_t* su = sizes + (size_t)unit * m + c0;
 
   // ---- A: scores ---------------------------------------------------------------
-  {
+  if constexpr (sizeof(T) == 2) {
+    // bf16: the G x d by d x 16 products of a 16-cluster tile are MFMA work
+    // (v_mfma_f32_16x16x32_bf16, heads padded to 16 columns).  Rows arrive with
+    // fully coalesced loads (a wave-wide load is 1 KiB of consecutive rows), pass
+    // through a padded per-wave LDS tile to reach the operand layout (lane =
+    // cluster row + 16 * k-block), and a second MFMA of the tile with itself
+    // yields the squared norms on the diagonal.
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+    typedef __attribute__((ext_vector_type(4))) float floatx4_t;
+    constexpr int KS = D / 32;            // MFMA k-steps
+    constexpr int CPR = D / 8;            // 16-byte chunks per row
+    constexpr int RPL = 64 / CPR;         // rows per wave-wide load
+    constexpr int NL = 16 / RPL;          // loads per 16-row tile
+    constexpr int PITCH = D * 2 + 16;     // LDS row pitch: 16 lanes of a k-block hit 64 distinct banks
+    __shared__ __attribute__((aligned(16))) char tile[4][16 * PITCH];
+    const int hj = lane & 15, kb = lane >> 4;
+    bf16x8_t qb[KS];
+#pragma unroll
+    for (int s2 = 0; s2 < KS; ++s2) {
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (hj < G) v = load16(q + ((size_t)(bh0 + hj) * D + 32 * s2 + 8 * kb));
+      qb[s2] = __builtin_bit_cast(bf16x8_t, v);
+    }
+    const T* Cu = C + ((size_t)unit * m + c0) * D;
+    const int lrow = lane / CPR, lch = lane % CPR;
+    float cn2 = 0.f;
+    const int ntile = (nrows + 15) / 16;
+    for (int t = wave; t < ntile; t += 4) {
+      uint4 raw[NL];
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        const int rr = min(16 * t + RPL * u + lrow, nrows - 1);
+        raw[u] = load16(Cu + (size_t)rr * D + lch * 8);
+      }
+      int sz[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sz[v] = su[min(16 * t + 4 * kb + v, nrows - 1)];
+#pragma unroll
+      for (int u = 0; u < NL; ++u) store16(&tile[wave][(RPL * u + lrow) * PITCH + lch * 16], raw[u]);
+      __builtin_amdgcn_wave_barrier();  // the tile is wave-private: LDS executes a wave's accesses in order
+      floatx4_t acc = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s2 = 0; s2 < KS; ++s2) {
+        const bf16x8_t a =
+            __builtin_bit_cast(bf16x8_t, load16(&tile[wave][hj * PITCH + (4 * s2 + kb) * 16]));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[s2], acc, 0, 0, 0);
+        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, a, gram, 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();
+      // acc[v] = z[row 4 kb + v][head hj]; gram[v] is on the diagonal when 4 kb + v == hj
+      const int dv = hj & 3;
+      const float dg = dv == 0 ? gram[0] : (dv == 1 ? gram[1] : (dv == 2 ? gram[2] : gram[3]));
+      if ((hj >> 2) == kb) cn2 = fmaxf(cn2, dg);
+      if (hj < G) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int cc = 16 * t + 4 * kb + v;
+          if (cc < nrows) {
+            const float val = sz[v] > 0 ? acc[v] : -INFINITY;
+            z[(size_t)(bh0 + hj) * m + c0 + cc] = val;
+            zw[cc * G + hj] = val;
+          }
+        }
+      }
+    }
+    cn2 = wave_max(cn2);
+    if (lane == 0) red[wave][2 * G] = cn2;
+  } else {
     float qf[G][EPC];
 #pragma unroll
     for (int g = 0; g < G; ++g) unpack<T>(load16(q + ((size_t)(bh0 + g) * D + sub * EPC)), qf[g]);
@@ -143,18 +210,19 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
   __syncthreads();
 
   // ---- C: value sums --------------------------------------------------------------
+  constexpr int UC = 4;
+  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
   float acc[G][EPC];
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
-  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
-  for (int c = grp; c < nrows; c += GROUPS * U) {
-    uint4 raw[U];
+  for (int c = grp; c < nrows; c += GROUPS * UC) {
+    uint4 raw[UC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
+    for (int u = 0; u < UC; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < UC; ++u) {
       const int cc = c + u * GROUPS;
       float vf[EPC], w[G];
       unpack<T>(raw[u], vf);
@@ -676,7 +744,7 @@ __device__ __forceinline__ int select_core(
     for (int i = lane; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
     qn2 = wave_sum_f(qn2);
     c2 = wave_max(c2);
-    const float steps = (float)(Elem<T>::EPC + 6 + 4);
+    const float steps = 48.f;  // covers the vector chain + tree and the MFMA accumulation alike
     guard_in = 2.0f * steps * 5.9604645e-8f * sqrtf(qn2) * sqrtf(c2);
   }
   // With LDSK the keys live in LDS and every sweep is a short rolled loop (the
@@ -1218,6 +1286,71 @@ __global__ __launch_bounds__(256) void gather_kernel(
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
 }
 
+// ============================================================================
+// 4. Merge: one normalisation over the partial results of the three zones.
+// ============================================================================
+// All threads of the workgroup must call this (it contains barriers); the first
+// D threads do the work.  p: the head's `slots` partial results.
+template <int D>
+__device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
+                                           float* __restrict__ out_head, float* __restrict__ lse_head) {
+  constexpr int STR = D + 2, TILE = 256;
+  const int e = threadIdx.x;
+  const bool active = e < D;
+  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
+  __shared__ float red[2];
+  // global maximum over the non-empty slots (independent loads, all in flight)
+  float mloc = kNegBig;
+  if (active)
+    for (int s = e; s < slots; s += D)
+      if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  mloc = wave_max(mloc);
+  if (active && (e & 63) == 0) red[e >> 6] = mloc;
+  __syncthreads();
+  const float M = D > 64 ? fmaxf(red[0], red[1]) : red[0];
+  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
+  for (int base = 0; base < slots; base += TILE) {
+    const int n = min(TILE, slots - base);
+    __syncthreads();
+    if (active)
+      for (int s = e; s < n; s += D) {
+        const float ls = p[(size_t)(base + s) * STR + 1];
+        const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+        wgt[s] = w;
+        zloc = fmaf(ls, w, zloc);
+      }
+    __syncthreads();
+    if (active) {
+      const float* pe = p + (size_t)base * STR + 2 + e;
+      int s = 0;
+      for (; s + 4 <= n; s += 4) {
+        A0 = fmaf(pe[(size_t)(s + 0) * STR], wgt[s + 0], A0);
+        A1 = fmaf(pe[(size_t)(s + 1) * STR], wgt[s + 1], A1);
+        A2 = fmaf(pe[(size_t)(s + 2) * STR], wgt[s + 2], A2);
+        A3 = fmaf(pe[(size_t)(s + 3) * STR], wgt[s + 3], A3);
+      }
+      for (; s < n; ++s) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
+    }
+  }
+  zloc = wave_sum_f(zloc);
+  __syncthreads();
+  if (active && (e & 63) == 0) red[e >> 6] = zloc;
+  __syncthreads();
+  if (active) {
+    const float Z = D > 64 ? red[0] + red[1] : red[0];
+    const float A = (A0 + A1) + (A2 + A3);
+    out_head[e] = Z > 0.f ? A / Z : 0.f;
+    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part, int slots,
+                                                  float* __restrict__ out, float* __restrict__ lse) {
+  const int bh = blockIdx.x;
+  merge_head<D>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
+}
+
 // ----------------------------------------------------------------------------
 // Selection and retrieval zone of one query head in ONE workgroup: with many
 // heads in flight (>= 2 per CU) the latency-bound selection of one workgroup
@@ -1235,7 +1368,9 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, const T* __restrict__ k_perm,
-    const T* __restrict__ v_perm, int N_idx) {
+    const T* __restrict__ v_perm, int N_idx, const T* __restrict__ k_steady,
+    const T* __restrict__ v_steady, int p, int stagger_period, float* __restrict__ out,
+    float* __restrict__ lse) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
   constexpr int GROUPS = NWV * RPW, U = 4, TILE = NT;
   extern __shared__ uint32_t dyn_keys[];
@@ -1246,6 +1381,39 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   __shared__ int sh_n[2];
 
   const int bh = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+  const int unit = b * Hkv + hq / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+
+  AttnState<T, D, 1> st;
+  st.init(q + (size_t)bh * D, sub, scale_log2);
+
+  // The steady rows of the head's KV unit (p > 0 only when this kernel owns the
+  // steady zone).  Selection is latency-bound and leaves the memory system idle;
+  // workgroups that share a CU are dispatched stagger_period ids apart, so every
+  // other period streams its steady rows first and the rest does it last: one
+  // neighbour streams while the other selects.
+  auto steady_rows = [&]() {
+    const T* Ks = k_steady + (size_t)unit * p * D + sub * EPC;
+    const T* Vs = v_steady + (size_t)unit * p * D + sub * EPC;
+    for (int i = grp; i < p; i += GROUPS * U) {
+      uint4 kraw[U], vraw[U];
+      bool valid[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int ii = i + u * GROUPS;
+        valid[u] = ii < p;
+        const int row = valid[u] ? ii : i;
+        kraw[u] = load16(Ks + (size_t)row * D);
+        vraw[u] = load16(Vs + (size_t)row * D);
+      }
+      st.template rows<U, LPR>(kraw, vraw, valid);
+    }
+  };
+  const bool steady_first = ((blockIdx.x / stagger_period) & 1) == 0;
+  if (p > 0 && steady_first) steady_rows();
+
   int ntok;
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
@@ -1258,16 +1426,9 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   __syncthreads();  // publishes s_pref / s_row (and the global copies) to every wave
   const int nsel_all = sh_n[0], total = sh_n[1];
 
-  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
-  const int unit = b * Hkv + hq / G;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
   const bool staged = nsel_all <= FUSED_STAGE;
   const int32_t* pref = staged ? s_pref : sel_pref + (size_t)bh * (rcap + 1);
   const int32_t* srow = staged ? s_row : sel_row + (size_t)bh * rcap;
-
-  AttnState<T, D, 1> st;
-  st.init(q + (size_t)bh * D, sub, scale_log2);
   const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
   const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
   for (int base = 0; base < total; base += TILE) {
@@ -1297,10 +1458,15 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
       st.template rows<U, LPR>(kraw, vraw, valid);
     }
   }
+  if (p > 0 && !steady_first) steady_rows();
   __syncthreads();
   merge_groups_and_store<T, D, 1, NWV>(st, smem, part + (size_t)bh * slots * (D + 2), 0);
+  // Every partial result of this head now exists (the meta-index pass ran before
+  // this kernel; the exact and the negative partials were just written by this
+  // workgroup): normalise here instead of in a separate launch.
+  __syncthreads();
+  merge_head<D>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
 }
-
 
 // ============================================================================
 // 3b. Steady zone: sink + local rows of one unit, shared by its G query heads.
@@ -1344,56 +1510,6 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
                                   (size_t)slots * (D + 2));
 }
 
-// ============================================================================
-// 4. Merge: one normalisation over the partial results of the three zones.
-// ============================================================================
-template <int D>
-__global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part, int slots,
-                                                  float* __restrict__ out, float* __restrict__ lse) {
-  constexpr int STR = D + 2, TILE = 256;
-  const int bh = blockIdx.x, e = threadIdx.x;
-  const float* p = part + (size_t)bh * slots * STR;
-  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
-  __shared__ float red[2];
-  // global maximum over the non-empty slots (independent loads, all in flight)
-  float mloc = kNegBig;
-  for (int s = e; s < slots; s += D)
-    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
-  mloc = wave_max(mloc);
-  if ((e & 63) == 0) red[e >> 6] = mloc;
-  __syncthreads();
-  const float M = D > 64 ? fmaxf(red[0], red[1]) : red[0];
-  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
-  for (int base = 0; base < slots; base += TILE) {
-    const int n = min(TILE, slots - base);
-    __syncthreads();
-    for (int s = e; s < n; s += D) {
-      const float ls = p[(size_t)(base + s) * STR + 1];
-      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
-      wgt[s] = w;
-      zloc = fmaf(ls, w, zloc);
-    }
-    __syncthreads();
-    const float* pe = p + (size_t)base * STR + 2 + e;
-    int s = 0;
-    for (; s + 4 <= n; s += 4) {
-      A0 = fmaf(pe[(size_t)(s + 0) * STR], wgt[s + 0], A0);
-      A1 = fmaf(pe[(size_t)(s + 1) * STR], wgt[s + 1], A1);
-      A2 = fmaf(pe[(size_t)(s + 2) * STR], wgt[s + 2], A2);
-      A3 = fmaf(pe[(size_t)(s + 3) * STR], wgt[s + 3], A3);
-    }
-    for (; s < n; ++s) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
-  }
-  zloc = wave_sum_f(zloc);
-  __syncthreads();
-  if ((e & 63) == 0) red[e >> 6] = zloc;
-  __syncthreads();
-  const float Z = D > 64 ? red[0] + red[1] : red[0];
-  const float A = (A0 + A1) + (A2 + A3);
-  out[(size_t)bh * D + e] = Z > 0.f ? A / Z : 0.f;
-  if (e == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
-}
-
 __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -1421,7 +1537,10 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   // With at least ~1.5 query heads per CU, selection and retrieval of a head run
   // fused in one workgroup and leave one partial result.
   g.fused = (m > 0 && r > 0 && heads >= 384 && m <= 512 * 32) ? 1 : 0;
-  if (g.fused) g.gather_chunks = 1;
+  if (g.fused) {
+    g.gather_chunks = 1;
+    g.steady_chunks = 0;  // the fused kernel attends the steady rows per head as well
+  }
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and the selected clusters' estimation terms with a minus sign
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0);
@@ -1471,9 +1590,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       static_cast<const T*>(ix.vsum), scale_log2, part, g.slots, neg_slot
     const size_t key_lds = sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512);
     if (g.fused) {
-      WAVE_LAUNCH("select_gather", (select_gather_kernel<T, D, 512, 32, true>), heads, 512, key_lds,
-                  st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
-                  static_cast<const T*>(ix.v_perm), ix.N_idx);
+      WAVE_LAUNCH("select_gather_steady", (select_gather_kernel<T, D, 512, 32, true>), heads, 512,
+                  key_lds, st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
+                  static_cast<const T*>(ix.v_perm), ix.N_idx, static_cast<const T*>(ix.k_steady),
+                  static_cast<const T*>(ix.v_steady), ix.p, 2, out, lse);
     } else {
       if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
@@ -1498,8 +1618,9 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
-  WAVE_LAUNCH("merge", (merge_kernel<D>), heads, D, 0, st, part,
-              g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0), out, lse);
+  if (!g.fused)  // the fused kernel normalises each head itself
+    WAVE_LAUNCH("merge", (merge_kernel<D>), heads, D, 0, st, part,
+                g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0), out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
