@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--workload", default="llama8b_120k_b16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the library's plain copy/read kernels over 1 GiB (profiler runs "
+                         "scale their counters by what these read)")
     ap.add_argument("--only", choices=["all", "build", "decode"], default="all",
                     help="build: stop after the index build (for profiler runs); "
                          "decode: build once untimed, then only the decode phase")
@@ -68,6 +71,27 @@ def main() -> int:
     K, V = synth.make_kv(wl, device=dev)
     queries = [synth.make_queries(wl, i, device=dev) for i in range(N_QUERY_SETS)]
     torch.cuda.synchronize()
+
+    calib = None
+    if args.calibrate:
+        nb = 1 << 30
+        src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        res = {}
+        for name, fn in (("copy", lambda: wb.wave_calibration_copy(dst, src, 8192)),
+                         ("read", lambda: wb.wave_calibration_read(src, sink, 8192))):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[name + "_GBps"] = round((2 if name == "copy" else 1) * nb / (e0.elapsed_time(e1) / 5) / 1e6, 1)
+        calib = {"bytes": nb, **res}
+        del src, dst
 
     # ---------------- index build ----------------
     ix = wb.alloc_index(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
@@ -175,7 +199,9 @@ def main() -> int:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(wl.name, {}).get(dominant)
+        tk = json.load(open(tpath)).get(wl.name, {}).get(dominant)
+        if tk:
+            traffic = tk["fetch_bytes"] + tk["write_bytes"]
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "bytes_per_launch": int(bytes_k.get(dominant, 0)),
@@ -260,6 +286,7 @@ def main() -> int:
         "decode": decode_info,
         "build": build_info,
         "parity": parity,
+        "calibration": calib,
     }
     print(json.dumps(line))
     return 0

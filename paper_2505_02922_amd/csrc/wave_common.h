@@ -33,6 +33,13 @@ struct Elem<bf16_t> {
 __device__ __forceinline__ uint4 load16(const void* p) {
   return *reinterpret_cast<const uint4*>(p);
 }
+// For rows that are read once per step and never again: keeps them from
+// displacing the reusable lines (scores, partial results) in the caches.
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void store16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
 
 template <typename T>

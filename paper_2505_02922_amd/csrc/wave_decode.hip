@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
         const int rr = min(16 * t + RPL * u + lrow, nrows - 1);
-        raw[u] = load16(Cu + (size_t)rr * D + lch * 8);
+        raw[u] = load16_stream(Cu + (size_t)rr * D + lch * 8);
       }
       int sz[4];
 #pragma unroll
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
   for (int c = grp; c < nrows; c += GROUPS * UC) {
     uint4 raw[UC];
 #pragma unroll
-    for (int u = 0; u < UC; ++u) raw[u] = load16(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
+    for (int u = 0; u < UC; ++u) raw[u] = load16_stream(Vu + (size_t)min(c + u * GROUPS, nrows - 1) * D);
 #pragma unroll
     for (int u = 0; u < UC; ++u) {
       const int cc = c + u * GROUPS;
@@ -1276,8 +1276,8 @@ __global__ __launch_bounds__(256) void gather_kernel(
         const int ii = i + u * GROUPS;
         valid[u] = ii < n;
         const int row = rowidx[valid[u] ? ii : i];
-        kraw[u] = load16(Ku + (size_t)row * D);
-        vraw[u] = load16(Vu + (size_t)row * D);
+        kraw[u] = load16_stream(Ku + (size_t)row * D);
+        vraw[u] = load16_stream(Vu + (size_t)row * D);
       }
       st.template rows<U, LPR>(kraw, vraw, valid);
     }
@@ -1452,8 +1452,8 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
         const int ii = i + u * GROUPS;
         valid[u] = ii < n;
         const int row = rowidx[valid[u] ? ii : i];
-        kraw[u] = load16(Ku + (size_t)row * D);
-        vraw[u] = load16(Vu + (size_t)row * D);
+        kraw[u] = load16_stream(Ku + (size_t)row * D);
+        vraw[u] = load16_stream(Vu + (size_t)row * D);
       }
       st.template rows<U, LPR>(kraw, vraw, valid);
     }
@@ -1501,8 +1501,8 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
       const int ii = i + u * GROUPS;
       valid[u] = ii < r1;
       const int row = valid[u] ? ii : i;
-      kraw[u] = load16(Ku + (size_t)row * D);
-      vraw[u] = load16(Vu + (size_t)row * D);
+      kraw[u] = load16_stream(Ku + (size_t)row * D);
+      vraw[u] = load16_stream(Vu + (size_t)row * D);
     }
     st.template rows<U, LPR>(kraw, vraw, valid);
   }
