@@ -747,42 +747,49 @@ __device__ __forceinline__ int select_core(
     const float steps = 48.f;  // covers the vector chain + tree and the MFMA accumulation alike
     guard_in = 2.0f * steps * 5.9604645e-8f * sqrtf(qn2) * sqrtf(c2);
   }
-  // With LDSK the keys live in LDS and every sweep is a short rolled loop (the
-  // code of this kernel runs once per workgroup, so unrolled sweeps over many
-  // registers cost more in instruction fetch than they save); without, they
-  // stay in VPT registers per thread (for m too large for LDS).
-  constexpr uint32_t kKeyNegInf = 0x007fffffu;  // order_key(-inf): below every finite score
-  uint32_t kreg[LDSK ? 1 : VPT];
+  // The keys live in LDS and every sweep is a short rolled loop (this code runs
+  // once per workgroup, so unrolled sweeps over registers would cost more in
+  // instruction fetch than they save).  LDSK: full 32-bit keys (m <= 16384).
+  // Otherwise only the upper 16 bits are kept (m <= 65536): a sweep sees the
+  // start of a key's 2^16-wide bucket, except for buckets inside the "hot" range
+  // around the threshold, whose exact keys are re-read from memory.  All
+  // comparisons below are made against bounds that are either bucket-aligned or
+  // lie inside the hot range, so the truncated keys compare correctly.
+  constexpr uint32_t kKeyNegInf = LDSK ? 0x007fffffu : 0x007f0000u;  // (bucket of) order_key(-inf)
+  uint16_t* skeys16 = reinterpret_cast<uint16_t*>(skeys);
   const int nk = (m + NT - 1) / NT;  // sweeps; <= VPT
-  if constexpr (LDSK) {
-    for (int k0 = 0; k0 < nk; k0 += 8) {  // eight loads in flight per thread
-      float v[8];
+  uint32_t hot_lo = 1, hot_hi = 0;    // hot buckets (16-bit), empty to begin with
+  for (int k0 = 0; k0 < nk; k0 += 8) {  // eight loads in flight per thread
+    float v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int i = (k0 + u) * NT + tid;
-        v[u] = i < m ? zz[i] : -INFINITY;
+    for (int u = 0; u < 8; ++u) {
+      const int i = (k0 + u) * NT + tid;
+      v[u] = i < m ? zz[i] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (k0 + u < nk) {
+        const uint32_t ky = order_key(v[u] + 0.0f);  // + 0.0f folds -0 into +0
+        if constexpr (LDSK) skeys[(k0 + u) * NT + tid] = ky;
+        else skeys16[(k0 + u) * NT + tid] = (uint16_t)(ky >> 16);
       }
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (k0 + u < nk) skeys[(k0 + u) * NT + tid] = order_key(v[u] + 0.0f);  // + 0.0f folds -0 into +0
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-      const int i = k * NT + tid;
-      kreg[k] = i < m ? order_key(zz[i] + 0.0f) : kKeyNegInf;
-    }
   }
   // fn(k, key of cluster k * NT + tid) for every sweep; wave-uniform trip count
   auto for_k = [&](auto fn) {
-    if constexpr (LDSK) {
-      for (int k = 0; k < nk; ++k) fn(k, skeys[k * NT + tid]);
-    } else {
-#pragma unroll
-      for (int k = 0; k < VPT; ++k) fn(k, kreg[k]);
+    for (int k = 0; k < nk; ++k) {
+      if constexpr (LDSK) {
+        fn(k, skeys[k * NT + tid]);
+      } else {
+        const uint32_t b16 = skeys16[k * NT + tid];
+        uint32_t ky = b16 << 16;
+        if (b16 >= hot_lo && b16 <= hot_hi) {
+          const int i = k * NT + tid;
+          ky = i < m ? order_key(zz[i] + 0.0f) : ky;
+        }
+        fn(k, ky);
+      }
     }
   };
-
   // ---- valid count, maximum, |q|^2, max |C|^2 ----------------------------------
   int nv = 0;
   uint32_t kmax = kKeyNegInf, kmin = 0xffffffffu;  // over the valid scores
@@ -811,6 +818,7 @@ __device__ __forceinline__ int select_core(
     kmax = max(kmax, (uint32_t)tbl_cnt[w]);
     kmin = min(kmin, (uint32_t)tbl_cnt[NW + w]);
   }
+  if constexpr (!LDSK) kmax |= 0xffffu;  // end of the top bucket: an upper bound of every key
   const float zmax = key_to_float(kmax);
   const float guard = sh_f[0];
   const int r_eff = min(r, nvalid);
@@ -834,6 +842,31 @@ __device__ __forceinline__ int select_core(
     uint32_t khi = kmax + 1;   // count(>= khi) = 0 < r_eff
     int cnt_lo = nvalid, cnt_hi = 0;
     int it = 0;
+    if constexpr (!LDSK) {
+      // bucket-aligned steps while the keys are only known to 16 bits
+      while (khi - klo > 0x10000u && cnt_lo - cnt_hi > SURV_CAP) {
+        uint32_t mid = order_key(0.5f * key_to_float(klo) + 0.5f * key_to_float(khi - 1) + 0.0f) & 0xffff0000u;
+        if (mid <= klo) mid = klo + 0x10000u;   // klo is bucket-aligned here
+        if (mid >= khi) mid = khi - 0x10000u;   // so is khi
+        int c = 0;
+        for_k([&](int, uint32_t ky) { c += __popcll(__ballot(ky >= mid)); });
+        const int slot = it % 3;
+        if (lane == 0) atomicAdd(&cnt3[slot], c);
+        if (tid == 0) cnt3[(it + 1) % 3] = 0;
+        __syncthreads();
+        const int total = cnt3[slot];
+        if (total >= r_eff) {
+          klo = mid;
+          cnt_lo = total;
+        } else {
+          khi = mid;
+          cnt_hi = total;
+        }
+        ++it;
+      }
+      hot_lo = klo >> 16;
+      hot_hi = (khi - 1) >> 16;  // from here on the keys inside [klo, khi) are exact
+    }
     while (khi - klo > 1 && cnt_lo - cnt_hi > SURV_CAP) {
       uint32_t mid = order_key(0.5f * key_to_float(klo) + 0.5f * key_to_float(khi - 1) + 0.0f);
       if (mid <= klo || mid >= khi) mid = klo + ((khi - klo) >> 1);
@@ -900,6 +933,10 @@ __device__ __forceinline__ int select_core(
     hi = tau + guard;
     klo_band = order_key((tau - guard) + 0.0f);
     khi_band = order_key(hi + 0.0f);
+    if constexpr (!LDSK) {
+      hot_lo = klo_band >> 16;
+      hot_hi = khi_band >> 16;
+    }
     __syncthreads();
     if (tid == 0) sh_i[2] = 0;
     __syncthreads();
@@ -1289,66 +1326,74 @@ __global__ __launch_bounds__(256) void gather_kernel(
 // ============================================================================
 // 4. Merge: one normalisation over the partial results of the three zones.
 // ============================================================================
-// All threads of the workgroup must call this (it contains barriers); the first
-// D threads do the work.  p: the head's `slots` partial results.
-template <int D>
+// All NT threads of the workgroup must call this (it contains barriers).  Thread
+// t owns output dimension t % D and every (NT / D)-th partial result.
+// p: the head's `slots` partial results (max, sum, acc[D]).
+template <int D, int NT>
 __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
                                            float* __restrict__ out_head, float* __restrict__ lse_head) {
-  constexpr int STR = D + 2, TILE = 256;
-  const int e = threadIdx.x;
-  const bool active = e < D;
+  constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
+  static_assert(NT % D == 0 && NT >= D, "whole slot groups");
+  const int tid = threadIdx.x, e = tid % D, sg = tid / D;
   __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
-  __shared__ float red[2];
+  __shared__ float red[NWV];
+  __shared__ float accs[NSG * D];
   // global maximum over the non-empty slots (independent loads, all in flight)
   float mloc = kNegBig;
-  if (active)
-    for (int s = e; s < slots; s += D)
-      if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  for (int s = tid; s < slots; s += NT)
+    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
   mloc = wave_max(mloc);
-  if (active && (e & 63) == 0) red[e >> 6] = mloc;
+  if ((tid & 63) == 0) red[tid >> 6] = mloc;
   __syncthreads();
-  const float M = D > 64 ? fmaxf(red[0], red[1]) : red[0];
+  float M = red[0];
+#pragma unroll
+  for (int w = 1; w < NWV; ++w) M = fmaxf(M, red[w]);
   float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
   for (int base = 0; base < slots; base += TILE) {
     const int n = min(TILE, slots - base);
     __syncthreads();
-    if (active)
-      for (int s = e; s < n; s += D) {
-        const float ls = p[(size_t)(base + s) * STR + 1];
-        const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
-        wgt[s] = w;
-        zloc = fmaf(ls, w, zloc);
-      }
-    __syncthreads();
-    if (active) {
-      const float* pe = p + (size_t)base * STR + 2 + e;
-      int s = 0;
-      for (; s + 4 <= n; s += 4) {
-        A0 = fmaf(pe[(size_t)(s + 0) * STR], wgt[s + 0], A0);
-        A1 = fmaf(pe[(size_t)(s + 1) * STR], wgt[s + 1], A1);
-        A2 = fmaf(pe[(size_t)(s + 2) * STR], wgt[s + 2], A2);
-        A3 = fmaf(pe[(size_t)(s + 3) * STR], wgt[s + 3], A3);
-      }
-      for (; s < n; ++s) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
+    for (int s = tid; s < n; s += NT) {
+      const float ls = p[(size_t)(base + s) * STR + 1];
+      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+      wgt[s] = w;
+      zloc = fmaf(ls, w, zloc);
     }
+    __syncthreads();
+    const float* pe = p + (size_t)base * STR + 2 + e;
+    int s = sg;
+    for (; s + 3 * NSG < n; s += 4 * NSG) {
+      A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
+      A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
+      A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
+      A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
+    }
+    for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
   }
   zloc = wave_sum_f(zloc);
   __syncthreads();
-  if (active && (e & 63) == 0) red[e >> 6] = zloc;
+  if ((tid & 63) == 0) red[tid >> 6] = zloc;
+  accs[sg * D + e] = (A0 + A1) + (A2 + A3);
   __syncthreads();
-  if (active) {
-    const float Z = D > 64 ? red[0] + red[1] : red[0];
-    const float A = (A0 + A1) + (A2 + A3);
+  if (sg == 0) {
+    float Z = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) Z += red[w];
+#pragma unroll
+    for (int g = 0; g < NSG; ++g) A += accs[g * D + e];
     out_head[e] = Z > 0.f ? A / Z : 0.f;
     if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
   }
 }
 
+constexpr int MERGE_THREADS = 1024;
+
 template <int D>
-__global__ __launch_bounds__(D) void merge_kernel(const float* __restrict__ part, int slots,
-                                                  float* __restrict__ out, float* __restrict__ lse) {
+__global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(const float* __restrict__ part, int slots,
+                                                              float* __restrict__ out,
+                                                              float* __restrict__ lse) {
   const int bh = blockIdx.x;
-  merge_head<D>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
+  merge_head<D, MERGE_THREADS>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D,
+                               lse + bh);
 }
 
 // ----------------------------------------------------------------------------
@@ -1465,7 +1510,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   // this kernel; the exact and the negative partials were just written by this
   // workgroup): normalise here instead of in a separate launch.
   __syncthreads();
-  merge_head<D>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
+  merge_head<D, NT>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
 }
 
 // ============================================================================
@@ -1525,7 +1570,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.score_chunks = m > 0 ? (m + DENSE_ROWS - 1) / DENSE_ROWS : 0;
   g.est_rows = DENSE_ROWS;
   g.est_chunks = g.score_chunks;
-  g.steady_rows = 256;
+  g.steady_rows = units >= 64 ? 256 : 64;  // few units: smaller pieces to spread over the CUs
   g.steady_chunks = ix.p > 0 ? (ix.p + g.steady_rows - 1) / g.steady_rows : 0;
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
   g.rcap = r > 0 ? r : 1;
@@ -1598,9 +1643,9 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
                     WAVE_SELECT_ARGS);
-      else if (m <= 1024 * 64)  // keys in registers
-        WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024, 0, st,
-                    WAVE_SELECT_ARGS);
+      else if (m <= 1024 * 64)  // upper halves of the keys in LDS (128 KiB at most)
+        WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024,
+                    sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SELECT_ARGS);
       else
         WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SELECT_ARGS);
       if (g.gather_chunks > 0)
@@ -1619,7 +1664,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
   if (!g.fused)  // the fused kernel normalises each head itself
-    WAVE_LAUNCH("merge", (merge_kernel<D>), heads, D, 0, st, part,
+    WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part,
                 g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0), out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }

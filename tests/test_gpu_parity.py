@@ -264,3 +264,40 @@ def test_decode_many_clusters_hand_index(m, dup):
     wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d)
     for r in (0, 5, 300, m):
         _decode_and_check(wl, ix, {(0, 0): ref}, q, r, f"hand m={m}")
+
+
+@pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),
+                                        ("llama8b_32k", [(0, 0), (0, 3), (0, 7)])])
+def test_full_size_workload_sampled_units(name, units):
+    """The benchmark's own workloads at full size, in the launch configuration
+    bench.py times: whole-batch GPU build and decode; the oracle builds and
+    decodes the sampled (sequence, KV head) units from the same keys and values
+    and every array of those units, their selected sets and outputs must agree."""
+    wl = WL[name]
+    dev = torch.device("cuda")
+    K, V = synth.make_kv(wl, device=dev)
+    q = synth.make_queries(wl, 3, device=dev)
+    ix = wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
+                             wl.iters, 0)
+    r = pu.retrieve_count(wl)
+    out, lse, sel = wb.wave_attention_decode(q, ix, r, want_selected=True)
+    torch.cuda.synchronize()
+    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+    qn = q.double().cpu().numpy()
+    for (b, h) in units:
+        ref = wo.build_unit(K[b, h].double().cpu().numpy(), V[b, h].double().cpu().numpy(), plan,
+                            wl.iters, 0, b, h, wl.dtype)
+        tag = f"{name} b={b} h={h}"
+        assert np.array_equal(ix.sizes[b, h].cpu().numpy(), ref.sizes), tag
+        assert np.array_equal(ix.offsets[b, h].cpu().numpy(), ref.offsets), tag
+        assert np.array_equal(ix.perm[b, h].cpu().numpy(), ref.perm), tag
+        for nm in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
+            assert np.array_equal(ix.t[nm][b, h].float().cpu().numpy(),
+                                  getattr(ref, nm).astype(np.float32)), (tag, nm)
+        for g in range(wl.G):
+            hq = h * wl.G + g
+            parts = {}
+            o, l, s = wo.decode_unit(qn[b, hq], ref, r, parts)
+            pu.check_outputs(out[b, hq].cpu().numpy(), lse[b, hq:hq + 1].cpu().numpy(), o,
+                             np.array([l]), wl.dtype, f"{tag} hq={hq}")
+            pu.check_selected(sel[b, hq].cpu().numpy(), s, parts["z"], f"{tag} hq={hq}")
