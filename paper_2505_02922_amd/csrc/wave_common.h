@@ -186,7 +186,9 @@ struct DecodeGeom {
   int mwords;                      // 32-bit words of the selection bitmap per query head
   int rcap;                        // entries of the selected-id list per query head
   int fused;                       // selection and retrieval fused into one workgroup per head
-  size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part, total;
+  int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
+  size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part,
+      off_slice_ids, off_slice_cnt, off_cand, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 

@@ -352,15 +352,30 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
   float l = 0.f, acc[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
-  for (int t = grp; t < nsel; t += GROUPS) {
-    const int c = ids[t];
-    const float w = exp2f(fmaf(zz[c], scale_log2, -ref2));
-    const int size = off[c + 1] - off[c];
-    float vf[EPC];
-    unpack<T>(load16(vsum_u + (size_t)c * D + sub * EPC), vf);
-    l = fmaf(-(float)size, w, l);
+  constexpr int UN = 4;  // clusters in flight per group: the loads of a cluster depend on its id
+  for (int t0 = grp; t0 < nsel; t0 += GROUPS * UN) {
+    int c[UN];
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) acc[e] = fmaf(-w, vf[e], acc[e]);
+    for (int u = 0; u < UN; ++u) c[u] = ids[min(t0 + u * GROUPS, nsel - 1)];
+    float zc[UN];
+    int o0[UN], o1[UN];
+    uint4 raw[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      zc[u] = zz[c[u]];
+      o0[u] = off[c[u]];
+      o1[u] = off[c[u] + 1];
+      raw[u] = load16(vsum_u + (size_t)c[u] * D + sub * EPC);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const float w = t0 + u * GROUPS < nsel ? exp2f(fmaf(zc[u], scale_log2, -ref2)) : 0.f;
+      float vf[EPC];
+      unpack<T>(raw[u], vf);
+      l = fmaf(-(float)(o1[u] - o0[u]), w, l);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] = fmaf(-w, vf[e], acc[e]);
+    }
   }
 #pragma unroll
   for (int o = LPR; o < 64; o <<= 1) {
@@ -697,6 +712,18 @@ __global__ __launch_bounds__(NT) void select_kernel(
 // and running token counts of the first stage_cap selected clusters are also left
 // in the LDS arrays s_row / s_pref (s_pref gets nsel + 1 entries when nsel <=
 // stage_cap).  Returns the number of selected clusters; *ntok_out their tokens.
+// What a selection ranks: `npos` positions, position i standing for cluster
+// id_base + i, or idmap[i] when a map is given (ascending ids, so that "lower
+// position" is "lower id").  ids_only: stop after the ascending id list (written to
+// ids_ptr, padded with -1 to rcap) and its length (count_out).
+struct SelView {
+  int npos, id_base;
+  const int32_t* idmap;
+  int ids_only;
+  int32_t* ids_ptr;
+  int32_t* count_out;
+};
+
 template <typename T, int D, int NT, int VPT, bool LDSK>
 __device__ __forceinline__ int select_core(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
@@ -706,7 +733,7 @@ __device__ __forceinline__ int select_core(
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int bh, uint32_t* skeys, int* s_pref,
-    int* s_row, int stage_cap, int* ntok_out) {
+    int* s_row, int stage_cap, int* ntok_out, const SelView view) {
   constexpr int NW = NT / 64;
   constexpr int TBL = VPT * NW;  // (k, wave) pairs in ascending cluster order
   static_assert(TBL <= NT && TBL >= 2 * NW, "one table entry per thread; scratch for extrema");
@@ -715,7 +742,9 @@ __device__ __forceinline__ int select_core(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* zz = z + (size_t)bh * m;
   const int32_t* off = offsets + (size_t)unit * (m + 1);
-  int32_t* ids = sel_ids + (size_t)bh * rcap;
+  int32_t* ids = view.ids_ptr ? view.ids_ptr : sel_ids + (size_t)bh * rcap;
+  const int npos = view.npos;  // positions ranked here; position i is cluster cid(i)
+  auto cid = [&](int i) { return view.idmap ? view.idmap[i] : view.id_base + i; };
   int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
   int32_t* srow = sel_row + (size_t)bh * rcap;
   uint32_t* bits = bitmap + (size_t)bh * mwords;
@@ -757,14 +786,14 @@ __device__ __forceinline__ int select_core(
   // lie inside the hot range, so the truncated keys compare correctly.
   constexpr uint32_t kKeyNegInf = LDSK ? 0x007fffffu : 0x007f0000u;  // (bucket of) order_key(-inf)
   uint16_t* skeys16 = reinterpret_cast<uint16_t*>(skeys);
-  const int nk = (m + NT - 1) / NT;  // sweeps; <= VPT
+  const int nk = (npos + NT - 1) / NT;  // sweeps; <= VPT
   uint32_t hot_lo = 1, hot_hi = 0;    // hot buckets (16-bit), empty to begin with
   for (int k0 = 0; k0 < nk; k0 += 8) {  // eight loads in flight per thread
     float v[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int i = (k0 + u) * NT + tid;
-      v[u] = i < m ? zz[i] : -INFINITY;
+      v[u] = i < npos ? zz[cid(i)] : -INFINITY;
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
@@ -784,7 +813,7 @@ __device__ __forceinline__ int select_core(
         uint32_t ky = b16 << 16;
         if (b16 >= hot_lo && b16 <= hot_hi) {
           const int i = k * NT + tid;
-          ky = i < m ? order_key(zz[i] + 0.0f) : ky;
+          ky = i < npos ? order_key(zz[cid(i)] + 0.0f) : ky;
         }
         fn(k, ky);
       }
@@ -965,7 +994,7 @@ __device__ __forceinline__ int select_core(
       mode = 2;
       const T* Cu = C + (size_t)unit * m * D;
       for (int i = tid; i < n_cand; i += NT) {
-        const T* rowp = Cu + (size_t)cand_id[i] * D;
+        const T* rowp = Cu + (size_t)cid(cand_id[i]) * D;
         double acc = 0.0;
         for (int e = 0; e < D; ++e) acc = fma(to_f64(q[(size_t)bh * D + e]), to_f64(rowp[e]), acc);
         cand_z[i] = acc;
@@ -1050,11 +1079,18 @@ __device__ __forceinline__ int select_core(
     const uint64_t mk = __ballot(on);
     const int pos = tbl_cnt[k * NW + wave] + __popcll(mk & lt_mask);
     if (on && pos < rcap) {  // pos < rcap always holds for a consistent selection
-      ids[pos] = k * NT + tid;
-      if (usel) usel[pos] = k * NT + tid;
+      const int c = cid(k * NT + tid);
+      ids[pos] = c;
+      if (usel) usel[pos] = c;
     }
   });
   nsel = min(nsel, rcap);
+  if (view.ids_only) {  // a slice of a larger selection: the ids are all that is wanted
+    for (int i = nsel + tid; i < rcap; i += NT) ids[i] = -1;
+    if (tid == 0) *view.count_out = nsel;
+    *ntok_out = 0;
+    return nsel;
+  }
   __syncthreads();  // ids[] written by other waves are read below
 
   // ---- first row and running token count of every selected cluster -------------------
@@ -1110,7 +1146,77 @@ __global__ __launch_bounds__(NT) void select_cached_kernel(
   select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
                                    usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
                                    user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
-                                   dyn_keys, nullptr, nullptr, 0, &ntok);
+                                   dyn_keys, nullptr, nullptr, 0, &ntok,
+                                   SelView{m, 0, nullptr, 0, nullptr, nullptr});
+}
+
+// Selection over many clusters with few heads: each head's clusters are cut
+// into slices ranked by workgroups of their own (the r best of a slice contain
+// every cluster of the slice that is among the r best overall), and a second
+// kernel ranks the union of the slices' lists, at most nslices * r ids.
+template <typename T, int D, int NT, int VPT>
+__global__ __launch_bounds__(NT) void select_slice_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
+    int32_t* __restrict__ slice_ids, int32_t* __restrict__ slice_cnt) {
+  extern __shared__ uint32_t dyn_keys[];
+  const int bh = blockIdx.x / nslices, sl = blockIdx.x - bh * nslices;
+  const int base = sl * slice_len, len = min(slice_len, m - base);
+  int ntok;
+  // ids_only: everything after the id list (the head-level outputs) is skipped
+  select_core<T, D, NT, VPT, true>(
+      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
+      sel_row, bitmap, zref_out, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
+      dyn_keys, nullptr, nullptr, 0, &ntok,
+      SelView{len, base, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r,
+              slice_cnt + (size_t)bh * nslices + sl});
+}
+
+template <typename T, int D, int NT, int VPT>
+__global__ __launch_bounds__(NT) void select_combine_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int nslices,
+    const int32_t* __restrict__ slice_ids, const int32_t* __restrict__ slice_cnt,
+    int32_t* __restrict__ cand) {
+  extern __shared__ uint32_t dyn_keys[];
+  __shared__ int sbase[65];
+  const int bh = blockIdx.x;
+  const int32_t* cnt = slice_cnt + (size_t)bh * nslices;
+  int32_t* mine = cand + (size_t)bh * nslices * r;
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int sidx = 0; sidx < nslices; ++sidx) {
+      sbase[sidx] = acc;
+      acc += cnt[sidx];
+    }
+    sbase[nslices] = acc;
+  }
+  __syncthreads();
+  // the slices' lists are ascending and the slices are ascending id ranges:
+  // their concatenation is ascending
+  for (int sidx = 0; sidx < nslices; ++sidx) {
+    const int n = sbase[sidx + 1] - sbase[sidx];
+    const int32_t* src = slice_ids + ((size_t)bh * nslices + sidx) * r;
+    for (int j = threadIdx.x; j < n; j += NT) mine[sbase[sidx] + j] = src[j];
+  }
+  const int npos = sbase[nslices];
+  __syncthreads();
+  int ntok;
+  select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                                   usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
+                                   user_selected, vsum, scale_log2, part, slots, neg_slot, bh, dyn_keys,
+                                   nullptr, nullptr, 0, &ntok,
+                                   SelView{npos, 0, mine, 0, nullptr, nullptr});
 }
 
 // ============================================================================
@@ -1463,7 +1569,8 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
       sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, vsum, scale_log2, part, slots,
-      neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok);
+      neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok,
+      SelView{m, 0, nullptr, 0, nullptr, nullptr});
   if (threadIdx.x == 0) {
     sh_n[0] = nsel;
     sh_n[1] = ntok;
@@ -1586,6 +1693,12 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
     g.gather_chunks = 1;
     g.steady_chunks = 0;  // the fused kernel attends the steady rows per head as well
   }
+  // Few heads over many clusters: rank slices of 8192 clusters in parallel, then
+  // the union of their lists (at most nslices * r <= 16384 ids).
+  g.slice_len = 8192;
+  g.nslices = (m + g.slice_len - 1) / g.slice_len;
+  g.sliced = (!g.fused && r > 0 && m > 16384 && g.nslices <= 64 &&
+              (long long)g.nslices * r <= 16384) ? 1 : 0;
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and the selected clusters' estimation terms with a minus sign
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0);
@@ -1601,6 +1714,11 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.off_zref = o;    o = align_up(o + sizeof(float) * (size_t)heads);
   g.off_nsel = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads);
   g.off_part = o;    o = align_up(o + sizeof(float) * (size_t)heads * g.slots * (D + 2));
+  if (g.sliced) {
+    g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
+    g.off_slice_cnt = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices);
+    g.off_cand = o;      o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
+  }
   g.total = o;
   return g;
 }
@@ -1640,7 +1758,18 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   static_cast<const T*>(ix.v_perm), ix.N_idx, static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, 2, out, lse);
     } else {
-      if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
+      if (g.sliced) {
+        int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
+        int32_t* slice_cnt = reinterpret_cast<int32_t*>(w + g.off_slice_cnt);
+        int32_t* cand = reinterpret_cast<int32_t*>(w + g.off_cand);
+        WAVE_LAUNCH("select_slices", (select_slice_kernel<T, D, 512, 32>), heads * g.nslices, 512,
+                    sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512), st, WAVE_SELECT_ARGS,
+                    g.nslices, g.slice_len, slice_ids, slice_cnt);
+        const int npos_max = g.nslices * r;
+        WAVE_LAUNCH("select", (select_combine_kernel<T, D, 512, 32>), heads, 512,
+                    sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512), st, WAVE_SELECT_ARGS,
+                    g.nslices, slice_ids, slice_cnt, cand);
+      } else if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
                     WAVE_SELECT_ARGS);
       else if (m <= 1024 * 64)  // upper halves of the keys in LDS (128 KiB at most)
