@@ -187,8 +187,9 @@ struct DecodeGeom {
   int rcap;                        // entries of the selected-id list per query head
   int fused;                       // selection and retrieval fused into one workgroup per head
   int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
+  int est_with_slices_pct;         // sliced path: share of the estimation work in the slices' launch
   size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part,
-      off_slice_ids, off_slice_cnt, off_cand, total;
+      off_slice_ids, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 

@@ -33,30 +33,45 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 // ============================================================================
 constexpr int DENSE_ROWS = 256;
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, const T* __restrict__ C,
-                                                    const T* __restrict__ vsum,
-                                                    const int32_t* __restrict__ sizes,
-                                                    float* __restrict__ z, float* __restrict__ cn2part,
-                                                    int Hkv, int m, int chunks, int slots, int slot0,
-                                                    float scale_log2, float* __restrict__ part) {
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
-  constexpr int STR = D + 2;
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int unit = wg / chunks, chunk = wg - unit * chunks;
-  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
+// LDS of the meta-index pass for a workgroup of NT threads over NT clusters.
+template <typename T, int D, int G, int NT>
+struct DenseLds {
+  static constexpr int NWV = NT / 64, STR = D + 2;
+  static constexpr int PITCH = D * 2 + 16;  // bf16 tile row pitch: 16 lanes of a k-block hit 64 distinct banks
+  static constexpr size_t ZW = sizeof(float) * NT * G;             // [cluster][head]: z, then w
+  static constexpr size_t SMEM = sizeof(float) * NWV * G * STR;    // per-wave partial sums
+  static constexpr size_t RED = sizeof(float) * NWV * (2 * G + 1);
+  static constexpr size_t ZREF = sizeof(float) * G;
+  static constexpr size_t TILE = sizeof(T) == 2 ? (size_t)NWV * 16 * PITCH : 0;
+  static constexpr size_t estimate_bytes = (ZW + SMEM + RED + ZREF + 15) / 16 * 16;
+  static constexpr size_t score_bytes = (estimate_bytes + TILE + 15) / 16 * 16;
+  float* zw;
+  float* smem;
+  float (*red)[2 * G + 1];
+  float* zref_s;
+  char* tile;
+  __device__ __forceinline__ explicit DenseLds(char* base) {
+    zw = reinterpret_cast<float*>(base);
+    smem = reinterpret_cast<float*>(base + ZW);
+    red = reinterpret_cast<float (*)[2 * G + 1]>(base + ZW + SMEM);
+    zref_s = reinterpret_cast<float*>(base + ZW + SMEM + RED);
+    tile = base + estimate_bytes;
+  }
+};
+
+// A: scores of clusters [c0, c0 + nrows) of one unit for its G heads, written to
+// z and left in lds.zw; every wave leaves the largest squared centroid norm it
+// saw in lds.red[wave][2 G].  The caller synchronises.
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* __restrict__ C,
+                                             const int32_t* __restrict__ su, float* __restrict__ z,
+                                             int unit, int bh0, int m, int c0, int nrows,
+                                             const DenseLds<T, D, G, NT>& lds) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
+  constexpr int U = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
-  const int bh0 = b * Hq + h * G;
-  __shared__ __attribute__((aligned(16))) float zw[DENSE_ROWS * G];  // [cluster][head]: z, then w
-  __shared__ float smem[4 * G * STR];
-  __shared__ float red[4][2 * G + 1];
-  __shared__ float zref_s[G];
-
-  const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-  const int32_t* su = sizes + (size_t)unit * m + c0;
-
-  // ---- A: scores ---------------------------------------------------------------
+  float* zw = lds.zw;
   if constexpr (sizeof(T) == 2) {
     // bf16: the G x d by d x 16 products of a 16-cluster tile are MFMA work
     // (v_mfma_f32_16x16x32_bf16, heads padded to 16 columns).  Rows arrive with
@@ -70,8 +85,8 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
     constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int RPL = 64 / CPR;         // rows per wave-wide load
     constexpr int NL = 16 / RPL;          // loads per 16-row tile
-    constexpr int PITCH = D * 2 + 16;     // LDS row pitch: 16 lanes of a k-block hit 64 distinct banks
-    __shared__ __attribute__((aligned(16))) char tile[4][16 * PITCH];
+    constexpr int PITCH = DenseLds<T, D, G, NT>::PITCH;
+    char* tile = lds.tile + (size_t)wave * 16 * PITCH;
     const int hj = lane & 15, kb = lane >> 4;
     bf16x8_t qb[KS];
 #pragma unroll
@@ -84,7 +99,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
     const int lrow = lane / CPR, lch = lane % CPR;
     float cn2 = 0.f;
     const int ntile = (nrows + 15) / 16;
-    for (int t = wave; t < ntile; t += 4) {
+    for (int t = wave; t < ntile; t += NWV) {
       uint4 raw[NL];
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
@@ -95,13 +110,12 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
 #pragma unroll
       for (int v = 0; v < 4; ++v) sz[v] = su[min(16 * t + 4 * kb + v, nrows - 1)];
 #pragma unroll
-      for (int u = 0; u < NL; ++u) store16(&tile[wave][(RPL * u + lrow) * PITCH + lch * 16], raw[u]);
+      for (int u = 0; u < NL; ++u) store16(&tile[(RPL * u + lrow) * PITCH + lch * 16], raw[u]);
       __builtin_amdgcn_wave_barrier();  // the tile is wave-private: LDS executes a wave's accesses in order
       floatx4_t acc = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s2 = 0; s2 < KS; ++s2) {
-        const bf16x8_t a =
-            __builtin_bit_cast(bf16x8_t, load16(&tile[wave][hj * PITCH + (4 * s2 + kb) * 16]));
+        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, load16(&tile[hj * PITCH + (4 * s2 + kb) * 16]));
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[s2], acc, 0, 0, 0);
         gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, a, gram, 0, 0, 0);
       }
@@ -123,7 +137,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
       }
     }
     cn2 = wave_max(cn2);
-    if (lane == 0) red[wave][2 * G] = cn2;
+    if (lane == 0) lds.red[wave][2 * G] = cn2;
   } else {
     float qf[G][EPC];
 #pragma unroll
@@ -168,32 +182,60 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
     // sum over the LPR lanes of a row of per-lane maxima >= maximum over rows of the row sums
     cn2 = group_sum<LPR>(cn2);
     cn2 = wave_max(cn2);
-    if (lane == 0) red[wave][2 * G] = cn2;
+    if (lane == 0) lds.red[wave][2 * G] = cn2;
   }
-  __syncthreads();
+}
 
+// Largest squared centroid norm of the range, after dense_scores and a barrier.
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ float dense_cn2(const DenseLds<T, D, G, NT>& lds) {
+  float v = lds.red[0][2 * G];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) v = fmaxf(v, lds.red[w][2 * G]);
+  return v;
+}
+
+// B, C: estimation terms of clusters [c0, c0 + nrows) for the unit's G heads from
+// the scores in lds.zw (visible to all threads): one partial per head at
+// part_head0 + g * head_stride.  All NT threads call this.
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
+                                               const int32_t* __restrict__ su, int unit, int m, int c0,
+                                               int nrows, float scale_log2,
+                                               const DenseLds<T, D, G, NT>& lds,
+                                               float* __restrict__ part_head0, size_t head_stride) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
+  constexpr int STR = D + 2;
+  constexpr int UC = 4;  // rows in flight per group
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  float* zw = lds.zw;
+  float* smem = lds.smem;
+  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
   // ---- B: weights relative to the range maximum -----------------------------------
   float zmax[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float mx = -INFINITY;
-    for (int i = threadIdx.x; i < nrows; i += 256) mx = fmaxf(mx, zw[i * G + g]);
+    for (int i = threadIdx.x; i < nrows; i += NT) mx = fmaxf(mx, zw[i * G + g]);
     zmax[g] = wave_max(mx);
   }
   if (lane == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) red[wave][g] = zmax[g];
+    for (int g = 0; g < G; ++g) lds.red[wave][g] = zmax[g];
   }
   __syncthreads();
   float lsum[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const float mx = fmaxf(fmaxf(red[0][g], red[1][g]), fmaxf(red[2][g], red[3][g]));
+    float mx = lds.red[0][g];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) mx = fmaxf(mx, lds.red[w][g]);
     zmax[g] = mx > -INFINITY ? mx : 0.f;   // a range of empty clusters only: every weight is 0
-    if (threadIdx.x == 0) zref_s[g] = zmax[g];
+    if (threadIdx.x == 0) lds.zref_s[g] = zmax[g];
     const float ref2 = zmax[g] * scale_log2;
     float ls = 0.f;
-    for (int i = threadIdx.x; i < nrows; i += 256) {
+    for (int i = threadIdx.x; i < nrows; i += NT) {
       const float w = exp2f(fmaf(zw[i * G + g], scale_log2, -ref2));  // exp2(-inf) = 0
       zw[i * G + g] = w;
       ls = fmaf((float)su[i], w, ls);
@@ -202,16 +244,11 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
   }
   if (lane == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) red[wave][G + g] = lsum[g];
+    for (int g = 0; g < G; ++g) lds.red[wave][G + g] = lsum[g];
   }
-  if (threadIdx.x == 0)
-    cn2part[(size_t)unit * chunks + chunk] =
-        fmaxf(fmaxf(red[0][2 * G], red[1][2 * G]), fmaxf(red[2][2 * G], red[3][2 * G]));
   __syncthreads();
 
   // ---- C: value sums --------------------------------------------------------------
-  constexpr int UC = 4;
-  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
   float acc[G][EPC];
 #pragma unroll
   for (int g = 0; g < G; ++g)
@@ -264,20 +301,64 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * STR; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * STR; idx += NT) {
     const int g = idx / STR, e = idx - g * STR;
-    float v;
+    float v = 0.f;
     if (e == 0) {
-      v = zref_s[g] * scale_log2;
+      v = lds.zref_s[g] * scale_log2;
     } else if (e == 1) {
-      v = red[0][G + g] + red[1][G + g] + red[2][G + g] + red[3][G + g];
-    } else {
-      v = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) v += smem[(size_t)(w * G + g) * STR + e];
+      for (int w = 0; w < NWV; ++w) v += lds.red[w][G + g];
+    } else {
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) v += smem[(size_t)(w * G + g) * STR + e];
     }
-    part[((size_t)(bh0 + g) * slots + slot0 + chunk) * STR + e] = v;
+    part_head0[(size_t)g * head_stride + e] = v;
   }
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, const T* __restrict__ C,
+                                                    const T* __restrict__ vsum,
+                                                    const int32_t* __restrict__ sizes,
+                                                    float* __restrict__ z, float* __restrict__ cn2part,
+                                                    int Hkv, int m, int chunks, int slots, int slot0,
+                                                    float scale_log2, float* __restrict__ part) {
+  using Lds = DenseLds<T, D, G, 256>;
+  __shared__ __attribute__((aligned(16))) char lds_raw[Lds::score_bytes];
+  const Lds lds(lds_raw);
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int unit = wg / chunks, chunk = wg - unit * chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
+  const int bh0 = b * Hq + h * G;
+  const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
+  const int32_t* su = sizes + (size_t)unit * m + c0;
+  dense_scores<T, D, G, 256>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+  __syncthreads();
+  if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
+  dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
+                               part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
+                               (size_t)slots * (D + 2));
+}
+
+// The scores alone (the estimation terms are made by other launches, next to
+// the selection).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, const T* __restrict__ C,
+                                                    const int32_t* __restrict__ sizes,
+                                                    float* __restrict__ z, float* __restrict__ cn2part,
+                                                    int Hkv, int m, int chunks) {
+  using Lds = DenseLds<T, D, G, 256>;
+  __shared__ __attribute__((aligned(16))) char lds_raw[Lds::score_bytes];
+  const Lds lds(lds_raw);
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int unit = wg / chunks, chunk = wg - unit * chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
+  const int bh0 = b * Hq + h * G;
+  const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
+  dense_scores<T, D, G, 256>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds);
+  __syncthreads();
+  if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
 }
 
 // ============================================================================
@@ -291,6 +372,7 @@ __global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, con
 // ============================================================================
 constexpr int CAND_CAP = 1024;
 constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
+constexpr int SEL_BINS = 2048; // buckets of the one-sweep histogram that starts the threshold search
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t u = __float_as_uint(f);
@@ -352,7 +434,7 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
   float l = 0.f, acc[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
-  constexpr int UN = 4;  // clusters in flight per group: the loads of a cluster depend on its id
+  constexpr int UN = 8;  // clusters in flight per group: the loads of a cluster depend on its id
   for (int t0 = grp; t0 < nsel; t0 += GROUPS * UN) {
     int c[UN];
 #pragma unroll
@@ -715,13 +797,12 @@ __global__ __launch_bounds__(NT) void select_kernel(
 // What a selection ranks: `npos` positions, position i standing for cluster
 // id_base + i, or idmap[i] when a map is given (ascending ids, so that "lower
 // position" is "lower id").  ids_only: stop after the ascending id list (written to
-// ids_ptr, padded with -1 to rcap) and its length (count_out).
+// ids_ptr, padded with -1 to rcap).
 struct SelView {
   int npos, id_base;
   const int32_t* idmap;
   int ids_only;
   int32_t* ids_ptr;
-  int32_t* count_out;
 };
 
 template <typename T, int D, int NT, int VPT, bool LDSK>
@@ -758,6 +839,8 @@ __device__ __forceinline__ int select_core(
   __shared__ int cnt3[3];
   __shared__ int sh_i[4];
   __shared__ float sh_f[2];
+  static_assert(SEL_BINS * sizeof(int) <= CAND_CAP * sizeof(double), "the histogram borrows cand_z");
+  int* hist = reinterpret_cast<int*>(cand_z);  // free until the candidates are re-scored
 
   // ---- this thread's scores as order-preserving integer keys -------------------
   // Error bound inputs first, so that their loads overlap with the key loads:
@@ -793,7 +876,8 @@ __device__ __forceinline__ int select_core(
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int i = (k0 + u) * NT + tid;
-      v[u] = i < npos ? zz[cid(i)] : -INFINITY;
+      const int c = i < npos ? cid(i) : -1;  // an id map may hold -1: a hole, never selected
+      v[u] = c >= 0 ? zz[c] : -INFINITY;
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
@@ -871,6 +955,49 @@ __device__ __forceinline__ int select_core(
     uint32_t khi = kmax + 1;   // count(>= khi) = 0 < r_eff
     int cnt_lo = nvalid, cnt_hi = 0;
     int it = 0;
+    {
+      // Stage 0, one sweep: count the valid keys by their upper 16 bits (sign,
+      // exponent, 7 mantissa bits) in the SEL_BINS buckets below the maximum's
+      // (everything lower shares bin 0); a scan from the top finds the bucket
+      // that holds the r-th largest key, which replaces most halving steps.
+      const uint32_t top16 = kmax >> 16;
+      const uint32_t lo16 = top16 >= (uint32_t)(SEL_BINS - 1) ? top16 - (SEL_BINS - 1) : 0u;
+      for (int i = tid; i < SEL_BINS; i += NT) hist[i] = 0;
+      __syncthreads();
+      for_k([&](int, uint32_t ky) {
+        if (ky > kKeyNegInf) {
+          const uint32_t b16 = ky >> 16;
+          atomicAdd(&hist[b16 > lo16 ? b16 - lo16 : 0u], 1);
+        }
+      });
+      __syncthreads();
+      constexpr int PER = SEL_BINS / NT;
+      static_assert(PER >= 1 && PER * NT == SEL_BINS, "bins per thread");
+      int mine[PER], s = 0;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        mine[j] = hist[SEL_BINS - 1 - (tid * PER + j)];  // thread 0 holds the top bins
+        s += mine[j];
+      }
+      int tot;
+      int above = block_excl_scan<NT>(s, scan_scratch, tot);  // keys in the bins above mine[0]'s
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        if (above < r_eff && above + mine[j] >= r_eff) {  // exactly one (thread, j): r_eff <= nvalid
+          sh_i[0] = SEL_BINS - 1 - (tid * PER + j);
+          sh_i[1] = above;
+          sh_i[3] = above + mine[j];
+        }
+        above += mine[j];
+      }
+      __syncthreads();
+      const int bsel = sh_i[0];
+      cnt_hi = sh_i[1];
+      cnt_lo = sh_i[3];
+      if (bsel > 0) klo = (lo16 + (uint32_t)bsel) << 16;                  // count(>= klo) = cnt_lo
+      if (bsel < SEL_BINS - 1) khi = (lo16 + (uint32_t)bsel + 1u) << 16;  // count(>= khi) = cnt_hi
+      __syncthreads();  // sh_i is reused below
+    }
     if constexpr (!LDSK) {
       // bucket-aligned steps while the keys are only known to 16 bits
       while (khi - klo > 0x10000u && cnt_lo - cnt_hi > SURV_CAP) {
@@ -1087,7 +1214,6 @@ __device__ __forceinline__ int select_core(
   nsel = min(nsel, rcap);
   if (view.ids_only) {  // a slice of a larger selection: the ids are all that is wanted
     for (int i = nsel + tid; i < rcap; i += NT) ids[i] = -1;
-    if (tid == 0) *view.count_out = nsel;
     *ntok_out = 0;
     return nsel;
   }
@@ -1147,76 +1273,7 @@ __global__ __launch_bounds__(NT) void select_cached_kernel(
                                    usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
                                    user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
                                    dyn_keys, nullptr, nullptr, 0, &ntok,
-                                   SelView{m, 0, nullptr, 0, nullptr, nullptr});
-}
-
-// Selection over many clusters with few heads: each head's clusters are cut
-// into slices ranked by workgroups of their own (the r best of a slice contain
-// every cluster of the slice that is among the r best overall), and a second
-// kernel ranks the union of the slices' lists, at most nslices * r ids.
-template <typename T, int D, int NT, int VPT>
-__global__ __launch_bounds__(NT) void select_slice_kernel(
-    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
-    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
-    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
-    float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
-    int32_t* __restrict__ slice_ids, int32_t* __restrict__ slice_cnt) {
-  extern __shared__ uint32_t dyn_keys[];
-  const int bh = blockIdx.x / nslices, sl = blockIdx.x - bh * nslices;
-  const int base = sl * slice_len, len = min(slice_len, m - base);
-  int ntok;
-  // ids_only: everything after the id list (the head-level outputs) is skipped
-  select_core<T, D, NT, VPT, true>(
-      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
-      sel_row, bitmap, zref_out, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
-      dyn_keys, nullptr, nullptr, 0, &ntok,
-      SelView{len, base, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r,
-              slice_cnt + (size_t)bh * nslices + sl});
-}
-
-template <typename T, int D, int NT, int VPT>
-__global__ __launch_bounds__(NT) void select_combine_kernel(
-    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
-    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
-    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
-    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
-    float* __restrict__ part, int slots, int neg_slot, int nslices,
-    const int32_t* __restrict__ slice_ids, const int32_t* __restrict__ slice_cnt,
-    int32_t* __restrict__ cand) {
-  extern __shared__ uint32_t dyn_keys[];
-  __shared__ int sbase[65];
-  const int bh = blockIdx.x;
-  const int32_t* cnt = slice_cnt + (size_t)bh * nslices;
-  int32_t* mine = cand + (size_t)bh * nslices * r;
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int sidx = 0; sidx < nslices; ++sidx) {
-      sbase[sidx] = acc;
-      acc += cnt[sidx];
-    }
-    sbase[nslices] = acc;
-  }
-  __syncthreads();
-  // the slices' lists are ascending and the slices are ascending id ranges:
-  // their concatenation is ascending
-  for (int sidx = 0; sidx < nslices; ++sidx) {
-    const int n = sbase[sidx + 1] - sbase[sidx];
-    const int32_t* src = slice_ids + ((size_t)bh * nslices + sidx) * r;
-    for (int j = threadIdx.x; j < n; j += NT) mine[sbase[sidx] + j] = src[j];
-  }
-  const int npos = sbase[nslices];
-  __syncthreads();
-  int ntok;
-  select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
-                                   usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
-                                   user_selected, vsum, scale_log2, part, slots, neg_slot, bh, dyn_keys,
-                                   nullptr, nullptr, 0, &ntok,
-                                   SelView{npos, 0, mine, 0, nullptr, nullptr});
+                                   SelView{m, 0, nullptr, 0, nullptr});
 }
 
 // ============================================================================
@@ -1241,6 +1298,40 @@ struct AttnState {
         qf[g][e] *= scale_log2;
         acc[g][e] = 0.f;
       }
+    }
+  }
+
+  // U rows whose logits s[g][u] (base-2 units) are known and which count mult[u]
+  // times in the normaliser: a cluster standing for its members.
+  template <int U>
+  __device__ __forceinline__ void rows_given(const float (&s)[NG][U], const float (&mult)[U],
+                                             const uint4 (&vraw)[U]) {
+    float p[NG][U];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      float mn = mx[g];
+#pragma unroll
+      for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[g][u]);   // -inf for rows that do not count
+      const float alpha = exp2f(mx[g] - mn);
+      float ps = 0.f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        p[g][u] = exp2f(s[g][u] - mn);
+        ps = fmaf(mult[u], p[g][u], ps);
+      }
+      l[g] = fmaf(l[g], alpha, ps);
+      mx[g] = mn;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[g][e] *= alpha;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float vf[EPC];
+      unpack<T>(vraw[u], vf);
+#pragma unroll
+      for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(p[g][u], vf[e], acc[g][e]);
     }
   }
 
@@ -1350,6 +1441,68 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
 }
 
 // ============================================================================
+// 4. Merge: one normalisation over the partial results of the three zones.
+// ============================================================================
+// All NT threads of the workgroup must call this (it contains barriers).  Thread
+// t owns output dimension t % D and every (NT / D)-th partial result.
+// p: the head's `slots` partial results (max, sum, acc[D]).
+template <int D, int NT>
+__device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
+                                           float* __restrict__ out_head, float* __restrict__ lse_head) {
+  constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
+  static_assert(NT % D == 0 && NT >= D, "whole slot groups");
+  const int tid = threadIdx.x, e = tid % D, sg = tid / D;
+  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
+  __shared__ float red[NWV];
+  __shared__ float accs[NSG * D];
+  // global maximum over the non-empty slots (independent loads, all in flight)
+  float mloc = kNegBig;
+  for (int s = tid; s < slots; s += NT)
+    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  mloc = wave_max(mloc);
+  if ((tid & 63) == 0) red[tid >> 6] = mloc;
+  __syncthreads();
+  float M = red[0];
+#pragma unroll
+  for (int w = 1; w < NWV; ++w) M = fmaxf(M, red[w]);
+  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
+  for (int base = 0; base < slots; base += TILE) {
+    const int n = min(TILE, slots - base);
+    __syncthreads();
+    for (int s = tid; s < n; s += NT) {
+      const float ls = p[(size_t)(base + s) * STR + 1];
+      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+      wgt[s] = w;
+      zloc = fmaf(ls, w, zloc);
+    }
+    __syncthreads();
+    const float* pe = p + (size_t)base * STR + 2 + e;
+    int s = sg;
+    for (; s + 3 * NSG < n; s += 4 * NSG) {
+      A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
+      A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
+      A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
+      A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
+    }
+    for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
+  }
+  zloc = wave_sum_f(zloc);
+  __syncthreads();
+  if ((tid & 63) == 0) red[tid >> 6] = zloc;
+  accs[sg * D + e] = (A0 + A1) + (A2 + A3);
+  __syncthreads();
+  if (sg == 0) {
+    float Z = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) Z += red[w];
+#pragma unroll
+    for (int g = 0; g < NSG; ++g) A += accs[g * D + e];
+    out_head[e] = Z > 0.f ? A / Z : 0.f;
+    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
+  }
+}
+
+// ============================================================================
 // 3a. Retrieval zone: one workgroup handles one slice of the tokens of the
 //     clusters selected by one query head, reading them in place from the
 //     cluster-contiguous K/V.
@@ -1427,68 +1580,6 @@ __global__ __launch_bounds__(256) void gather_kernel(
   }
   __syncthreads();
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
-}
-
-// ============================================================================
-// 4. Merge: one normalisation over the partial results of the three zones.
-// ============================================================================
-// All NT threads of the workgroup must call this (it contains barriers).  Thread
-// t owns output dimension t % D and every (NT / D)-th partial result.
-// p: the head's `slots` partial results (max, sum, acc[D]).
-template <int D, int NT>
-__device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
-                                           float* __restrict__ out_head, float* __restrict__ lse_head) {
-  constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
-  static_assert(NT % D == 0 && NT >= D, "whole slot groups");
-  const int tid = threadIdx.x, e = tid % D, sg = tid / D;
-  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
-  __shared__ float red[NWV];
-  __shared__ float accs[NSG * D];
-  // global maximum over the non-empty slots (independent loads, all in flight)
-  float mloc = kNegBig;
-  for (int s = tid; s < slots; s += NT)
-    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
-  mloc = wave_max(mloc);
-  if ((tid & 63) == 0) red[tid >> 6] = mloc;
-  __syncthreads();
-  float M = red[0];
-#pragma unroll
-  for (int w = 1; w < NWV; ++w) M = fmaxf(M, red[w]);
-  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
-  for (int base = 0; base < slots; base += TILE) {
-    const int n = min(TILE, slots - base);
-    __syncthreads();
-    for (int s = tid; s < n; s += NT) {
-      const float ls = p[(size_t)(base + s) * STR + 1];
-      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
-      wgt[s] = w;
-      zloc = fmaf(ls, w, zloc);
-    }
-    __syncthreads();
-    const float* pe = p + (size_t)base * STR + 2 + e;
-    int s = sg;
-    for (; s + 3 * NSG < n; s += 4 * NSG) {
-      A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
-      A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
-      A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
-      A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
-    }
-    for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
-  }
-  zloc = wave_sum_f(zloc);
-  __syncthreads();
-  if ((tid & 63) == 0) red[tid >> 6] = zloc;
-  accs[sg * D + e] = (A0 + A1) + (A2 + A3);
-  __syncthreads();
-  if (sg == 0) {
-    float Z = 0.f, A = 0.f;
-#pragma unroll
-    for (int w = 0; w < NWV; ++w) Z += red[w];
-#pragma unroll
-    for (int g = 0; g < NSG; ++g) A += accs[g * D + e];
-    out_head[e] = Z > 0.f ? A / Z : 0.f;
-    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
-  }
 }
 
 constexpr int MERGE_THREADS = 1024;
@@ -1570,7 +1661,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
       sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, vsum, scale_log2, part, slots,
       neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok,
-      SelView{m, 0, nullptr, 0, nullptr, nullptr});
+      SelView{m, 0, nullptr, 0, nullptr});
   if (threadIdx.x == 0) {
     sh_n[0] = nsel;
     sh_n[1] = ntok;
@@ -1623,28 +1714,23 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
 // ============================================================================
 // 3b. Steady zone: sink + local rows of one unit, shared by its G query heads.
 // ============================================================================
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
-                                                     const T* __restrict__ k_steady,
-                                                     const T* __restrict__ v_steady, int Hkv, int p,
-                                                     int chunks, int rows_per_chunk, int slots,
-                                                     int slot0, float scale_log2,
-                                                     float* __restrict__ part) {
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW;
+// Rows [r0, r1) of one unit's steady buffers for its G query heads; smem:
+// (NT / 64) * G * (D + 2) floats.  All NT threads call this.
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ void steady_rows_partial(const T* __restrict__ q,
+                                                    const T* __restrict__ k_steady,
+                                                    const T* __restrict__ v_steady, int unit, int bh0,
+                                                    int p, int r0, int r1, float scale_log2,
+                                                    float* smem, float* __restrict__ part_head0,
+                                                    size_t head_stride) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
   constexpr int U = (G <= 4) ? 4 : 2;
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int unit = wg / chunks, chunk = wg - unit * chunks;
-  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
-  __shared__ float smem[4 * G * (D + 2)];
-
-  const int bh0 = b * Hq + h * G;
   AttnState<T, D, G> st;
   st.init(q + (size_t)bh0 * D, sub, scale_log2);
   const T* Ku = k_steady + (size_t)unit * p * D + sub * EPC;
   const T* Vu = v_steady + (size_t)unit * p * D + sub * EPC;
-  const int r0 = chunk * rows_per_chunk, r1 = min(p, r0 + rows_per_chunk);
   for (int i = r0 + grp; i < r1; i += GROUPS * U) {
     uint4 kraw[U], vraw[U];
     bool valid[U];
@@ -1658,8 +1744,168 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
     }
     st.template rows<U, LPR>(kraw, vraw, valid);
   }
-  merge_groups_and_store<T, D, G>(st, smem, part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
-                                  (size_t)slots * (D + 2));
+  merge_groups_and_store<T, D, G, NWV>(st, smem, part_head0, head_stride);
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
+                                                     const T* __restrict__ k_steady,
+                                                     const T* __restrict__ v_steady, int Hkv, int p,
+                                                     int chunks, int rows_per_chunk, int slots,
+                                                     int slot0, float scale_log2,
+                                                     float* __restrict__ part) {
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int unit = wg / chunks, chunk = wg - unit * chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
+  __shared__ float smem[4 * G * (D + 2)];
+  const int bh0 = b * Hq + h * G;
+  const int r0 = chunk * rows_per_chunk, r1 = min(p, r0 + rows_per_chunk);
+  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p, r0, r1, scale_log2, smem,
+                                    part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
+                                    (size_t)slots * (D + 2));
+}
+
+// ----------------------------------------------------------------------------
+// Few heads over many clusters: ranking a slice is a chain of short dependent
+// steps that leaves the memory system idle, so the same launch also carries the
+// work that does not depend on the selection: the estimation terms of all
+// clusters (from the scores of the previous launch) and the steady zone.  The
+// slice workgroups have the lowest ids, so they are dispatched first.
+// ----------------------------------------------------------------------------
+// Work that does not depend on the selection, carried by the launches of the
+// sliced selection: estimation ranges [est_first, est_first + n_est_wgs) over
+// all units' ranges of NT clusters, then the steady-zone pieces.
+struct SideWork {
+  const int32_t* sizes;
+  int est_rows, est_chunks, est_slot0, est_first, n_est_wgs;
+  const void* k_steady;
+  const void* v_steady;
+  int p, steady_chunks, steady_rows, steady_slot0;
+};
+
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* __restrict__ q,
+                                          const float* __restrict__ z, const T* __restrict__ vsum,
+                                          int Hq, int Hkv, int m, float scale_log2,
+                                          float* __restrict__ part, int slots, char* lds_raw) {
+  if (wg < sw.n_est_wgs) {
+    // Estimation terms of sw.est_rows clusters of one unit for its G heads, as a
+    // stream: every group of LPR lanes takes rows of value sums with their
+    // scores (read back from z) and sizes and keeps an online-softmax state, the
+    // cluster's score as the logit and its size as the multiplicity.  No barrier
+    // before the final merge, so the loads of many rows are in flight.
+    constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
+    constexpr int GROUPS = NWV * RPW, U = 4;
+    static_assert(G <= LPR, "one lane per head's score");
+    wg = xcd_logical_block(wg, sw.n_est_wgs) + sw.est_first;
+    const int unit = wg / sw.est_chunks, chunk = wg - unit * sw.est_chunks;
+    const int b = unit / Hkv, h = unit - b * Hkv;
+    const int bh0 = b * Hq + h * G;
+    const int c0 = chunk * sw.est_rows, nrows = min(sw.est_rows, m - c0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % LPR, grp = wave * RPW + lane / LPR, gbase = lane - sub;
+    AttnState<T, D, G> st;
+    st.init(q + (size_t)bh0 * D, sub, scale_log2);  // the queries themselves are not used: scores are given
+    const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+    const float* zsrc = z + (size_t)(bh0 + (sub < G ? sub : 0)) * m + c0;  // lane sub fetches head sub's score
+    const int32_t* ssrc = sw.sizes + (size_t)unit * m + c0;
+    for (int i = grp; i < nrows; i += GROUPS * U) {
+      uint4 vraw[U];
+      float mine[U], mult[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int ii = i + u * GROUPS;
+        const int row = ii < nrows ? ii : i;
+        vraw[u] = load16_stream(Vu + (size_t)row * D);
+        mine[u] = ii < nrows ? zsrc[row] : -INFINITY;  // beyond the range: weight 0
+        mult[u] = (float)ssrc[row];
+      }
+      float sc[G][U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) sc[g][u] = __shfl(mine[u], gbase + g) * scale_log2;
+      }
+      st.template rows_given<U>(sc, mult, vraw);
+    }
+    merge_groups_and_store<T, D, G, NWV>(st, reinterpret_cast<float*>(lds_raw),
+                                         part + ((size_t)bh0 * slots + sw.est_slot0 + chunk) * (D + 2),
+                                         (size_t)slots * (D + 2));
+    return;
+  }
+  wg -= sw.n_est_wgs;
+  const int unit = wg / sw.steady_chunks, chunk = wg - unit * sw.steady_chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv;
+  const int bh0 = b * Hq + h * G;
+  const int r0 = chunk * sw.steady_rows, r1 = min(sw.p, r0 + sw.steady_rows);
+  steady_rows_partial<T, D, G, NT>(q, static_cast<const T*>(sw.k_steady),
+                                   static_cast<const T*>(sw.v_steady), unit, bh0, sw.p, r0, r1,
+                                   scale_log2, reinterpret_cast<float*>(lds_raw),
+                                   part + ((size_t)bh0 * slots + sw.steady_slot0 + chunk) * (D + 2),
+                                   (size_t)slots * (D + 2));
+}
+
+// ----------------------------------------------------------------------------
+// Few heads over many clusters: ranking a slice (and then the union of the
+// slices' lists) is a chain of short dependent steps that leaves the memory
+// system idle, so the two launches also carry the work that does not depend on
+// the selection: the estimation terms of all clusters (from the scores of the
+// first launch) and the steady zone.  The selecting workgroups have the lowest
+// ids, so they are dispatched first.
+// ----------------------------------------------------------------------------
+template <typename T, int D, int G, int NT, int VPT>
+__global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
+    int32_t* __restrict__ slice_ids, int n_select_wgs, const SideWork sw) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];  // a slice's keys, or the other roles' LDS
+  if ((int)blockIdx.x < n_select_wgs) {
+    const int bh = blockIdx.x / nslices, sl = blockIdx.x - bh * nslices;
+    const int base = sl * slice_len, len = min(slice_len, m - base);
+    int ntok;
+    select_core<T, D, NT, VPT, true>(
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
+        sel_row, bitmap, zref_out, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
+        dyn_keys, nullptr, nullptr, 0, &ntok,
+        SelView{len, base, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r});
+    return;
+  }
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+                         slots, reinterpret_cast<char*>(dyn_keys));
+}
+
+template <typename T, int D, int G, int NT, int VPT>
+__global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int nslices,
+    const int32_t* __restrict__ slice_ids, int n_select_wgs, const SideWork sw) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];
+  if ((int)blockIdx.x < n_select_wgs) {
+    // A slice's list is ascending and padded with -1 to r entries, and the
+    // slices are ascending id ranges: read one after the other, with the padding
+    // as holes, the lists are one ascending id map of nslices * r positions.
+    const int bh = blockIdx.x;
+    int ntok;
+    select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                                     usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out,
+                                     nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot,
+                                     bh, dyn_keys, nullptr, nullptr, 0, &ntok,
+                                     SelView{nslices * r, 0, slice_ids + (size_t)bh * nslices * r, 0,
+                                             nullptr});
+    return;
+  }
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+                         slots, reinterpret_cast<char*>(dyn_keys));
 }
 
 __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
@@ -1701,6 +1947,11 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
               (long long)g.nslices * r <= 16384) ? 1 : 0;
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and the selected clusters' estimation terms with a minus sign
+  if (g.sliced) {  // the estimation terms come from 512-thread workgroups next to the slices
+    g.est_rows = 512;
+    g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
+    g.est_with_slices_pct = 40;  // share of the estimation ranges that ride with the slices
+  }
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0);
   if (g.slots < 1) g.slots = 1;
   g.mwords = (m + 31) / 32;
@@ -1716,8 +1967,6 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.off_part = o;    o = align_up(o + sizeof(float) * (size_t)heads * g.slots * (D + 2));
   if (g.sliced) {
     g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
-    g.off_slice_cnt = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices);
-    g.off_cand = o;      o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
   }
   g.total = o;
   return g;
@@ -1744,9 +1993,13 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
 
   if (m > 0) {
     const int est_slot0 = g.gather_chunks + g.steady_chunks, neg_slot = est_slot0 + g.est_chunks;
-    WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
-                static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
-                ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part);
+    if (g.sliced)
+      WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
+                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks);
+    else
+      WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
+                  static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
+                  ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part);
 #define WAVE_SELECT_ARGS                                                                           \
   q, static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, r,    \
       g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected,                        \
@@ -1760,15 +2013,27 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     } else {
       if (g.sliced) {
         int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
-        int32_t* slice_cnt = reinterpret_cast<int32_t*>(w + g.off_slice_cnt);
-        int32_t* cand = reinterpret_cast<int32_t*>(w + g.off_cand);
-        WAVE_LAUNCH("select_slices", (select_slice_kernel<T, D, 512, 32>), heads * g.nslices, 512,
-                    sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512), st, WAVE_SELECT_ARGS,
-                    g.nslices, g.slice_len, slice_ids, slice_cnt);
+        // Each head's clusters are cut into slices ranked by workgroups of their own
+        // (the r best of a slice contain every cluster of the slice that is among the
+        // r best overall); the second launch ranks the union of the slices' lists.
         const int npos_max = g.nslices * r;
-        WAVE_LAUNCH("select", (select_combine_kernel<T, D, 512, 32>), heads, 512,
-                    sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512), st, WAVE_SELECT_ARGS,
-                    g.nslices, slice_ids, slice_cnt, cand);
+        size_t lds_a = sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512);
+        size_t lds_b = sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512);
+        const size_t lds_side = sizeof(float) * 8 * G * (D + 2);  // the side roles' final merge
+        if (lds_a < lds_side) lds_a = lds_side;
+        if (lds_b < lds_side) lds_b = lds_side;
+        const int n_est = units * g.est_chunks;
+        const int n_est_a = (int)((long long)n_est * g.est_with_slices_pct / 100);
+        SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, n_est_a, ix.k_steady,
+                    ix.v_steady, ix.p, g.steady_chunks, g.steady_rows, g.gather_chunks};
+        WAVE_LAUNCH("select_slices+side", (slices_side_kernel<T, D, G, 512, 32>),
+                    heads * g.nslices + n_est_a + units * g.steady_chunks, 512, lds_a, st,
+                    WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, heads * g.nslices, sw);
+        sw.est_first = n_est_a;
+        sw.n_est_wgs = n_est - n_est_a;
+        sw.steady_chunks = 0;  // done by the first launch
+        WAVE_LAUNCH("select+side", (combine_side_kernel<T, D, G, 512, 32>), heads + sw.n_est_wgs, 512,
+                    lds_b, st, WAVE_SELECT_ARGS, g.nslices, slice_ids, heads, sw);
       } else if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
                     WAVE_SELECT_ARGS);
@@ -1777,6 +2042,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                     sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SELECT_ARGS);
       else
         WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SELECT_ARGS);
+      if (g.steady_chunks > 0 && g.gather_chunks > 0 && !g.sliced)  // sliced: done next to the slices
+        WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
+                    static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
+                    g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
       if (g.gather_chunks > 0)
         WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                     static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow,
@@ -1788,7 +2057,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     const size_t n = (size_t)heads * topk;  // no clusters exist: nothing is selected
     WAVE_LAUNCH("fill", fill_i32_kernel, (unsigned)((n + 255) / 256), 256, 0, st, selected, n, -1);
   }
-  if (g.steady_chunks > 0)
+  if ((m == 0 || g.gather_chunks == 0) && g.steady_chunks > 0)  // otherwise launched above
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
