@@ -192,7 +192,7 @@ def main() -> int:
         "meta_index": meta, "steady": steady_b, "gather": gather_b, "select_gather": gather_b,
         "select_gather_steady": gather_b + steady_b, "select": 0, "merge": 0,
         "scores": meta // 2, "select_slices+side": 0, "select+side": meta // 2 + steady_b,
-        "gather+merge": gather_b,
+        "gather+merge": gather_b, "meta_index+steady": meta + steady_b,
     }
     step_bytes = meta + steady_b + gather_b
     kern = {k: v[0] / max(v[1], 1) for k, v in dec_prof.items()}      # ms per launch

@@ -186,10 +186,11 @@ struct DecodeGeom {
   int mwords;                      // 32-bit words of the selection bitmap per query head
   int rcap;                        // entries of the selected-id list per query head
   int fused;                       // selection and retrieval fused into one workgroup per head
+  int neg_in_gather, neg_slots;    // selected clusters' estimation terms: taken out by the retrieval kernel / a partial of their own
   int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
   int est_with_slices_pct;         // sliced path: share of the estimation work in the slices' launch
   size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part,
-      off_slice_ids, total;
+      off_slice_ids, off_slice_z, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 

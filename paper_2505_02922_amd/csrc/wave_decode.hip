@@ -801,8 +801,11 @@ __global__ __launch_bounds__(NT) void select_kernel(
 struct SelView {
   int npos, id_base;
   const int32_t* idmap;
-  int ids_only;
+  const float* zmap;   // with an id map: the scores by position (-inf at holes), saves the lookup in z
+  int ids_only;        // 1: a slice (ids and scores to ids_ptr / z_out); 2: the head's list and count,
+                       // nothing after them (the retrieval kernel derives the rest)
   int32_t* ids_ptr;
+  float* z_out;        // ids_only: the scores of the listed ids, -inf padded like the ids
 };
 
 template <typename T, int D, int NT, int VPT, bool LDSK>
@@ -871,16 +874,21 @@ __device__ __forceinline__ int select_core(
   uint16_t* skeys16 = reinterpret_cast<uint16_t*>(skeys);
   const int nk = (npos + NT - 1) / NT;  // sweeps; <= VPT
   uint32_t hot_lo = 1, hot_hi = 0;    // hot buckets (16-bit), empty to begin with
-  for (int k0 = 0; k0 < nk; k0 += 8) {  // eight loads in flight per thread
-    float v[8];
+  constexpr int KB = 16;  // loads in flight per thread
+  for (int k0 = 0; k0 < nk; k0 += KB) {
+    float v[KB];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < KB; ++u) {
       const int i = (k0 + u) * NT + tid;
-      const int c = i < npos ? cid(i) : -1;  // an id map may hold -1: a hole, never selected
-      v[u] = c >= 0 ? zz[c] : -INFINITY;
+      if (view.zmap) {  // scores by position; holes of the id map are -inf here
+        v[u] = i < npos ? view.zmap[i] : -INFINITY;
+      } else {
+        const int c = i < npos ? cid(i) : -1;
+        v[u] = c >= 0 ? zz[c] : -INFINITY;
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < KB; ++u)
       if (k0 + u < nk) {
         const uint32_t ky = order_key(v[u] + 0.0f);  // + 0.0f folds -0 into +0
         if constexpr (LDSK) skeys[(k0 + u) * NT + tid] = ky;
@@ -1201,7 +1209,7 @@ __device__ __forceinline__ int select_core(
   __syncthreads();
   if (tid < TBL) tbl_cnt[tid] = cbase;
   __syncthreads();
-  for_k([&](int k, uint32_t) {
+  for_k([&](int k, uint32_t ky) {
     const bool on = (sel >> k) & 1ull;
     const uint64_t mk = __ballot(on);
     const int pos = tbl_cnt[k * NW + wave] + __popcll(mk & lt_mask);
@@ -1209,11 +1217,20 @@ __device__ __forceinline__ int select_core(
       const int c = cid(k * NT + tid);
       ids[pos] = c;
       if (usel) usel[pos] = c;
+      if (LDSK && view.z_out) view.z_out[pos] = key_to_float(ky);  // the key is the score, bit for bit
     }
   });
   nsel = min(nsel, rcap);
-  if (view.ids_only) {  // a slice of a larger selection: the ids are all that is wanted
-    for (int i = nsel + tid; i < rcap; i += NT) ids[i] = -1;
+  if (view.ids_only) {
+    for (int i = nsel + tid; i < rcap; i += NT) {
+      ids[i] = -1;
+      if (view.z_out) view.z_out[i] = -INFINITY;
+    }
+    if (view.ids_only == 2) {
+      if (usel)
+        for (int i = nsel + tid; i < usel_stride; i += NT) usel[i] = -1;
+      if (tid == 0) nsel_out[bh] = nsel;
+    }
     *ntok_out = 0;
     return nsel;
   }
@@ -1273,7 +1290,7 @@ __global__ __launch_bounds__(NT) void select_cached_kernel(
                                    usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
                                    user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
                                    dyn_keys, nullptr, nullptr, 0, &ntok,
-                                   SelView{m, 0, nullptr, 0, nullptr});
+                                   SelView{m, 0, nullptr, nullptr, 2, nullptr, nullptr});
 }
 
 // ============================================================================
@@ -1303,7 +1320,8 @@ struct AttnState {
 
   // U rows whose logits s[g][u] (base-2 units) are known and which count mult[u]
   // times in the normaliser: a cluster standing for its members.
-  template <int U>
+  // NEG: the rows are taken out again (terms added elsewhere for every cluster).
+  template <int U, bool NEG = false>
   __device__ __forceinline__ void rows_given(const float (&s)[NG][U], const float (&mult)[U],
                                              const uint4 (&vraw)[U]) {
     float p[NG][U];
@@ -1316,7 +1334,7 @@ struct AttnState {
       float ps = 0.f;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        p[g][u] = exp2f(s[g][u] - mn);
+        p[g][u] = NEG ? -exp2f(s[g][u] - mn) : exp2f(s[g][u] - mn);
         ps = fmaf(mult[u], p[g][u], ps);
       }
       l[g] = fmaf(l[g], alpha, ps);
@@ -1507,15 +1525,20 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
 //     clusters selected by one query head, reading them in place from the
 //     cluster-contiguous K/V.
 // ============================================================================
-constexpr int GATHER_TILE = 256;
-constexpr int GATHER_STAGE = 2048;  // selected clusters whose ranges are staged in LDS
+constexpr int GATHER_TILE = 256;  // tokens (and clusters) per pass of a workgroup
 
+// Workgroup `chunk` of a head takes an equal share of the head's selected
+// clusters, by their position in the ascending id list: it reads their row
+// ranges from the offsets, attends their tokens exactly, and, when own_neg is
+// set, takes the same clusters' estimation terms (which the estimation pass
+// added for every cluster) out again, in the same online-softmax state.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_kernel(
     const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
-    const int32_t* __restrict__ sel_pref, const int32_t* __restrict__ sel_row,
-    const int32_t* __restrict__ nsel_arr, int Hq, int Hkv, int N_idx, int rcap, int chunks,
-    int slots, float scale_log2, float* __restrict__ part) {
+    const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ nsel_arr,
+    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
+    int Hq, int Hkv, int N_idx, int m, int rcap, int chunks, int slots, float scale_log2, int own_neg,
+    float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
   const int bh = wg / chunks, chunk = wg - bh * chunks;
@@ -1525,60 +1548,90 @@ __global__ __launch_bounds__(256) void gather_kernel(
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
 
   __shared__ int rowidx[GATHER_TILE];
-  __shared__ int s_pref[GATHER_STAGE + 1];
-  __shared__ int s_row[GATHER_STAGE];
+  __shared__ int cl_pref[GATHER_TILE + 1];
+  __shared__ int cl_row[GATHER_TILE];
+  __shared__ int cl_id[GATHER_TILE];
+  __shared__ float cl_logit[GATHER_TILE];
+  __shared__ int scan_scratch[4];
   __shared__ float smem[4 * (D + 2)];
 
   const int nsel = nsel_arr[bh];
-  const int32_t* gpref = sel_pref + (size_t)bh * (rcap + 1);
-  const int32_t* grow = sel_row + (size_t)bh * rcap;
-  const int total = gpref[nsel];
-  const int per = (total + chunks - 1) / chunks;
-  const int t0 = min(total, chunk * per), t1 = min(total, t0 + per);
-
-  // The token range [t0, t1) of the concatenated selected clusters maps to rows
-  // through (running token count, first row) per selected cluster.
-  const bool staged = nsel <= GATHER_STAGE;
-  if (staged && t0 < t1) {
-    for (int i = threadIdx.x; i <= nsel; i += 256) s_pref[i] = gpref[i];
-    for (int i = threadIdx.x; i < nsel; i += 256) s_row[i] = grow[i];
-  }
-  const int32_t* pref = staged ? s_pref : gpref;
-  const int32_t* srow = staged ? s_row : grow;
+  const int c_lo = (int)((long long)chunk * nsel / chunks), c_hi = (int)((long long)(chunk + 1) * nsel / chunks);
+  const int32_t* ids = sel_ids + (size_t)bh * rcap;
+  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const float* zz = z + (size_t)bh * m;
 
   AttnState<T, D, 1> st;
   st.init(q + (size_t)bh * D, sub, scale_log2);
   const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
   const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
+  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
 
-  for (int base = t0; base < t1; base += GATHER_TILE) {
-    const int n = min(GATHER_TILE, t1 - base);
-    __syncthreads();
-    if ((int)threadIdx.x < n) {
-      const int t = base + threadIdx.x;
-      int a = 0, e = nsel;  // largest a with pref[a] <= t
-      while (e - a > 1) {
-        const int mid = (a + e) >> 1;
-        if (pref[mid] <= t) a = mid; else e = mid;
-      }
-      rowidx[threadIdx.x] = srow[a] + (t - pref[a]);
+  for (int cb = c_lo; cb < c_hi; cb += GATHER_TILE) {
+    const int nc = min(GATHER_TILE, c_hi - cb);
+    // (first row, running token count, id, logit) of the pass's clusters
+    int r0 = 0, size = 0, id = 0;
+    float zc = -INFINITY;
+    if ((int)threadIdx.x < nc) {
+      id = ids[cb + threadIdx.x];
+      r0 = off[id];
+      size = off[id + 1] - r0;
+      zc = zz[id];
     }
-    __syncthreads();
-    for (int i = grp; i < n; i += GROUPS * U) {
-      uint4 kraw[U], vraw[U];
-      bool valid[U];
+    int total;
+    const int ex = block_excl_scan<256>(size, scan_scratch, total);  // barriers inside: the LDS arrays are free
+    if ((int)threadIdx.x < nc) {
+      cl_pref[threadIdx.x] = ex;
+      cl_row[threadIdx.x] = r0;
+      cl_id[threadIdx.x] = id;
+      cl_logit[threadIdx.x] = zc * scale_log2;
+    }
+    if (threadIdx.x == 0) cl_pref[nc] = total;
+    for (int base = 0; base < total; base += GATHER_TILE) {
+      const int n = min(GATHER_TILE, total - base);
+      __syncthreads();
+      if ((int)threadIdx.x < n) {
+        const int t = base + threadIdx.x;
+        int a = 0, e = nc;  // largest a with cl_pref[a] <= t
+        while (e - a > 1) {
+          const int mid = (a + e) >> 1;
+          if (cl_pref[mid] <= t) a = mid; else e = mid;
+        }
+        rowidx[threadIdx.x] = cl_row[a] + (t - cl_pref[a]);
+      }
+      __syncthreads();
+      for (int i = grp; i < n; i += GROUPS * U) {
+        uint4 kraw[U], vraw[U];
+        bool valid[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int ii = i + u * GROUPS;
-        valid[u] = ii < n;
-        const int row = rowidx[valid[u] ? ii : i];
-        kraw[u] = load16_stream(Ku + (size_t)row * D);
-        vraw[u] = load16_stream(Vu + (size_t)row * D);
+        for (int u = 0; u < U; ++u) {
+          const int ii = i + u * GROUPS;
+          valid[u] = ii < n;
+          const int row = rowidx[valid[u] ? ii : i];
+          kraw[u] = load16_stream(Ku + (size_t)row * D);
+          vraw[u] = load16_stream(Vu + (size_t)row * D);
+        }
+        st.template rows<U, LPR>(kraw, vraw, valid);
       }
-      st.template rows<U, LPR>(kraw, vraw, valid);
     }
+    __syncthreads();  // cl_* complete even when the pass has no tokens
+    if (own_neg) {
+      for (int i = grp; i < nc; i += GROUPS * U) {
+        uint4 vraw[U];
+        float sc[1][U], mult[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int ii = i + u * GROUPS;
+          const int j = ii < nc ? ii : i;
+          vraw[u] = load16(VSu + (size_t)cl_id[j] * D);
+          sc[0][u] = ii < nc ? cl_logit[j] : -INFINITY;
+          mult[u] = (float)(cl_pref[j + 1] - cl_pref[j]);
+        }
+        st.template rows_given<U, true>(sc, mult, vraw);
+      }
+    }
+    __syncthreads();  // before the next pass overwrites cl_*
   }
-  __syncthreads();
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
 }
 
@@ -1661,7 +1714,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
       sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, vsum, scale_log2, part, slots,
       neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok,
-      SelView{m, 0, nullptr, 0, nullptr});
+      SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr});
   if (threadIdx.x == 0) {
     sh_n[0] = nsel;
     sh_n[1] = ntok;
@@ -1772,6 +1825,47 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
 // clusters (from the scores of the previous launch) and the steady zone.  The
 // slice workgroups have the lowest ids, so they are dispatched first.
 // ----------------------------------------------------------------------------
+// The meta-index pass with the steady-zone pieces as extra workgroups (few heads:
+// neither fills the chip alone, and a launch less is a few microseconds less).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void dense_steady_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const T* __restrict__ vsum,
+    const int32_t* __restrict__ sizes, float* __restrict__ z, float* __restrict__ cn2part, int Hkv,
+    int m, int chunks, int slots, int slot0, float scale_log2, float* __restrict__ part,
+    int n_dense_wgs, const T* __restrict__ k_steady, const T* __restrict__ v_steady, int p,
+    int steady_chunks, int steady_rows, int steady_slot0) {
+  using Lds = DenseLds<T, D, G, 256>;
+  constexpr size_t kSteadyBytes = sizeof(float) * 4 * G * (D + 2);
+  __shared__ __attribute__((aligned(16))) char
+      lds_raw[Lds::score_bytes > kSteadyBytes ? Lds::score_bytes : kSteadyBytes];
+  const int Hq = Hkv * G;
+  if ((int)blockIdx.x < n_dense_wgs) {
+    const Lds lds(lds_raw);
+    const int wg = xcd_logical_block(blockIdx.x, n_dense_wgs);
+    const int unit = wg / chunks, chunk = wg - unit * chunks;
+    const int b = unit / Hkv, h = unit - b * Hkv;
+    const int bh0 = b * Hq + h * G;
+    const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
+    const int32_t* su = sizes + (size_t)unit * m + c0;
+    dense_scores<T, D, G, 256>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+    __syncthreads();
+    if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
+    dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
+                                 part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
+                                 (size_t)slots * (D + 2));
+    return;
+  }
+  const int wg = (int)blockIdx.x - n_dense_wgs;
+  const int unit = wg / steady_chunks, chunk = wg - unit * steady_chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv;
+  const int bh0 = b * Hq + h * G;
+  const int r0 = chunk * steady_rows, r1 = min(p, r0 + steady_rows);
+  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p, r0, r1, scale_log2,
+                                    reinterpret_cast<float*>(lds_raw),
+                                    part + ((size_t)bh0 * slots + steady_slot0 + chunk) * (D + 2),
+                                    (size_t)slots * (D + 2));
+}
+
 // Work that does not depend on the selection, carried by the launches of the
 // sliced selection: estimation ranges [est_first, est_first + n_est_wgs) over
 // all units' ranges of NT clusters, then the steady-zone pieces.
@@ -1862,7 +1956,8 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
-    int32_t* __restrict__ slice_ids, int n_select_wgs, const SideWork sw) {
+    int32_t* __restrict__ slice_ids, float* __restrict__ slice_z, int n_select_wgs,
+    const SideWork sw) {
   extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];  // a slice's keys, or the other roles' LDS
   if ((int)blockIdx.x < n_select_wgs) {
     const int bh = blockIdx.x / nslices, sl = blockIdx.x - bh * nslices;
@@ -1872,7 +1967,8 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
         q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
         sel_row, bitmap, zref_out, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
         dyn_keys, nullptr, nullptr, 0, &ntok,
-        SelView{len, base, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r});
+        SelView{len, base, nullptr, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r,
+                slice_z + ((size_t)bh * nslices + sl) * r});
     return;
   }
   side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
@@ -1888,7 +1984,8 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int nslices,
-    const int32_t* __restrict__ slice_ids, int n_select_wgs, const SideWork sw) {
+    const int32_t* __restrict__ slice_ids, const float* __restrict__ slice_z, int n_select_wgs,
+    const SideWork sw) {
   extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];
   if ((int)blockIdx.x < n_select_wgs) {
     // A slice's list is ascending and padded with -1 to r entries, and the
@@ -1900,8 +1997,8 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
                                      usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out,
                                      nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot,
                                      bh, dyn_keys, nullptr, nullptr, 0, &ntok,
-                                     SelView{nslices * r, 0, slice_ids + (size_t)bh * nslices * r, 0,
-                                             nullptr});
+                                     SelView{nslices * r, 0, slice_ids + (size_t)bh * nslices * r,
+                                             slice_z + (size_t)bh * nslices * r, 2, nullptr, nullptr});
     return;
   }
   side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
@@ -1946,13 +2043,18 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.sliced = (!g.fused && r > 0 && m > 16384 && g.nslices <= 64 &&
               (long long)g.nslices * r <= 16384) ? 1 : 0;
   // partial results per head: retrieval, steady, estimation of all clusters per
-  // range, and the selected clusters' estimation terms with a minus sign
+  // range, and (see below) the selected clusters' estimation terms with a minus sign
   if (g.sliced) {  // the estimation terms come from 512-thread workgroups next to the slices
     g.est_rows = 512;
     g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
     g.est_with_slices_pct = 40;  // share of the estimation ranges that ride with the slices
   }
-  g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0);
+  // Who takes the selected clusters' estimation terms out again: the retrieval
+  // kernel itself (no partial of their own), except after the fused kernel and
+  // after the streaming selection, which write them as one more partial.
+  g.neg_in_gather = (m > 0 && !g.fused && (g.sliced || m <= 1024 * 64)) ? 1 : 0;
+  g.neg_slots = (m > 0 && !g.neg_in_gather) ? 1 : 0;
+  g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots;
   if (g.slots < 1) g.slots = 1;
   g.mwords = (m + 31) / 32;
   size_t o = 0;
@@ -1967,6 +2069,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.off_part = o;    o = align_up(o + sizeof(float) * (size_t)heads * g.slots * (D + 2));
   if (g.sliced) {
     g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
+    g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * r);
   }
   g.total = o;
   return g;
@@ -1992,10 +2095,19 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
 
   if (m > 0) {
-    const int est_slot0 = g.gather_chunks + g.steady_chunks, neg_slot = est_slot0 + g.est_chunks;
+    const int est_slot0 = g.gather_chunks + g.steady_chunks;
+    const int neg_slot = est_slot0 + g.est_chunks;  // exists when g.neg_slots is 1
     if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks);
+    else if (!g.fused && g.steady_chunks > 0)
+      WAVE_LAUNCH("meta_index+steady", (dense_steady_kernel<T, D, G>),
+                  units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
+                  static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
+                  ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part,
+                  units * g.score_chunks, static_cast<const T*>(ix.k_steady),
+                  static_cast<const T*>(ix.v_steady), ix.p, g.steady_chunks, g.steady_rows,
+                  g.gather_chunks);
     else
       WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
@@ -2013,6 +2125,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     } else {
       if (g.sliced) {
         int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
+        float* slice_z = reinterpret_cast<float*>(w + g.off_slice_z);
         // Each head's clusters are cut into slices ranked by workgroups of their own
         // (the r best of a slice contain every cluster of the slice that is among the
         // r best overall); the second launch ranks the union of the slices' lists.
@@ -2028,12 +2141,12 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                     ix.v_steady, ix.p, g.steady_chunks, g.steady_rows, g.gather_chunks};
         WAVE_LAUNCH("select_slices+side", (slices_side_kernel<T, D, G, 512, 32>),
                     heads * g.nslices + n_est_a + units * g.steady_chunks, 512, lds_a, st,
-                    WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, heads * g.nslices, sw);
+                    WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, sw);
         sw.est_first = n_est_a;
         sw.n_est_wgs = n_est - n_est_a;
         sw.steady_chunks = 0;  // done by the first launch
         WAVE_LAUNCH("select+side", (combine_side_kernel<T, D, G, 512, 32>), heads + sw.n_est_wgs, 512,
-                    lds_b, st, WAVE_SELECT_ARGS, g.nslices, slice_ids, heads, sw);
+                    lds_b, st, WAVE_SELECT_ARGS, g.nslices, slice_ids, slice_z, heads, sw);
       } else if (m <= 512 * 32)  // keys in LDS (64 KiB at most)
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512, key_lds, st,
                     WAVE_SELECT_ARGS);
@@ -2042,14 +2155,11 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                     sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SELECT_ARGS);
       else
         WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SELECT_ARGS);
-      if (g.steady_chunks > 0 && g.gather_chunks > 0 && !g.sliced)  // sliced: done next to the slices
-        WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
-                    static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
-                    g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
       if (g.gather_chunks > 0)
         WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
-                    static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow,
-                    nsel, Hq, ix.Hkv, ix.N_idx, g.rcap, g.gather_chunks, g.slots, scale_log2, part);
+                    static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), sel, nsel,
+                    ix.offsets, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, ix.N_idx, m, g.rcap,
+                    g.gather_chunks, g.slots, scale_log2, g.neg_in_gather, part);
     }
 #undef WAVE_SELECT_ARGS
   }
@@ -2057,13 +2167,13 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     const size_t n = (size_t)heads * topk;  // no clusters exist: nothing is selected
     WAVE_LAUNCH("fill", fill_i32_kernel, (unsigned)((n + 255) / 256), 256, 0, st, selected, n, -1);
   }
-  if ((m == 0 || g.gather_chunks == 0) && g.steady_chunks > 0)  // otherwise launched above
+  if (m == 0 && g.steady_chunks > 0)  // with clusters, the steady pieces ride with an earlier launch
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
   if (!g.fused)  // the fused kernel normalises each head itself
     WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part,
-                g.gather_chunks + g.steady_chunks + g.est_chunks + (m > 0 ? 1 : 0), out, lse);
+                g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
