@@ -13,8 +13,6 @@
 //               sort    (stable counting sort of the segment's points by cluster)
 //               update  (centroid = quant(member sum / |member sum|), fp64)
 //   finalize    sizes, offsets, mean of raw keys, value sums, permuted K/V rows
-#include <stdlib.h>
-
 #include "wave_common.h"
 
 namespace wave {
@@ -321,6 +319,128 @@ __global__ __launch_bounds__(64 * NW) void assign_mfma_kernel(
       assign[gp] = btile[f] * 32 + brow;
       const float gap = __int_as_float(best[f]) - (nsec > 0 ? __int_as_float(nsec) : 0.f);
       if (gap < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+    }
+  }
+}
+
+// ============================================================================
+// Assign, MFMA path with the segment's centroids resident in LDS: one workgroup
+// of 16 waves copies all k_s centroid rows into LDS once (padded rows, at most
+// ~136 KiB) and then every wave works through fragments of 32 * NF points on
+// its own: no barrier and no global centroid traffic inside the loop.
+// ============================================================================
+template <int D, int NF, int NW>
+__global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
+    const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
+    int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
+    int pieces_per_seg) {
+  constexpr int KS = D / 16;            // MFMA k-steps per tile
+  constexpr int ROWB = D * 2 + 16;      // LDS row pitch: 16 B pad keeps 16 lanes on 64 distinct banks
+  constexpr int CPR = D / 8;            // 16-byte chunks per centroid row
+  extern __shared__ __attribute__((aligned(16))) char cent[];  // 32 * ceil(k_s / 32) rows
+
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int sg = wg / pieces_per_seg, piece = wg - sg * pieces_per_seg;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int nfrag = (si.L_s + 31) / 32;
+  const int per = ((nfrag + pieces_per_seg - 1) / pieces_per_seg + NF - 1) / NF * NF;
+  const int f_lo = piece * per, f_hi = min(nfrag, f_lo + per);
+  if (f_lo >= f_hi) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
+  const bf16_t* Cs = chat + (size_t)sg * kk * D;
+  const int ntiles = (si.k_s + 31) / 32;
+
+  for (int id = tid; id < 32 * ntiles * CPR; id += 64 * NW) {
+    const int row = id / CPR, ch = id - row * CPR;
+    store16(cent + row * ROWB + ch * 16, load16(Cs + (size_t)min(row, si.k_s - 1) * D + ch * 8));
+  }
+  __syncthreads();
+
+  const int nfull = si.k_s / 32;  // tiles without rows beyond k_s
+  constexpr float B0 = kAssignBias;
+  floatx16 bias = {B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0};
+  asm volatile("" : "+v"(bias));  // kept in registers: one accumulator-start operand for every tile
+  for (int fb = f_lo + wave * NF; fb < f_hi; fb += NW * NF) {
+    uint4 bfrag[NF][KS];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      const int row = min(32 * (fb + f) + col, si.L_s - 1);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) bfrag[f][s] = load16(X + (size_t)row * D + (2 * s + half) * 8);
+    }
+    int best[NF], second[NF], btile[NF];  // biased similarities as integers; 0 is below all of them
+#pragma unroll
+    for (int f = 0; f < NF; ++f) best[f] = second[f] = btile[f] = 0;
+    auto mfma_tile = [&](int t, floatx16 (&acc)[NF]) {
+      const char* tile = cent + (size_t)(32 * t + col) * ROWB + half * 16;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, load16(tile + s * 32));
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, bfrag[f][s]);
+          acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, s == 0 ? bias : acc[f], 0, 0, 0);
+        }
+      }
+    };
+    // One tile's MFMAs are issued between the integer epilogue instructions of
+    // the tile before it (two accumulator sets): the matrix pipe works while the
+    // vector ALU ranks the previous results.
+    auto interleave = [&]() {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // the first two LDS reads
+#pragma unroll
+      for (int i = 0; i < KS * NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the LDS read two MFMAs ahead
+        __builtin_amdgcn_sched_group_barrier(0x002, 48 / KS, 0);  // a share of the epilogue
+      }
+    };
+    floatx16 accA[NF], accB[NF];
+    if (nfull > 0) {
+      mfma_tile(0, accA);
+      int t = 1;
+      for (; t + 1 < nfull; t += 2) {
+        mfma_tile(t, accB);
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+        interleave();
+        mfma_tile(t + 1, accA);
+        assign_epilogue<NF, false>(accB, best, second, btile, t, half, si.k_s);
+        interleave();
+      }
+      if (t < nfull) {
+        mfma_tile(t, accB);
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+        interleave();
+        assign_epilogue<NF, false>(accB, best, second, btile, t, half, si.k_s);
+      } else {
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+      }
+    }
+    if (nfull < ntiles) {  // the last tile has rows beyond k_s
+      mfma_tile(nfull, accA);
+      assign_epilogue<NF, true>(accA, best, second, btile, nfull, half, si.k_s);
+    }
+    // lanes l and l ^ 32 hold the same points over disjoint centroid rows
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      int brow = (best[f] & 27) | (4 * half);
+      const int ob = __shfl_xor(best[f], 32), os = __shfl_xor(second[f], 32);
+      const int ot = __shfl_xor(btile[f], 32), orow = __shfl_xor(brow, 32);
+      const int nsec = max(min(best[f], ob), max(second[f], os));
+      if (ob > best[f]) {
+        best[f] = ob;
+        btile[f] = ot;
+        brow = orow;
+      }
+      const int point = 32 * (fb + f) + col;
+      if (half == 0 && fb + f < f_hi && point < si.L_s) {
+        const size_t gp = (size_t)si.unit * N_idx + si.seg_start + point;
+        assign[gp] = btile[f] * 32 + brow;
+        const float gap = __int_as_float(best[f]) - (nsec > 0 ? __int_as_float(nsec) : 0.f);
+        if (gap < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+      }
     }
   }
 }
@@ -708,26 +828,21 @@ static void launch_assign(const T* xhat, const T* chat, int32_t* assign, int32_t
                           int S, int L, int kk, int N_idx, int segs, hipStream_t st) {
   const int Lmax = L < N_idx ? L : N_idx;
   if constexpr (sizeof(T) == 2) {
-    // tuning knob while the kernel shape is being chosen: WAVE_ASSIGN=<NF><NW>
-    static int variant = -1;
-    if (variant < 0) {
-      const char* e = getenv("WAVE_ASSIGN");
-      variant = e ? atoi(e) : 108;
+    // Centroids resident in LDS when a segment's padded rows fit (k = 512 at d = 128 is
+    // 136 KiB of the 160 KiB); two workgroups per segment keep the last round of
+    // workgroups short.  Otherwise the centroids are staged through LDS tile by tile.
+    const int kmax = kk < Lmax ? kk : Lmax;
+    const size_t resident_lds = (size_t)32 * ((kmax + 31) / 32) * (D * 2 + 16);
+    if (resident_lds <= 144 * 1024) {
+      const int pieces = Lmax > 2048 ? 2 : 1;
+      WAVE_LAUNCH("assign_mfma", (assign_resident_kernel<D, 1, 16>), segs * pieces, 1024, resident_lds, st,
+                  xhat, chat, assign, flag, nflag, S, L, kk, N_idx, pieces);
+    } else {
+      constexpr int PWG = 8 * 32;
+      const int wps = (Lmax + PWG - 1) / PWG;
+      WAVE_LAUNCH("assign_mfma", (assign_mfma_kernel<D, 1, 8>), segs * wps, 64 * 8, 0, st, xhat, chat,
+                  assign, flag, nflag, S, L, kk, N_idx, wps);
     }
-#define WAVE_ASSIGN_CASE(nf, nw)                                                                     \
-  case nf * 100 + nw: {                                                                               \
-    constexpr int PWG = nw * 32 * nf;                                                                \
-    const int wps = (Lmax + PWG - 1) / PWG;                                                          \
-    WAVE_LAUNCH("assign_mfma", (assign_mfma_kernel<D, nf, nw>), segs * wps, 64 * nw, 0, st, xhat,    \
-                chat, assign, flag, nflag, S, L, kk, N_idx, wps);                                    \
-    break;                                                                                           \
-  }
-    switch (variant) {
-      WAVE_ASSIGN_CASE(1, 4) WAVE_ASSIGN_CASE(1, 8) WAVE_ASSIGN_CASE(1, 16) WAVE_ASSIGN_CASE(2, 4)
-      WAVE_ASSIGN_CASE(2, 8) WAVE_ASSIGN_CASE(2, 16) WAVE_ASSIGN_CASE(4, 4) WAVE_ASSIGN_CASE(4, 8)
-      default: break;
-    }
-#undef WAVE_ASSIGN_CASE
   } else {
     const int wps = (Lmax + 255) / 256;
     WAVE_LAUNCH("assign_plain", (assign_plain_kernel<T, D>), segs * wps, 256, 0, st, xhat, chat,

@@ -39,6 +39,11 @@ CASES = {
     "bf16_many_heads": _small("llama8b_32k", name="bf16_many_heads", B=48, N=1300, Hq=8, Hkv=2,
                               segment_len=512, clusters_per_segment=32, n_local=40, n_components=64,
                               iters=3, retrieve_frac=0.1),
+    # 600 clusters per segment: more centroid rows than fit in LDS at once, so the assign step
+    # stages them tile by tile instead of keeping them resident
+    "bf16_big_k": _small("llama8b_32k", name="bf16_big_k", N=2900, Hq=4, Hkv=1, segment_len=1400,
+                         clusters_per_segment=600, n_local=60, n_components=512, iters=3,
+                         retrieve_frac=0.05),
     # d = 128 in f32 (32 lanes per row)
     "f32_d128": _small("tiny_f32", name="f32_d128", d=128, N=1500, Hq=2, Hkv=1, segment_len=512,
                        clusters_per_segment=32, n_local=30, iters=3, retrieve_abs=9),
