@@ -373,6 +373,7 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
 constexpr int CAND_CAP = 1024;
 constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
 constexpr int SEL_BINS = 2048; // buckets of the one-sweep histogram that starts the threshold search
+constexpr int SEL_HIST_MIN = 6144;  // below this many scores plain halving steps are as fast
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t u = __float_as_uint(f);
@@ -963,7 +964,7 @@ __device__ __forceinline__ int select_core(
     uint32_t khi = kmax + 1;   // count(>= khi) = 0 < r_eff
     int cnt_lo = nvalid, cnt_hi = 0;
     int it = 0;
-    {
+    if (npos > SEL_HIST_MIN) {
       // Stage 0, one sweep: count the valid keys by their upper 16 bits (sign,
       // exponent, 7 mantissa bits) in the SEL_BINS buckets below the maximum's
       // (everything lower shares bin 0); a scan from the top finds the bucket

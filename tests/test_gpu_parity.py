@@ -39,6 +39,10 @@ CASES = {
     "bf16_many_heads": _small("llama8b_32k", name="bf16_many_heads", B=48, N=1300, Hq=8, Hkv=2,
                               segment_len=512, clusters_per_segment=32, n_local=40, n_components=64,
                               iters=3, retrieve_frac=0.1),
+    # 392 query heads, 7 per KV head: the fused selection + retrieval kernel at GQA 7:1
+    "bf16_many_heads_g7": _small("qwen7b_64k_b64", name="bf16_many_heads_g7", B=28, N=900, Hq=14,
+                                 Hkv=2, segment_len=400, clusters_per_segment=24, n_local=300,
+                                 n_components=64, iters=2, retrieve_frac=0.1),
     # 600 clusters per segment: more centroid rows than fit in LDS at once, so the assign step
     # stages them tile by tile instead of keeping them resident
     "bf16_big_k": _small("llama8b_32k", name="bf16_big_k", N=2900, Hq=4, Hkv=1, segment_len=1400,
