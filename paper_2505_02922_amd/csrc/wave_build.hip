@@ -40,6 +40,15 @@ __device__ __forceinline__ SegInfo seg_info(int sg, int S, int L, int kk, int N_
   return r;
 }
 
+// a / b for many a and one b: with r the correctly rounded 1 / b, one multiply
+// and one fused residual correction give the correctly rounded quotient (the
+// classic Newton step on the quotient), three instructions instead of a full
+// division each.
+__device__ __forceinline__ double div_shared(double a, double b, double r) {
+  const double q = a * r;
+  return fma(fma(-q, b, a), r, q);
+}
+
 // ============================================================================
 // Segment mean (fp64).  One workgroup per segment; fixed summation order.
 // ============================================================================
@@ -98,18 +107,23 @@ __global__ __launch_bounds__(256) void normalise_kernel(const T* __restrict__ K,
     n2 = group_sum_f64<LPR>(n2);
     const double nrm = sqrt(n2);
     const double dv = nrm > 0.0 ? nrm : 1.0;
+    const double rdv = 1.0 / dv;
     T o[EPC];
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(x[e] / dv);
+    for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(div_shared(x[e], dv, rdv));
     store16(xhat + (size_t)row * D + sub * EPC, *reinterpret_cast<uint4*>(o));
   }
 }
 
 // ============================================================================
-// Seeded initial centroids: a Fisher-Yates shuffle kept as a sparse list of the
-// positions that differ from the identity (at most k of them).  Wave 0 of the
-// workgroup runs the k sequential draws, its lanes searching the list together;
-// then the whole workgroup copies the chosen rows.
+// Seeded initial centroids: the first k entries of a Fisher-Yates shuffle of the
+// segment's positions, without running the shuffle.  The generator's state
+// advances by a constant per draw, so draw i is a function of i alone, and so is
+// its target j_i = i + draw_i mod (L_s - i).  Step i picks the value found at
+// position j_i and leaves position i's value there.  The value at position p
+// just before step b (p >= b) is p itself unless an earlier step targeted p; if
+// t < b is the latest such step, it is the value position t held before step t.
+// Every thread follows that chain for its own i (chains are short: k << L).
 // ============================================================================
 constexpr int KMAX = 4096;
 
@@ -120,43 +134,24 @@ __global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
-  __shared__ int mpos[KMAX], mval[KMAX], chosen[KMAX];
-  const int lane = threadIdx.x & 63;
-  if (threadIdx.x < 64) {
-    uint64_t st = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s);
-    int nmoved = 0;
-    for (int i = 0; i < si.k_s; ++i) {
-      const uint64_t draw = splitmix64_next(st);
-      const int j = i + (int)(draw % (uint64_t)(si.L_s - i));
-      int at_j = -1, at_i = -1;
-      for (int t = lane; t < nmoved; t += 64) {
-        const int p = mpos[t];
-        if (p == j) at_j = t;
-        if (p == i) at_i = t;
-      }
-      // each position occurs at most once in the list: a max over lanes finds it
-      for (int off = 32; off >= 1; off >>= 1) {
-        at_j = max(at_j, __shfl_xor(at_j, off));
-        at_i = max(at_i, __shfl_xor(at_i, off));
-      }
-      const int vj = at_j >= 0 ? mval[at_j] : j;
-      const int vi = at_i >= 0 ? mval[at_i] : i;
-      __builtin_amdgcn_wave_barrier();
-      if (lane == 0) {
-        chosen[i] = vj;
-        if (j != i) {
-          if (at_j >= 0) {
-            mval[at_j] = vi;
-          } else {
-            mpos[nmoved] = j;
-            mval[nmoved] = vi;
-          }
-        }
-      }
-      if (j != i && at_j < 0) ++nmoved;
-      __threadfence_block();
-      __builtin_amdgcn_wave_barrier();
+  __shared__ int target[KMAX], chosen[KMAX];
+  const uint64_t st0 = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s);
+  for (int i = threadIdx.x; i < si.k_s; i += 256) {
+    uint64_t st = st0 + (uint64_t)i * 0x9E3779B97F4A7C15ull;  // state before draw i
+    const uint64_t draw = splitmix64_next(st);
+    target[i] = i + (int)(draw % (uint64_t)(si.L_s - i));
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < si.k_s; i += 256) {
+    int cur = target[i], bound = i;
+    while (true) {
+      int t = -1;
+      for (int u = 0; u < bound; ++u) t = target[u] == cur ? u : t;  // latest earlier step onto cur
+      if (t < 0) break;
+      cur = t;
+      bound = t;
     }
+    chosen[i] = cur;
   }
   __syncthreads();
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
@@ -690,8 +685,9 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   const double nrm = sqrt(n2);
   if (!(nrm > 0.0)) return;  // members cancel: keep the centroid
   T o[EPC];
+  const double rn = 1.0 / nrm;
 #pragma unroll
-  for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(acc[e] / nrm);
+  for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(div_shared(acc[e], nrm, rn));
   store16(chat + (size_t)gc * D + sub * EPC, *reinterpret_cast<uint4*>(o));
 }
 
