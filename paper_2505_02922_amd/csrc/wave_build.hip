@@ -520,7 +520,19 @@ __global__ __launch_bounds__(256) void refine_kernel(const T* __restrict__ xhat,
     for (int c = threadIdx.x; c < k_s; c += 256) {
       const T* row = Cs + (size_t)c * D;
       double a = 0.0;
-      for (int e = 0; e < D; ++e) a = fma(xs[e], to_f64(row[e]), a);
+      constexpr int EPC = Elem<T>::EPC;
+      for (int e0 = 0; e0 < D; e0 += 4 * EPC) {  // four 16-byte chunks in flight, summed in index order
+        uint4 raw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw[u] = load16(row + e0 + u * EPC);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          float f[EPC];
+          unpack<T>(raw[u], f);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) a = fma(xs[e0 + u * EPC + e], (double)f[e], a);
+        }
+      }
       if (a > bv) {  // c ascends within a thread, so strict > keeps the lowest index
         bv = a;
         bi = c;
@@ -663,7 +675,7 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   for (; i + 4 <= n; i += 4) {
     uint4 raw[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) raw[u] = load16(X + (size_t)ord[i + u] * D);
+    for (int u = 0; u < 4; ++u) raw[u] = load16_stream(X + (size_t)ord[i + u] * D);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float f[EPC];
