@@ -43,8 +43,12 @@ struct DenseLds {
   static constexpr size_t RED = sizeof(float) * NWV * (2 * G + 1);
   static constexpr size_t ZREF = sizeof(float) * G;
   static constexpr size_t TILE = sizeof(T) == 2 ? (size_t)NWV * 16 * PITCH : 0;
-  static constexpr size_t estimate_bytes = (ZW + SMEM + RED + ZREF + 15) / 16 * 16;
-  static constexpr size_t score_bytes = (estimate_bytes + TILE + 15) / 16 * 16;
+  // zw, red, zref live through all phases; the scoring tiles (phase A) and the
+  // per-wave partial sums (end of phase C) never live at the same time and share
+  // one region, which lets one more workgroup fit on a CU.
+  static constexpr size_t FIXED = (ZW + RED + ZREF + 15) / 16 * 16;
+  static constexpr size_t estimate_bytes = FIXED + (SMEM + 15) / 16 * 16;
+  static constexpr size_t score_bytes = FIXED + ((TILE > SMEM ? TILE : SMEM) + 15) / 16 * 16;
   float* zw;
   float* smem;
   float (*red)[2 * G + 1];
@@ -52,10 +56,10 @@ struct DenseLds {
   char* tile;
   __device__ __forceinline__ explicit DenseLds(char* base) {
     zw = reinterpret_cast<float*>(base);
-    smem = reinterpret_cast<float*>(base + ZW);
-    red = reinterpret_cast<float (*)[2 * G + 1]>(base + ZW + SMEM);
-    zref_s = reinterpret_cast<float*>(base + ZW + SMEM + RED);
-    tile = base + estimate_bytes;
+    red = reinterpret_cast<float (*)[2 * G + 1]>(base + ZW);
+    zref_s = reinterpret_cast<float*>(base + ZW + RED);
+    smem = reinterpret_cast<float*>(base + FIXED);
+    tile = base + FIXED;
   }
 };
 
