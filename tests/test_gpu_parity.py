@@ -245,8 +245,8 @@ def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
 
 @pytest.mark.parametrize("m,dup", [(3000, True), (20000, False), (40000, True), (70000, False)])
 def test_decode_many_clusters_hand_index(m, dup):
-    """Every size class of the selection kernel (scores in registers with 512 or
-    1024 threads, and the streaming fallback), with and without exact score ties."""
+    """Every size class of the selection (32-bit keys in LDS, slices + union, 16-bit keys
+    in LDS, and the streaming fallback), with and without exact score ties."""
     d, dtype, p, Hq, Hkv = 128, "bf16", 8, 2, 1
     arrs, n = _hand_index(m, d, dtype, p, seed=m, dup_scores=dup)
     # Dimensions whose plan has exactly m clusters: segments of 4 tokens with one
@@ -276,7 +276,9 @@ def test_decode_many_clusters_hand_index(m, dup):
 
 
 @pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),
-                                        ("llama8b_32k", [(0, 0), (0, 3), (0, 7)])])
+                                        ("llama8b_32k", [(0, 0), (0, 3), (0, 7)]),
+                                        ("llama8b_1m", [(0, 5)]),
+                                        ("qwen7b_64k_b64", [(0, 0), (63, 3)])])
 def test_full_size_workload_sampled_units(name, units):
     """The benchmark's own workloads at full size, in the launch configuration
     bench.py times: whole-batch GPU build and decode; the oracle builds and
