@@ -243,11 +243,13 @@ def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
                 perm=np.arange(n), k_perm=Kp, v_perm=Vp, k_steady=Ks, v_steady=Vs), n
 
 
-@pytest.mark.parametrize("m,dup", [(3000, True), (20000, False), (40000, True), (70000, False)])
-def test_decode_many_clusters_hand_index(m, dup):
+@pytest.mark.parametrize("m,dup,Hq", [(3000, True, 2), (20000, False, 2), (40000, True, 2),
+                                      (70000, False, 2), (20000, True, 7)])
+def test_decode_many_clusters_hand_index(m, dup, Hq):
     """Every size class of the selection (32-bit keys in LDS, slices + union, 16-bit keys
-    in LDS, and the streaming fallback), with and without exact score ties."""
-    d, dtype, p, Hq, Hkv = 128, "bf16", 8, 2, 1
+    in LDS, and the streaming fallback), with and without exact score ties; once with 7
+    query heads on the KV head (the estimation and steady work beside the slices at G = 7)."""
+    d, dtype, p, Hkv = 128, "bf16", 8, 1
     arrs, n = _hand_index(m, d, dtype, p, seed=m, dup_scores=dup)
     # Dimensions whose plan has exactly m clusters: segments of 4 tokens with one
     # cluster each.  The hand index then fills sizes/offsets as it likes (0..3 rows
