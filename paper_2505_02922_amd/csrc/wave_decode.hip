@@ -27,9 +27,10 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 //         relative to the largest score of the range, and sum_c s_c w_c;
 //      C  sum_c w_c VS_c.
 //    The result is one partial (max, sum, acc[d]) per head and range.  Clusters
-//    that a head later selects are taken out again by the selection kernel, which
-//    writes the same terms with a minus sign (the terms are bounded by the final
-//    normaliser, so the cancellation costs about one fp32 ulp of the output).
+//    that a head later selects are taken out again, with the same terms and a
+//    minus sign, by the fused selection kernel or by the retrieval kernel (the
+//    terms are bounded by the final normaliser, so the cancellation costs about
+//    one fp32 ulp of the output).
 // ============================================================================
 constexpr int DENSE_ROWS = 256;
 
@@ -367,12 +368,11 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
 
 // ============================================================================
 // 2. Top-r selection per query head.
-//    Radix select (4 passes of 8 bits) on the order-preserving integer image of
-//    the fp32 scores gives the r-th largest score tau.  Scores accumulate in
-//    fp32, so clusters within the accumulation error bound of tau are re-scored
-//    in fp64 and ranked exactly (ties to the lower id).  Outputs: a bitmap of
-//    the selected clusters, their ids ascending, the running token count of the
-//    selected clusters, and the reference score for the estimation zone.
+//    The r-th largest score tau is searched on the order-preserving integer
+//    image of the fp32 scores.  Scores accumulate in fp32, so clusters within the
+//    accumulation error bound of tau are re-scored in fp64 and ranked exactly
+//    (ties to the lower id).  Outputs: the selected ids in ascending order and
+//    their number; on the fused path also first rows and running token counts.
 // ============================================================================
 constexpr int CAND_CAP = 1024;
 constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
@@ -490,9 +490,10 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
   }
 }
 
-// NT threads per query head; with VPT > 0 every thread keeps VPT scores in
-// registers (m <= NT * VPT) and all passes run on them, with VPT == 0 the
-// scores are re-read from memory in every pass.
+// The fallback for more clusters than the LDS-keyed selections below take: NT
+// threads per query head; used with VPT == 0, where the scores are re-read from
+// memory in every pass (radix select, 4 passes of 8 bits, on the integer keys).
+// With VPT > 0 every thread would keep VPT scores in registers (m <= NT * VPT).
 template <typename T, int D, int NT, int VPT>
 __global__ __launch_bounds__(NT) void select_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
@@ -785,15 +786,16 @@ __global__ __launch_bounds__(NT) void select_kernel(
 }
 
 // ----------------------------------------------------------------------------
-// Selection with all m scores of a head held in registers (m <= NT * VPT).
-// Thread tid keeps clusters k * NT + tid, so the 64 lanes of a wave hold 64
-// consecutive clusters for every k: a ballot is two words of the bitmap, and
-// popcounts of ballots give counts and ranks without atomics.
-//   1. threshold: bisection on the order-preserving integer key for the
-//      r-th largest score (one ballot/popcount sweep and one barrier per bit);
+// Selection with the keys of all ranked positions in LDS (at most NT * VPT).
+// Thread tid owns positions k * NT + tid, so the 64 lanes of a wave hold 64
+// consecutive positions for every k, and popcounts of ballots give counts and
+// ranks in position order without atomics.
+//   1. threshold: a one-sweep histogram of the keys' upper bits, then halving of
+//      the value interval (one ballot/popcount sweep and one barrier per step)
+//      until few scores are left, which one wave finishes;
 //   2. guard band around it, fp64 ranking of the few scores inside;
-//   3. ids and running token counts in ascending id order from a small table of
-//      per-(k, wave) counts.
+//   3. ids (and, unless told to stop there, first rows and running token counts)
+//      in ascending order from a small table of per-(k, wave) counts.
 // ----------------------------------------------------------------------------
 // skeys: LDS for NT * ceil(m / NT) keys when LDSK.  If stage_cap > 0 the first rows
 // and running token counts of the first stage_cap selected clusters are also left
@@ -1526,9 +1528,9 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
 }
 
 // ============================================================================
-// 3a. Retrieval zone: one workgroup handles one slice of the tokens of the
-//     clusters selected by one query head, reading them in place from the
-//     cluster-contiguous K/V.
+// 3a. Retrieval zone: one workgroup handles a share of the clusters selected by
+//     one query head, reading their tokens in place from the cluster-contiguous
+//     K/V.
 // ============================================================================
 constexpr int GATHER_TILE = 256;  // tokens (and clusters) per pass of a workgroup
 
@@ -1823,13 +1825,6 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
                                     (size_t)slots * (D + 2));
 }
 
-// ----------------------------------------------------------------------------
-// Few heads over many clusters: ranking a slice is a chain of short dependent
-// steps that leaves the memory system idle, so the same launch also carries the
-// work that does not depend on the selection: the estimation terms of all
-// clusters (from the scores of the previous launch) and the steady zone.  The
-// slice workgroups have the lowest ids, so they are dispatched first.
-// ----------------------------------------------------------------------------
 // The meta-index pass with the steady-zone pieces as extra workgroups (few heads:
 // neither fills the chip alone, and a launch less is a few microseconds less).
 template <typename T, int D, int G>
