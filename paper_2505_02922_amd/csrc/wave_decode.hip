@@ -39,7 +39,8 @@ template <typename T, int D, int G, int NT>
 struct DenseLds {
   static constexpr int NWV = NT / 64, STR = D + 2;
   static constexpr int PITCH = D * 2 + 16;  // bf16 tile row pitch: 16 lanes of a k-block hit 64 distinct banks
-  static constexpr size_t ZW = sizeof(float) * NT * G;             // [cluster][head]: z, then w
+  static constexpr int ZG = (G + 3) / 4 * 4;                       // heads per row of zw, padded to whole float4s
+  static constexpr size_t ZW = sizeof(float) * NT * ZG;            // [cluster][head]: z, then w
   static constexpr size_t SMEM = sizeof(float) * NWV * G * STR;    // per-wave partial sums
   static constexpr size_t RED = sizeof(float) * NWV * (2 * G + 1);
   static constexpr size_t ZREF = sizeof(float) * G;
@@ -73,6 +74,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
                                              int unit, int bh0, int m, int c0, int nrows,
                                              const DenseLds<T, D, G, NT>& lds) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
+  constexpr int ZG = DenseLds<T, D, G, NT>::ZG;
   constexpr int U = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
@@ -136,7 +138,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
           if (cc < nrows) {
             const float val = sz[v] > 0 ? acc[v] : -INFINITY;
             z[(size_t)(bh0 + hj) * m + c0 + cc] = val;
-            zw[cc * G + hj] = val;
+            zw[cc * ZG + hj] = val;
           }
         }
       }
@@ -180,7 +182,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
         if (cc < nrows && sub < G) {
           const float v = sz[u] > 0 ? mine : -INFINITY;
           z[(size_t)(bh0 + sub) * m + c0 + cc] = v;
-          zw[cc * G + sub] = v;
+          zw[cc * ZG + sub] = v;
         }
       }
     }
@@ -210,6 +212,7 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
                                                const DenseLds<T, D, G, NT>& lds,
                                                float* __restrict__ part_head0, size_t head_stride) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
+  constexpr int ZG = DenseLds<T, D, G, NT>::ZG;
   constexpr int STR = D + 2;
   constexpr int UC = 4;  // rows in flight per group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -222,7 +225,7 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float mx = -INFINITY;
-    for (int i = threadIdx.x; i < nrows; i += NT) mx = fmaxf(mx, zw[i * G + g]);
+    for (int i = threadIdx.x; i < nrows; i += NT) mx = fmaxf(mx, zw[i * ZG + g]);
     zmax[g] = wave_max(mx);
   }
   if (lane == 0) {
@@ -241,8 +244,8 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
     const float ref2 = zmax[g] * scale_log2;
     float ls = 0.f;
     for (int i = threadIdx.x; i < nrows; i += NT) {
-      const float w = exp2f(fmaf(zw[i * G + g], scale_log2, -ref2));  // exp2(-inf) = 0
-      zw[i * G + g] = w;
+      const float w = exp2f(fmaf(zw[i * ZG + g], scale_log2, -ref2));  // exp2(-inf) = 0
+      zw[i * ZG + g] = w;
       ls = fmaf((float)su[i], w, ls);
     }
     lsum[g] = wave_sum_f(ls);
@@ -269,16 +272,14 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
       float vf[EPC], w[G];
       unpack<T>(raw[u], vf);
       if (cc < nrows) {
-        if constexpr (G % 4 == 0) {
+        float wp[ZG];
 #pragma unroll
-          for (int g4 = 0; g4 < G; g4 += 4) {
-            const float4 t = *reinterpret_cast<const float4*>(&zw[cc * G + g4]);
-            w[g4] = t.x; w[g4 + 1] = t.y; w[g4 + 2] = t.z; w[g4 + 3] = t.w;
-          }
-        } else {
-#pragma unroll
-          for (int g = 0; g < G; ++g) w[g] = zw[cc * G + g];
+        for (int g4 = 0; g4 < ZG; g4 += 4) {
+          const float4 t = *reinterpret_cast<const float4*>(&zw[cc * ZG + g4]);
+          wp[g4] = t.x; wp[g4 + 1] = t.y; wp[g4 + 2] = t.z; wp[g4 + 3] = t.w;
         }
+#pragma unroll
+        for (int g = 0; g < G; ++g) w[g] = wp[g];
       } else {
 #pragma unroll
         for (int g = 0; g < G; ++g) w[g] = 0.f;
@@ -323,7 +324,7 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
 }
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ q, const T* __restrict__ C,
+__global__ __launch_bounds__(256, 4) void dense_kernel(const T* __restrict__ q, const T* __restrict__ C,
                                                     const T* __restrict__ vsum,
                                                     const int32_t* __restrict__ sizes,
                                                     float* __restrict__ z, float* __restrict__ cn2part,
