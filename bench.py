@@ -219,6 +219,36 @@ def main() -> int:
         "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
     }
 
+    # ---------------- brute-force full attention on the same inputs (context) ----------------
+    fws = wb.workspace(wb.wave_full_attention_workspace(wl.B, wl.Hq, wl.N, wl.d), dev)
+    fout, flse = torch.empty_like(out), torch.empty_like(lse)
+    nfull = 10
+    for i in range(2):
+        wb.wave_full_attention_decode(queries[i], K, V, out=fout, lse=flse, ws=fws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(nfull):
+        wb.wave_full_attention_decode(queries[i % N_QUERY_SETS], K, V, out=fout, lse=flse, ws=fws)
+    e1.record()
+    torch.cuda.synchronize()
+    full_ms = e0.elapsed_time(e1) / nfull
+    full_bytes = 2 * units * wl.N * row
+    step(0)
+    wb.wave_full_attention_decode(queries[0], K, V, out=fout, lse=flse, ws=fws)
+    torch.cuda.synchronize()
+    full_info = {
+        "ms_per_step": round(full_ms, 4), "bytes_per_step": int(full_bytes),
+        "GBps": round(full_bytes / (full_ms * 1e-3) / 1e9, 1),
+        "wave_index_speedup": round(full_ms / ms_per_step, 2),
+        "max_abs_diff_of_outputs": float((out - fout).abs().max()),
+        "rel_l2_diff_of_outputs": float((out - fout).norm() / fout.norm()),
+        "note": "brute-force decode attention over all N tokens with this library's own kernel on the "
+                "same inputs; the difference of outputs is the approximation error of the method at "
+                "this budget on synthetic data, not a parity figure",
+    }
+    del fws
+
     # ---------------- CPU baseline: the oracle on a bounded sample ----------------
     cpu = None
     parity = None
@@ -287,6 +317,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "decode": decode_info,
         "build": build_info,
+        "full_attention": full_info,
         "parity": parity,
         "calibration": calib,
     }

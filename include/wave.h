@@ -137,6 +137,21 @@ wave_status wave_attention_decode(const void *q, const wave_index *ix, int Hq, i
                                   int32_t *selected, void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
+/* Full decode attention, the operation the wave index approximates (the
+ * attention equation of the background section): for every query head,
+ * o = softmax(q K^T / sqrt(d)) V over all N tokens of its KV head, by streaming
+ * K and V once per KV head with an online softmax (fp32 accumulation) and one
+ * log-sum-exp merge.  It is the same-hardware baseline for the decode step and
+ * the limit wave_attention_decode reaches when every cluster is retrieved.
+ *   q          DEVICE [B,Hq,d] dtype;  K, V  DEVICE [B,Hkv,N,d] dtype
+ *   out        DEVICE [B,Hq,d] fp32;   lse   DEVICE [B,Hq] fp32 (natural log)
+ *   workspace  DEVICE, 256-byte aligned, >= wave_full_attention_workspace(...)
+ * wave_full_attention_workspace returns 0 for unsupported shapes. */
+size_t wave_full_attention_workspace(int B, int Hq, int N, int d);
+wave_status wave_full_attention_decode(const void *q, const void *K, const void *V, int dtype, int B,
+                                       int Hq, int Hkv, int N, int d, float *out, float *lse,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Test hook, host only: the k_s distinct seed-token indices (relative to the
  * segment start) with which segment s of unit (b, h) starts k-means: the first
  * k_s entries of a Fisher-Yates shuffle of 0..L_s-1 driven by splitmix64 keyed

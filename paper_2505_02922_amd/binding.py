@@ -21,7 +21,8 @@ BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_pe
                 "v_steady")
 STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
                 4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
-EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode", "wave_init_indices",
+EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode",
+           "wave_full_attention_workspace", "wave_full_attention_decode", "wave_init_indices",
            "wave_kmeans_assign_step", "wave_calibration_copy", "wave_calibration_read",
            "wave_profile_enable", "wave_profile_read", "wave_status_string")
 
@@ -64,6 +65,9 @@ def lib() -> ctypes.CDLL:
         L.wave_index_build.argtypes = [vp, vp, ctypes.POINTER(wave_index), i32, u64, vp, sz, vp]
         L.wave_attention_decode.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32, vp,
                                             vp, vp, vp, sz, vp]
+        L.wave_full_attention_workspace.argtypes = [i32, i32, i32, i32]
+        L.wave_full_attention_decode.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
+                                                 sz, vp]
         L.wave_init_indices.argtypes = [u64, i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
         L.wave_kmeans_assign_step.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.wave_calibration_copy.argtypes = [vp, vp, sz, i32, vp]
@@ -76,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.wave_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = i32
+        L.wave_full_attention_workspace.restype = sz
         _lib = L
     return _lib
 
@@ -218,6 +223,33 @@ def wave_attention_decode(q: torch.Tensor, ix: Index, topk_clusters: int, n_sink
     if st != 0:
         raise WaveError(st, "wave_attention_decode")
     return out, lse, selected
+
+
+def wave_full_attention_workspace(B: int, Hq: int, N: int, d: int) -> int:
+    return int(lib().wave_full_attention_workspace(B, Hq, N, d))
+
+
+def wave_full_attention_decode(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                               out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                               ws: Optional[torch.Tensor] = None):
+    """q [B, Hq, d], K and V [B, Hkv, N, d], device tensors of one dtype.  Returns
+    (out [B,Hq,d] f32, lse [B,Hq] f32) of full attention over all N tokens."""
+    assert q.is_cuda and K.is_cuda and V.is_cuda and q.dtype == K.dtype == V.dtype and K.shape == V.shape
+    q, K, V = q.contiguous(), K.contiguous(), V.contiguous()
+    B, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    if out is None:
+        out = torch.empty(B, Hq, d, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    if ws is None:
+        ws = workspace(wave_full_attention_workspace(B, Hq, N, d), q.device)
+    st = lib().wave_full_attention_decode(q.data_ptr(), K.data_ptr(), V.data_ptr(), _dtype_code(q.dtype),
+                                          B, Hq, Hkv, N, d, out.data_ptr(), lse.data_ptr(),
+                                          ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_full_attention_decode")
+    return out, lse
 
 
 def wave_init_indices(seed: int, b: int, h: int, s: int, L_s: int, k_s: int) -> List[int]:

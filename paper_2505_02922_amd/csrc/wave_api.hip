@@ -218,6 +218,27 @@ wave_status wave_attention_decode(const void* q, const wave_index* ix, int Hq, i
                        static_cast<hipStream_t>(hip_stream));
 }
 
+size_t wave_full_attention_workspace(int B, int Hq, int N, int d) {
+  if (B < 1 || Hq < 1 || N < 1 || (d != 64 && d != 128)) return 0;
+  return align_up(sizeof(float) * (size_t)B * Hq * full_attention_chunks(N) * (d + 2));
+}
+
+wave_status wave_full_attention_decode(const void* q, const void* K, const void* V, int dtype, int B,
+                                       int Hq, int Hkv, int N, int d, float* out, float* lse,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (dtype != WAVE_F32 && dtype != WAVE_BF16) return WAVE_ERR_DTYPE;
+  if (!q || !K || !V || !out || !lse || B < 1 || Hkv < 1 || N < 1) return WAVE_ERR_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return WAVE_ERR_ARG;
+  if (d != 64 && d != 128) return WAVE_ERR_SHAPE;
+  if (Hq < Hkv || Hq % Hkv != 0 || Hq / Hkv > 8) return WAVE_ERR_SHAPE;
+  if ((long long)B * Hkv * full_attention_chunks(N) >= (1ll << 31)) return WAVE_ERR_SHAPE;
+  const size_t need = wave_full_attention_workspace(B, Hq, N, d);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+    return WAVE_ERR_WORKSPACE;
+  return launch_full_attention(q, K, V, dtype, B, Hq, Hkv, N, d, out, lse, workspace,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
 wave_status wave_init_indices(uint64_t seed, int b, int h, int s, int L_s, int k_s, int32_t* out) {
   if (!out || L_s < 1 || k_s < 1 || k_s > L_s) return WAVE_ERR_ARG;
   // Fisher-Yates on a sparse image of the array: only positions that were

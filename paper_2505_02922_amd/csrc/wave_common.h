@@ -202,6 +202,12 @@ BuildGeom build_geometry(const wave_index& ix);
 
 wave_status launch_decode(const void* q, const wave_index& ix, int Hq, int topk, float* out,
                           float* lse, int32_t* selected, void* ws, hipStream_t st);
+// Full attention over all N tokens: chunks of FULL_ATTN_ROWS tokens per workgroup.
+constexpr int FULL_ATTN_ROWS = 1024;
+inline int full_attention_chunks(int N) { return (N + FULL_ATTN_ROWS - 1) / FULL_ATTN_ROWS; }
+wave_status launch_full_attention(const void* q, const void* K, const void* V, int dtype, int B, int Hq,
+                                  int Hkv, int N, int d, float* out, float* lse, void* ws,
+                                  hipStream_t st);
 wave_status launch_build(const void* K, const void* V, const wave_index& ix, int iters,
                          uint64_t seed, void* ws, hipStream_t st);
 wave_status launch_assign_step(const void* xhat, const void* chat, int dtype, int L_s, int k_s, int d,

@@ -2190,6 +2190,46 @@ static wave_status decode_td(int G, const void* q, const wave_index& ix, int Hq,
   }
 }
 
+// Full attention = the steady-zone kernel over all N rows of K and V, then the merge.
+template <typename T, int D, int G>
+static wave_status full_tdg(const void* q, const void* K, const void* V, int B, int Hkv, int N,
+                            float* out, float* lse, void* ws, hipStream_t st) {
+  const int units = B * Hkv, heads = units * G, chunks = full_attention_chunks(N);
+  float* part = static_cast<float*>(ws);
+  const float scale_log2 = kLog2e / sqrtf((float)D);
+  WAVE_LAUNCH("full_attention", (steady_kernel<T, D, G>), units * chunks, 256, 0, st,
+              static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), Hkv, N,
+              chunks, FULL_ATTN_ROWS, chunks, 0, scale_log2, part);
+  WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, chunks, out, lse);
+  return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+}
+
+template <typename T, int D>
+static wave_status full_td(int G, const void* q, const void* K, const void* V, int B, int Hkv, int N,
+                           float* out, float* lse, void* ws, hipStream_t st) {
+  switch (G) {
+#define WAVE_G(n) \
+  case n: return full_tdg<T, D, n>(q, K, V, B, Hkv, N, out, lse, ws, st);
+    WAVE_G(1) WAVE_G(2) WAVE_G(3) WAVE_G(4) WAVE_G(5) WAVE_G(6) WAVE_G(7) WAVE_G(8)
+#undef WAVE_G
+    default: return WAVE_ERR_SHAPE;
+  }
+}
+
+wave_status launch_full_attention(const void* q, const void* K, const void* V, int dtype, int B, int Hq,
+                                  int Hkv, int N, int d, float* out, float* lse, void* ws,
+                                  hipStream_t st) {
+  const int G = Hq / Hkv;
+  if (dtype == WAVE_BF16) {
+    if (d == 128) return full_td<bf16_t, 128>(G, q, K, V, B, Hkv, N, out, lse, ws, st);
+    if (d == 64) return full_td<bf16_t, 64>(G, q, K, V, B, Hkv, N, out, lse, ws, st);
+  } else {
+    if (d == 128) return full_td<float, 128>(G, q, K, V, B, Hkv, N, out, lse, ws, st);
+    if (d == 64) return full_td<float, 64>(G, q, K, V, B, Hkv, N, out, lse, ws, st);
+  }
+  return WAVE_ERR_SHAPE;
+}
+
 wave_status launch_decode(const void* q, const wave_index& ix, int Hq, int topk, float* out,
                           float* lse, int32_t* selected, void* ws, hipStream_t st) {
   const int G = Hq / ix.Hkv;

@@ -110,6 +110,18 @@ def test_entry_points_refuse_bad_arguments_on_the_host():
     assert dec(8, 4, 4, 64, dws - 1) == 4
     # a larger topk needs a larger workspace than the one planned for topk = 4
     assert dec(8, 60, 4, 64, dws) == 4
+    # full attention: workspace size formula, bad shapes, small workspace
+    need = L.wave_full_attention_workspace(2, 8, 5000, 128)
+    assert need >= 4 * 2 * 8 * 5 * 130 and need % 256 == 0
+    assert L.wave_full_attention_workspace(2, 8, 5000, 96) == 0
+    full = lambda dt, Hq, Hkv, d, wsb: L.wave_full_attention_decode(fake, fake, fake, dt, 2, Hq, Hkv,
+                                                                    5000, d, fake, fake, fake, wsb, None)
+    assert full(9, 8, 2, 128, need) == 3
+    assert full(1, 8, 3, 128, need) == 2
+    assert full(1, 8, 2, 96, need) == 2
+    assert full(1, 8, 2, 128, need - 1) == 4
+    assert L.wave_full_attention_decode(None, fake, fake, 1, 2, 8, 2, 5000, 128, fake, fake, fake, need,
+                                        None) == 1
     # assign-step hook
     assert L.wave_kmeans_assign_step(fake, fake, 1, 100, 200, 128, fake, fake, 1 << 20, None) == 2
     assert L.wave_kmeans_assign_step(fake, fake, 7, 100, 10, 128, fake, fake, 1 << 20, None) == 3

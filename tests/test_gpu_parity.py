@@ -314,3 +314,36 @@ def test_full_size_workload_sampled_units(name, units):
             pu.check_outputs(out[b, hq].cpu().numpy(), lse[b, hq:hq + 1].cpu().numpy(), o,
                              np.array([l]), wl.dtype, f"{tag} hq={hq}")
             pu.check_selected(sel[b, hq].cpu().numpy(), s, parts["z"], f"{tag} hq={hq}")
+
+
+@pytest.mark.parametrize("case", ["tiny_f32", "bf16_g4", "bf16_g7", "bf16_d64", "f32_d128"])
+def test_full_attention_matches_oracle(case):
+    """The brute-force decode kernel (the attention equation over all N tokens)
+    against the oracle's full attention, every head."""
+    wl = CASES[case]
+    K, V = synth.make_kv(wl)
+    q = synth.make_queries(wl, 1)
+    out, lse = wb.wave_full_attention_decode(q.cuda(), K.cuda(), V.cuda())
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    Kn, Vn, qn = K.double().numpy(), V.double().numpy(), q.double().numpy()
+    for b in range(wl.B):
+        for hq in range(wl.Hq):
+            o, l = wo.full_attention(qn[b, hq], Kn[b, hq // wl.G], Vn[b, hq // wl.G])
+            pu.check_outputs(out[b, hq], lse[b, hq:hq + 1], o, np.array([l]), wl.dtype,
+                             f"{case} full b={b} hq={hq}")
+
+
+def test_full_attention_is_the_limit_of_the_wave_decode():
+    """Retrieving every cluster reproduces what the brute-force kernel computes."""
+    wl = CASES["bf16_g4"]
+    K, V = synth.make_kv(wl)
+    q = synth.make_queries(wl, 2).cuda()
+    Kc, Vc = K.cuda(), V.cuda()
+    ix = wb.wave_index_build(Kc, Vc, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
+                             wl.iters, 0)
+    o1, l1, _ = wb.wave_attention_decode(q, ix, ix.m)
+    o2, l2 = wb.wave_full_attention_decode(q, Kc, Vc)
+    torch.cuda.synchronize()
+    assert float((o1 - o2).abs().max()) < 2e-5
+    assert float((l1 - l2).abs().max()) < 2e-5
