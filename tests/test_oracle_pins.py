@@ -239,6 +239,61 @@ def test_jensen_bound_and_monotone_in_r():
         prev = lse
 
 
+def test_estimation_budget_by_hand():
+    # One steady token, three clusters with centroid logits 2, 0, -2 (d = 4, scale 1/2),
+    # nothing retrieved, budget of one estimated cluster: only the best-ranked one counts.
+    q = np.array([2.0, 0, 0, 0])
+    Ks, Vs = np.array([[0.0, 0, 0, 0]]), np.array([[1.0, 1, 1, 1]])
+    C = np.array([[-2.0, 0, 0, 0], [2.0, 0, 0, 0], [0.0, 0, 0, 0]])
+    VS = np.array([[0.0, 5, 0, 0], [3.0, 0, 0, 0], [0.0, 0, 7, 0]])
+    sizes = np.array([5, 3, 2])
+    plan = wo.make_plan(11, 1, 0, 10, 3)
+    ix = wo.UnitIndex(plan, "f32", C, VS, sizes, np.array([0, 5, 8, 10]), np.arange(10),
+                      np.zeros((10, 4)), np.zeros((10, 4)), Ks, Vs, np.zeros(0, dtype=np.int64))
+    o, lse, _ = wo.decode_unit(q, ix, 0, est_clusters=1)
+    Z = 1.0 + 3 * math.exp(2.0)
+    want = (np.array([1.0, 1, 1, 1]) + math.exp(2.0) * VS[1]) / Z
+    assert np.allclose(o, want, atol=1e-15) and abs(lse - math.log(Z)) < 1e-14
+    o, lse, _ = wo.decode_unit(q, ix, 0, est_clusters=2)    # clusters 1 and 2, not 0
+    Z = 1.0 + 3 * math.exp(2.0) + 2 * math.exp(0.0)
+    want = (np.array([1.0, 1, 1, 1]) + math.exp(2.0) * VS[1] + VS[2]) / Z
+    assert np.allclose(o, want, atol=1e-15) and abs(lse - math.log(Z)) < 1e-14
+    o, lse, sel = wo.decode_unit(q, ix, 1, est_clusters=1)  # cluster 1 retrieved, 2 estimated
+    assert sel.tolist() == [1]
+
+
+def test_estimation_budget_limits():
+    K, V, q, plan, ix, _, _ = _tiny_unit(seed=21)
+    nonempty = int((ix.sizes > 0).sum())
+    for r in (0, 4, 9):
+        o_all, l_all, s_all = wo.decode_unit(q, ix, r)
+        # a budget that covers every other cluster is the method as stated
+        for e in (nonempty - r, nonempty, 10 ** 6):
+            o, l, s = wo.decode_unit(q, ix, r, est_clusters=e)
+            assert np.array_equal(o, o_all) and l == l_all and np.array_equal(s, s_all)
+        # no estimation: exact softmax attention over the steady and retrieved tokens alone
+        o0, l0, s0 = wo.decode_unit(q, ix, r, est_clusters=0)
+        rows = (np.concatenate([np.arange(ix.offsets[c], ix.offsets[c + 1]) for c in s0])
+                if s0.size else np.zeros(0, dtype=np.int64))
+        Ksub = np.concatenate([ix.k_steady, ix.k_perm[rows]])
+        Vsub = np.concatenate([ix.v_steady, ix.v_perm[rows]])
+        o_ref, l_ref = wo.full_attention(q, Ksub, Vsub)
+        assert np.allclose(o0, o_ref, atol=1e-13) and abs(l0 - l_ref) < 1e-12
+        # every estimated cluster adds positive mass: lse grows with the budget, up to the full one
+        prev = l0
+        for e in range(1, nonempty - r + 1, 3):
+            parts = {}
+            _, l, _ = wo.decode_unit(q, ix, r, parts, est_clusters=e)
+            assert l >= prev - 1e-13 and l <= l_all + 1e-13
+            assert parts["est"].size == e
+            total = parts["w_steady"].sum() + parts["w_retr"].sum() + parts["w_est"].sum()
+            assert abs(total - 1.0) < 1e-13
+            # the estimated clusters are the best-ranked ones after the retrieved
+            order, z = wo.rank_clusters(q, ix.centroids, ix.sizes)
+            assert set(parts["est"].tolist()) == set(order[min(r, nonempty):min(r, nonempty) + e].tolist())
+            prev = l
+
+
 def dataclasses_replace(ix, **kw):
     return dataclasses.replace(ix, **kw)
 
