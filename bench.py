@@ -248,6 +248,29 @@ def main() -> int:
                 "this budget on synthetic data, not a parity figure",
     }
     del fws
+    # zone budgets (estimation zone restricted to a share of the clusters; untuned launches)
+    budgets = []
+    for share in (0.0, 0.232):
+        e = int(round(share * ix.m))
+        bws2 = wb.workspace(wb.wave_attention_decode_budget_workspace(ix, wl.Hq, r, e), dev)
+        bout, blse = torch.empty_like(out), torch.empty_like(lse)
+        for i in range(2):
+            wb.wave_attention_decode_budget(queries[0], ix, r, e, out=bout, lse=blse, ws=bws2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(10):
+            wb.wave_attention_decode_budget(queries[0], ix, r, e, out=bout, lse=blse, ws=bws2)
+        e1.record()
+        torch.cuda.synchronize()
+        budgets.append({"estimated_share_of_clusters": share, "est_clusters": e,
+                        "ms_per_step": round(e0.elapsed_time(e1) / 10, 4),
+                        "rel_l2_diff_to_full_attention": float((bout - fout).norm() / fout.norm())})
+        del bws2
+    budgets.append({"estimated_share_of_clusters": "all other clusters", "est_clusters": ix.m - r,
+                    "ms_per_step": round(ms_per_step, 4),
+                    "rel_l2_diff_to_full_attention": full_info["rel_l2_diff_of_outputs"]})
+    full_info["zone_budgets"] = budgets
 
     # ---------------- CPU baseline: the oracle on a bounded sample ----------------
     cpu = None

@@ -137,6 +137,25 @@ wave_status wave_attention_decode(const void *q, const wave_index *ix, int Hq, i
                                   int32_t *selected, void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
+/* The decode step with a budget for the estimation zone, as in the paper's
+ * evaluation (parameter paragraph: an estimation zone of 23.2 % of the clusters
+ * so that the three zones cover about a quarter of the context) and its
+ * ablation without estimation: of the clusters that are not retrieved, only the
+ * est_clusters best-scoring ones (same ranking and tie rule as the retrieval)
+ * enter through their centroid, size and value sum; the others are ignored.
+ * est_clusters < 0, or a budget that reaches every cluster, is
+ * wave_attention_decode itself; est_clusters = 0 leaves the exact zones only.
+ * Same arguments otherwise; the workspace size comes from
+ * wave_attention_decode_budget_workspace (0 if the arguments are invalid).
+ * This path is not tuned: scores, two selections, steady, retrieval,
+ * estimation and merge are launches of their own. */
+size_t wave_attention_decode_budget_workspace(const wave_index *ix, int Hq, int topk_clusters,
+                                              int est_clusters);
+wave_status wave_attention_decode_budget(const void *q, const wave_index *ix, int Hq,
+                                         int topk_clusters, int est_clusters, int n_sink,
+                                         int n_local, float *out, float *lse, int32_t *selected,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Full decode attention, the operation the wave index approximates (the
  * attention equation of the background section): for every query head,
  * o = softmax(q K^T / sqrt(d)) V over all N tokens of its KV head, by streaming

@@ -22,6 +22,7 @@ BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_pe
 STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
                 4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
 EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode",
+           "wave_attention_decode_budget_workspace", "wave_attention_decode_budget",
            "wave_full_attention_workspace", "wave_full_attention_decode", "wave_init_indices",
            "wave_kmeans_assign_step", "wave_calibration_copy", "wave_calibration_read",
            "wave_profile_enable", "wave_profile_read", "wave_status_string")
@@ -65,6 +66,9 @@ def lib() -> ctypes.CDLL:
         L.wave_index_build.argtypes = [vp, vp, ctypes.POINTER(wave_index), i32, u64, vp, sz, vp]
         L.wave_attention_decode.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32, vp,
                                             vp, vp, vp, sz, vp]
+        L.wave_attention_decode_budget_workspace.argtypes = [ctypes.POINTER(wave_index), i32, i32, i32]
+        L.wave_attention_decode_budget.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32,
+                                                   i32, vp, vp, vp, vp, sz, vp]
         L.wave_full_attention_workspace.argtypes = [i32, i32, i32, i32]
         L.wave_full_attention_decode.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                                  sz, vp]
@@ -81,6 +85,7 @@ def lib() -> ctypes.CDLL:
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = i32
         L.wave_full_attention_workspace.restype = sz
+        L.wave_attention_decode_budget_workspace.restype = sz
         _lib = L
     return _lib
 
@@ -222,6 +227,38 @@ def wave_attention_decode(q: torch.Tensor, ix: Index, topk_clusters: int, n_sink
                                      ws.data_ptr(), ws.numel(), _stream())
     if st != 0:
         raise WaveError(st, "wave_attention_decode")
+    return out, lse, selected
+
+
+def wave_attention_decode_budget_workspace(ix: Index, Hq: int, topk_clusters: int, est_clusters: int) -> int:
+    return int(lib().wave_attention_decode_budget_workspace(ctypes.byref(ix.c), Hq, topk_clusters,
+                                                            est_clusters))
+
+
+def wave_attention_decode_budget(q: torch.Tensor, ix: Index, topk_clusters: int, est_clusters: int,
+                                 out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                                 selected: Optional[torch.Tensor] = None,
+                                 ws: Optional[torch.Tensor] = None, want_selected: bool = False):
+    """As wave_attention_decode, with only the est_clusters best-ranked clusters after the
+    retrieved ones estimated (negative: all of them; 0: none)."""
+    assert q.is_cuda and q.dtype == ix.dtype
+    q = q.contiguous()
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty(B, Hq, d, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    if selected is None and want_selected:
+        selected = torch.empty(B, Hq, max(topk_clusters, 1), dtype=torch.int32, device=q.device)
+    if ws is None:
+        ws = workspace(wave_attention_decode_budget_workspace(ix, Hq, topk_clusters, est_clusters), q.device)
+    st = lib().wave_attention_decode_budget(
+        q.data_ptr(), ctypes.byref(ix.c), Hq, topk_clusters, est_clusters, ix.n_sink, ix.n_local,
+        out.data_ptr(), lse.data_ptr(),
+        selected.data_ptr() if selected is not None and topk_clusters > 0 else None,
+        ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_attention_decode_budget")
     return out, lse, selected
 
 

@@ -218,6 +218,38 @@ wave_status wave_attention_decode(const void* q, const wave_index* ix, int Hq, i
                        static_cast<hipStream_t>(hip_stream));
 }
 
+static wave_status check_decode_args(const void* q, const wave_index* ix, int Hq, int topk_clusters,
+                                     int n_sink, int n_local, const float* out, const float* lse) {
+  wave_status st = check_dims(ix);
+  if (st != WAVE_OK) return st;
+  if (!q || !out || !lse || topk_clusters < 0) return WAVE_ERR_ARG;
+  if (!aligned16(q)) return WAVE_ERR_ARG;
+  if (Hq < ix->Hkv || Hq % ix->Hkv != 0 || Hq / ix->Hkv > 8) return WAVE_ERR_SHAPE;
+  if (!planned_fields_match(*ix)) return WAVE_ERR_SHAPE;
+  if (n_sink != ix->n_sink || n_local != ix->n_local) return WAVE_ERR_STEADY_MISMATCH;
+  return check_index_buffers(*ix);
+}
+
+size_t wave_attention_decode_budget_workspace(const wave_index* ix, int Hq, int topk_clusters,
+                                              int est_clusters) {
+  if (check_dims(ix) != WAVE_OK || !planned_fields_match(*ix) || topk_clusters < 0) return 0;
+  if (Hq < ix->Hkv || Hq % ix->Hkv != 0 || Hq / ix->Hkv > 8) return 0;
+  return budget_geometry(*ix, Hq, topk_clusters, est_clusters).total;
+}
+
+wave_status wave_attention_decode_budget(const void* q, const wave_index* ix, int Hq, int topk_clusters,
+                                         int est_clusters, int n_sink, int n_local, float* out,
+                                         float* lse, int32_t* selected, void* workspace,
+                                         size_t workspace_bytes, void* hip_stream) {
+  const wave_status st = check_decode_args(q, ix, Hq, topk_clusters, n_sink, n_local, out, lse);
+  if (st != WAVE_OK) return st;
+  const size_t need = budget_geometry(*ix, Hq, topk_clusters, est_clusters).total;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+    return WAVE_ERR_WORKSPACE;
+  return launch_decode_budget(q, *ix, Hq, topk_clusters, est_clusters, out, lse, selected, workspace,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
 size_t wave_full_attention_workspace(int B, int Hq, int N, int d) {
   if (B < 1 || Hq < 1 || N < 1 || (d != 64 && d != 128)) return 0;
   return align_up(sizeof(float) * (size_t)B * Hq * full_attention_chunks(N) * (d + 2));

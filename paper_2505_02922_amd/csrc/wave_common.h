@@ -202,6 +202,22 @@ BuildGeom build_geometry(const wave_index& ix);
 
 wave_status launch_decode(const void* q, const wave_index& ix, int Hq, int topk, float* out,
                           float* lse, int32_t* selected, void* ws, hipStream_t st);
+// Decode with a budget for the estimation zone (the e best-ranked clusters after
+// the r retrieved ones are estimated, the rest ignored): launch geometry and
+// workspace layout.  delegate: the budget covers every cluster, the plain decode runs.
+struct BudgetGeom {
+  int delegate;
+  int r, k2;                        // retrieved clusters, retrieved + estimated clusters
+  int rcap1, rcap2, mwords;
+  int sliced1, sliced2, nslices, slice_len;
+  int score_chunks, steady_rows, steady_chunks, gather_chunks, est_chunks, slots;
+  size_t off_z, off_cn2, off_ids1, off_ids2, off_nsel1, off_nsel2, off_pref, off_srow, off_bitmap,
+      off_zref, off_slice_ids, off_slice_z, off_part, total;
+};
+BudgetGeom budget_geometry(const wave_index& ix, int Hq, int topk, int est_clusters);
+wave_status launch_decode_budget(const void* q, const wave_index& ix, int Hq, int topk, int est_clusters,
+                                 float* out, float* lse, int32_t* selected, void* ws, hipStream_t st);
+
 // Full attention over all N tokens: chunks of FULL_ATTN_ROWS tokens per workgroup.
 constexpr int FULL_ATTN_ROWS = 1024;
 inline int full_attention_chunks(int N) { return (N + FULL_ATTN_ROWS - 1) / FULL_ATTN_ROWS; }

@@ -1326,6 +1326,17 @@ struct AttnState {
     }
   }
 
+  // For rows_given only: no queries needed.
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      mx[g] = kNegBig;
+      l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
+    }
+  }
+
   // U rows whose logits s[g][u] (base-2 units) are known and which count mult[u]
   // times in the normaliser: a cluster standing for its members.
   // NEG: the rows are taken out again (terms added elsewhere for every cluster).
@@ -1643,14 +1654,76 @@ __global__ __launch_bounds__(256) void gather_kernel(
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
 }
 
+// Estimation zone with a budget: the clusters of the (ascending) list ids2 that
+// are not in the (ascending) list ids1 enter with their centroid's score as the
+// logit, their size as the multiplicity and their value sum as the value.
+// Workgroup `chunk` of a head takes an equal share of the positions of ids2.
+constexpr int EST_STAGE = 4096;  // retrieved ids kept in LDS for the membership test
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void est_gather_kernel(
+    const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
+    const int32_t* __restrict__ ids1_all, const int32_t* __restrict__ nsel1_arr,
+    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
+    int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
+    float* __restrict__ part) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
+  const int bh = blockIdx.x / chunks, chunk = blockIdx.x - bh * chunks;
+  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+  const int unit = b * Hkv + hq / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  __shared__ int s_ids1[EST_STAGE];
+  __shared__ float smem[4 * (D + 2)];
+  const int nsel2 = nsel2_arr[bh], nsel1 = nsel1_arr[bh];
+  const int32_t* ids2 = ids2_all + (size_t)bh * rcap2;
+  const int32_t* ids1g = ids1_all + (size_t)bh * rcap1;
+  const bool staged = nsel1 <= EST_STAGE;
+  if (staged)
+    for (int i = threadIdx.x; i < nsel1; i += 256) s_ids1[i] = ids1g[i];
+  __syncthreads();
+  const int32_t* ids1 = staged ? s_ids1 : ids1g;
+  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const float* zz = z + (size_t)bh * m;
+  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+  const int c_lo = (int)((long long)chunk * nsel2 / chunks), c_hi = (int)((long long)(chunk + 1) * nsel2 / chunks);
+  AttnState<T, D, 1> st;
+  st.reset();
+  for (int i = c_lo + grp; i < c_hi; i += GROUPS * U) {
+    uint4 vraw[U];
+    float sc[1][U], mult[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ii = i + u * GROUPS;
+      const bool on = ii < c_hi;
+      const int id = ids2[on ? ii : i];
+      // member of the retrieved list?  (largest a with ids1[a] <= id)
+      bool retrieved = false;
+      if (nsel1 > 0) {
+        int a = 0, e = nsel1;
+        while (e - a > 1) {
+          const int mid = (a + e) >> 1;
+          if (ids1[mid] <= id) a = mid; else e = mid;
+        }
+        retrieved = ids1[a] == id;
+      }
+      vraw[u] = load16(VSu + (size_t)id * D);
+      sc[0][u] = (on && !retrieved) ? zz[id] * scale_log2 : -INFINITY;
+      mult[u] = (float)(off[id + 1] - off[id]);
+    }
+    st.template rows_given<U>(sc, mult, vraw);
+  }
+  merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + slot0 + chunk) * (D + 2), 0);
+}
+
 constexpr int MERGE_THREADS = 1024;
 
 template <int D>
 __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(const float* __restrict__ part, int slots,
-                                                              float* __restrict__ out,
+                                                              int slot_stride, float* __restrict__ out,
                                                               float* __restrict__ lse) {
-  const int bh = blockIdx.x;
-  merge_head<D, MERGE_THREADS>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D,
+  const int bh = blockIdx.x;  // a head's partials are slot_stride slots apart; the first `slots` count
+  merge_head<D, MERGE_THREADS>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
                                lse + bh);
 }
 
@@ -2174,7 +2247,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
   if (!g.fused)  // the fused kernel normalises each head itself
     WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part,
-                g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots, out, lse);
+                g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots, g.slots, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
@@ -2184,6 +2257,149 @@ static wave_status decode_td(int G, const void* q, const wave_index& ix, int Hq,
   switch (G) {
 #define WAVE_G(n) \
   case n: return decode_tdg<T, D, n>(q, ix, Hq, topk, out, lse, selected, ws, st);
+    WAVE_G(1) WAVE_G(2) WAVE_G(3) WAVE_G(4) WAVE_G(5) WAVE_G(6) WAVE_G(7) WAVE_G(8)
+#undef WAVE_G
+    default: return WAVE_ERR_SHAPE;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Decode with an estimation budget.  Not a tuned path: the scores alone, two
+// selections (the r best and the r + e best), then the steady zone, the retrieved
+// tokens, the estimated clusters and the merge as launches of their own.
+// ---------------------------------------------------------------------------
+BudgetGeom budget_geometry(const wave_index& ix, int Hq, int topk, int est_clusters) {
+  BudgetGeom g{};
+  const int m = ix.m, units = ix.B * ix.Hkv, heads = ix.B * Hq, D = ix.d;
+  const int r = m > 0 ? (topk < m ? topk : m) : 0;
+  if (m == 0 || est_clusters < 0 || (long long)r + est_clusters >= m) {
+    g.delegate = 1;
+    g.total = decode_geometry(ix, Hq, topk).total;
+    return g;
+  }
+  g.r = r;
+  g.k2 = r + est_clusters;
+  g.rcap1 = r > 0 ? r : 1;
+  g.rcap2 = g.k2 > 0 ? g.k2 : 1;
+  g.mwords = (m + 31) / 32;
+  g.slice_len = 8192;
+  g.nslices = (m + g.slice_len - 1) / g.slice_len;
+  auto sliced = [&](int k) {
+    return (k > 0 && m > 16384 && g.nslices <= 64 && (long long)g.nslices * k <= 16384) ? 1 : 0;
+  };
+  g.sliced1 = sliced(r);
+  g.sliced2 = sliced(g.k2);
+  g.score_chunks = (m + DENSE_ROWS - 1) / DENSE_ROWS;
+  g.steady_rows = units >= 64 ? 256 : 64;
+  g.steady_chunks = ix.p > 0 ? (ix.p + g.steady_rows - 1) / g.steady_rows : 0;
+  double expect = (double)r * (double)ix.N_idx / (double)m;
+  int gc = (int)((expect + GATHER_TILE - 1) / GATHER_TILE);
+  gc = gc < 1 ? 1 : (gc > 256 ? 256 : gc);
+  g.gather_chunks = r > 0 ? gc : 0;
+  int ec = (est_clusters + 255) / 256;
+  ec = ec < 1 ? 1 : (ec > 256 ? 256 : ec);
+  g.est_chunks = est_clusters > 0 ? ec : 0;
+  g.slots = g.steady_chunks + g.gather_chunks + g.est_chunks;
+  size_t o = 0;
+  g.off_z = o;       o = align_up(o + sizeof(float) * (size_t)heads * m);
+  g.off_cn2 = o;     o = align_up(o + sizeof(float) * (size_t)units * g.score_chunks);
+  g.off_ids1 = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * g.rcap1);
+  g.off_ids2 = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * g.rcap2);
+  g.off_nsel1 = o;   o = align_up(o + sizeof(int32_t) * (size_t)heads);
+  g.off_nsel2 = o;   o = align_up(o + sizeof(int32_t) * (size_t)heads);
+  g.off_pref = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * (g.rcap2 + 1));
+  g.off_srow = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * g.rcap2);
+  g.off_bitmap = o;  o = align_up(o + sizeof(uint32_t) * (size_t)heads * g.mwords);
+  g.off_zref = o;    o = align_up(o + sizeof(float) * (size_t)heads);
+  if (g.sliced1 || g.sliced2) {
+    g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * g.rcap2);
+    g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * g.rcap2);
+  }
+  // one more slot than the merge reads: the streaming selection leaves a partial there
+  g.off_part = o;    o = align_up(o + sizeof(float) * (size_t)heads * (g.slots + 1) * (D + 2));
+  g.total = o;
+  return g;
+}
+
+template <typename T, int D, int G>
+static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int est_clusters, float* out,
+                              float* lse, int32_t* selected, int topk, void* ws, hipStream_t st) {
+  const BudgetGeom g = budget_geometry(ix, Hq, topk, est_clusters);
+  char* w = static_cast<char*>(ws);
+  float* z = reinterpret_cast<float*>(w + g.off_z);
+  float* cn2 = reinterpret_cast<float*>(w + g.off_cn2);
+  int32_t* ids1 = reinterpret_cast<int32_t*>(w + g.off_ids1);
+  int32_t* ids2 = reinterpret_cast<int32_t*>(w + g.off_ids2);
+  int32_t* nsel1 = reinterpret_cast<int32_t*>(w + g.off_nsel1);
+  int32_t* nsel2 = reinterpret_cast<int32_t*>(w + g.off_nsel2);
+  int32_t* pref = reinterpret_cast<int32_t*>(w + g.off_pref);
+  int32_t* srow = reinterpret_cast<int32_t*>(w + g.off_srow);
+  uint32_t* bitmap = reinterpret_cast<uint32_t*>(w + g.off_bitmap);
+  float* zref = reinterpret_cast<float*>(w + g.off_zref);
+  int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
+  float* slice_z = reinterpret_cast<float*>(w + g.off_slice_z);
+  float* part = reinterpret_cast<float*>(w + g.off_part);
+  const T* q = static_cast<const T*>(q_);
+  const T* C = static_cast<const T*>(ix.centroids);
+  const T* VS = static_cast<const T*>(ix.vsum);
+  const int units = ix.B * ix.Hkv, heads = ix.B * Hq, m = ix.m;
+  const float scale_log2 = kLog2e / sqrtf((float)D);
+  const int slots = g.slots + 1, spare_slot = g.slots;
+
+  WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q, C, ix.sizes, z,
+              cn2, ix.Hkv, m, g.score_chunks);
+  // the k best clusters of every head as an ascending id list (ids, nsel)
+  auto select_ids = [&](int k, int rcap, int sliced, int32_t* ids, int32_t* nsel, int32_t* usel) {
+#define WAVE_SEL(k_)                                                                                \
+  q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, k_, rcap, g.mwords, k_, ids, pref, srow,   \
+      bitmap, zref, nsel, usel, VS, scale_log2, part, slots, spare_slot
+    if (sliced) {
+      const int npos_max = g.nslices * k;
+      const size_t lds_a = sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512);
+      const size_t lds_b = sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512);
+      SideWork none{ix.sizes, 512, 1, 0, 0, 0, ix.k_steady, ix.v_steady, ix.p, 0, 64, 0};
+      WAVE_LAUNCH("select_slices", (slices_side_kernel<T, D, G, 512, 32>), heads * g.nslices, 512, lds_a,
+                  st, WAVE_SEL(k), g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, none);
+      WAVE_LAUNCH("select", (combine_side_kernel<T, D, G, 512, 32>), heads, 512, lds_b, st, WAVE_SEL(k),
+                  g.nslices, slice_ids, slice_z, heads, none);
+    } else if (m <= 512 * 32) {
+      WAVE_LAUNCH("select", (select_cached_kernel<T, D, 512, 32, true>), heads, 512,
+                  sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, WAVE_SEL(k));
+    } else if (m <= 1024 * 64) {
+      WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024,
+                  sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SEL(k));
+    } else {
+      WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SEL(k));
+    }
+#undef WAVE_SEL
+  };
+  select_ids(g.r, g.rcap1, g.sliced1, ids1, nsel1, selected);
+  if (est_clusters > 0) select_ids(g.k2, g.rcap2, g.sliced2, ids2, nsel2, nullptr);
+
+  if (g.steady_chunks > 0)
+    WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
+                static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
+                g.steady_chunks, g.steady_rows, slots, 0, scale_log2, part);
+  if (g.gather_chunks > 0)
+    WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
+                static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1,
+                ix.offsets, z, VS, Hq, ix.Hkv, ix.N_idx, m, g.rcap1, g.gather_chunks, slots, scale_log2, 0,
+                part + (size_t)g.steady_chunks * (D + 2));
+  if (g.est_chunks > 0)
+    WAVE_LAUNCH("estimate", (est_gather_kernel<T, D>), heads * g.est_chunks, 256, 0, st, ids2, nsel2, ids1,
+                nsel1, ix.offsets, z, VS, Hq, ix.Hkv, m, g.rcap2, g.rcap1, g.est_chunks, slots,
+                g.steady_chunks + g.gather_chunks, scale_log2, part);
+  WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, g.slots, slots, out, lse);
+  return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+}
+
+template <typename T, int D>
+static wave_status budget_td(int G, const void* q, const wave_index& ix, int Hq, int est_clusters,
+                             float* out, float* lse, int32_t* selected, int topk, void* ws,
+                             hipStream_t st) {
+  switch (G) {
+#define WAVE_G(n) \
+  case n: return budget_tdg<T, D, n>(q, ix, Hq, est_clusters, out, lse, selected, topk, ws, st);
     WAVE_G(1) WAVE_G(2) WAVE_G(3) WAVE_G(4) WAVE_G(5) WAVE_G(6) WAVE_G(7) WAVE_G(8)
 #undef WAVE_G
     default: return WAVE_ERR_SHAPE;
@@ -2200,7 +2416,7 @@ static wave_status full_tdg(const void* q, const void* K, const void* V, int B, 
   WAVE_LAUNCH("full_attention", (steady_kernel<T, D, G>), units * chunks, 256, 0, st,
               static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), Hkv, N,
               chunks, FULL_ATTN_ROWS, chunks, 0, scale_log2, part);
-  WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, chunks, out, lse);
+  WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, chunks, chunks, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
@@ -2239,6 +2455,21 @@ wave_status launch_decode(const void* q, const wave_index& ix, int Hq, int topk,
   } else {
     if (ix.d == 128) return decode_td<float, 128>(G, q, ix, Hq, topk, out, lse, selected, ws, st);
     if (ix.d == 64) return decode_td<float, 64>(G, q, ix, Hq, topk, out, lse, selected, ws, st);
+  }
+  return WAVE_ERR_SHAPE;
+}
+
+wave_status launch_decode_budget(const void* q, const wave_index& ix, int Hq, int topk, int est_clusters,
+                                 float* out, float* lse, int32_t* selected, void* ws, hipStream_t st) {
+  if (budget_geometry(ix, Hq, topk, est_clusters).delegate)
+    return launch_decode(q, ix, Hq, topk, out, lse, selected, ws, st);
+  const int G = Hq / ix.Hkv;
+  if (ix.dtype == WAVE_BF16) {
+    if (ix.d == 128) return budget_td<bf16_t, 128>(G, q, ix, Hq, est_clusters, out, lse, selected, topk, ws, st);
+    if (ix.d == 64) return budget_td<bf16_t, 64>(G, q, ix, Hq, est_clusters, out, lse, selected, topk, ws, st);
+  } else {
+    if (ix.d == 128) return budget_td<float, 128>(G, q, ix, Hq, est_clusters, out, lse, selected, topk, ws, st);
+    if (ix.d == 64) return budget_td<float, 64>(G, q, ix, Hq, est_clusters, out, lse, selected, topk, ws, st);
   }
   return WAVE_ERR_SHAPE;
 }

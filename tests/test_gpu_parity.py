@@ -275,6 +275,18 @@ def test_decode_many_clusters_hand_index(m, dup, Hq):
     wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d)
     for r in (0, 5, 300, m):
         _decode_and_check(wl, ix, {(0, 0): ref}, q, r, f"hand m={m}")
+    # the estimation budget through every selection size class as well
+    qn = q.double().numpy()
+    for r, e in ((300, 2000), (5, 5000)):
+        out, lse, sel = wb.wave_attention_decode_budget(q.cuda(), ix, r, e, want_selected=True)
+        torch.cuda.synchronize()
+        for hq in range(Hq):
+            parts = {}
+            o, l, s_ref = wo.decode_unit(qn[0, hq], ref, r, parts, est_clusters=e)
+            tag = f"hand m={m} budget r={r} e={e} hq={hq}"
+            pu.check_outputs(out[0, hq].cpu().numpy(), lse[0, hq:hq + 1].cpu().numpy(), o, np.array([l]),
+                             dtype, tag)
+            pu.check_selected(sel[0, hq].cpu().numpy(), s_ref, parts["z"], tag)
 
 
 @pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),
@@ -347,3 +359,34 @@ def test_full_attention_is_the_limit_of_the_wave_decode():
     torch.cuda.synchronize()
     assert float((o1 - o2).abs().max()) < 2e-5
     assert float((l1 - l2).abs().max()) < 2e-5
+
+
+@pytest.mark.parametrize("case", ["tiny_f32", "bf16_g4", "bf16_g7", "bf16_d64", "f32_d128"])
+def test_decode_with_estimation_budget(case):
+    """The estimation-zone budget (the e best-ranked clusters after the retrieved ones are
+    estimated, the rest ignored) against the oracle, including e = 0 and budgets that
+    reach every cluster (then it is the plain decode)."""
+    wl = CASES[case]
+    K, V, q = _inputs(wl, 1)
+    index_ref = pu.oracle_build(wl, K, V)
+    arrays = pu.oracle_index_arrays(wl, index_ref)
+    ix = wb.index_from_arrays(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
+                              wl.segment_len, wl.clusters_per_segment, arrays)
+    m = ix.m
+    qn = q.double().numpy()
+    r0 = pu.retrieve_count(wl)
+    for r, e in [(r0, 0), (r0, 1), (r0, max(1, round(0.232 * m))), (0, 5), (0, 0), (1, m // 2),
+                 (r0, m - r0 - 1), (r0, m), (r0, -1)]:
+        out, lse, sel = wb.wave_attention_decode_budget(q.cuda(), ix, r, e, want_selected=True)
+        torch.cuda.synchronize()
+        out, lse = out.cpu().numpy(), lse.cpu().numpy()
+        sel = sel.cpu().numpy() if sel is not None else None
+        for b in range(wl.B):
+            for hq in range(wl.Hq):
+                parts = {}
+                o, l, s = wo.decode_unit(qn[b, hq], index_ref[(b, hq // wl.G)], r, parts,
+                                         est_clusters=None if e < 0 else e)
+                tag = f"{case} budget b={b} hq={hq} r={r} e={e}"
+                pu.check_outputs(out[b, hq], lse[b, hq:hq + 1], o, np.array([l]), wl.dtype, tag)
+                if r > 0:
+                    pu.check_selected(sel[b, hq], s, parts["z"], tag)
