@@ -189,7 +189,7 @@ struct DecodeGeom {
   int neg_in_gather, neg_slots;    // selected clusters' estimation terms: taken out by the retrieval kernel / a partial of their own
   int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
   int est_with_slices_pct;         // sliced path: share of the estimation work in the slices' launch
-  size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_zref, off_nsel, off_part,
+  size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_nsel, off_part,
       off_slice_ids, off_slice_z, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
@@ -212,7 +212,7 @@ struct BudgetGeom {
   int sliced1, sliced2, nslices, slice_len;
   int score_chunks, steady_rows, steady_chunks, gather_chunks, est_chunks, slots;
   size_t off_z, off_cn2, off_ids1, off_ids2, off_nsel1, off_nsel2, off_pref, off_srow, off_bitmap,
-      off_zref, off_slice_ids, off_slice_z, off_part, total;
+      off_slice_ids, off_slice_z, off_part, total;
 };
 BudgetGeom budget_geometry(const wave_index& ix, int Hq, int topk, int est_clusters);
 wave_status launch_decode_budget(const void* q, const wave_index& ix, int Hq, int topk, int est_clusters,

@@ -501,7 +501,7 @@ __global__ __launch_bounds__(NT) void select_kernel(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot) {
   constexpr int NW = NT / 64;
@@ -774,10 +774,6 @@ __global__ __launch_bounds__(NT) void select_kernel(
     if (tid == 0) {
       pref[min(nsel, rcap)] = ntok;
       nsel_out[bh] = min(nsel, rcap);
-      // reference score of the estimation zone: every estimated cluster scores <= it
-      float ref = 0.f;
-      if (nvalid > 0) ref = (mode == 2 || mode == 3) ? fminf(hi, zmax) : zmax;
-      zref_out[bh] = ref;
     }
     __syncthreads();  // ids[] complete
     negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, min(nsel, rcap),
@@ -822,7 +818,7 @@ __device__ __forceinline__ int select_core(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int bh, uint32_t* skeys, int* s_pref,
     int* s_row, int stage_cap, int* ntok_out, const SelView view) {
@@ -839,7 +835,6 @@ __device__ __forceinline__ int select_core(
   auto cid = [&](int i) { return view.idmap ? view.idmap[i] : view.id_base + i; };
   int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
   int32_t* srow = sel_row + (size_t)bh * rcap;
-  uint32_t* bits = bitmap + (size_t)bh * mwords;
   int32_t* usel = user_selected ? user_selected + (size_t)bh * usel_stride : nullptr;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
 
@@ -1271,10 +1266,6 @@ __device__ __forceinline__ int select_core(
     pref[nsel] = carry;
     if (nsel < stage_cap) s_pref[nsel] = carry;
     nsel_out[bh] = nsel;
-    // reference score of the estimation zone: every estimated cluster scores <= it
-    float ref = 0.f;
-    if (nvalid > 0) ref = (mode == 2 || mode == 3) ? fminf(hi, zmax) : zmax;
-    zref_out[bh] = ref;
   }
   __syncthreads();
   negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
@@ -1289,13 +1280,13 @@ __global__ __launch_bounds__(NT) void select_cached_kernel(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot) {
   extern __shared__ uint32_t dyn_keys[];  // NT * ceil(m / NT) keys when LDSK
   int ntok;
   select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
-                                   usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out, nsel_out,
+                                   usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out,
                                    user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
                                    dyn_keys, nullptr, nullptr, 0, &ntok,
                                    SelView{m, 0, nullptr, nullptr, 2, nullptr, nullptr});
@@ -1741,7 +1732,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, const T* __restrict__ k_perm,
     const T* __restrict__ v_perm, int N_idx, const T* __restrict__ k_steady,
@@ -1793,7 +1784,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   int ntok;
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
-      sel_pref, sel_row, bitmap, zref_out, nsel_out, user_selected, vsum, scale_log2, part, slots,
+      sel_pref, sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots,
       neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok,
       SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr});
   if (threadIdx.x == 0) {
@@ -2027,7 +2018,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
     int32_t* __restrict__ slice_ids, float* __restrict__ slice_z, int n_select_wgs,
@@ -2039,7 +2030,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
     int ntok;
     select_core<T, D, NT, VPT, true>(
         q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
-        sel_row, bitmap, zref_out, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
+        sel_row, bitmap, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
         dyn_keys, nullptr, nullptr, 0, &ntok,
         SelView{len, base, nullptr, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r,
                 slice_z + ((size_t)bh * nslices + sl) * r});
@@ -2055,7 +2046,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
-    float* __restrict__ zref_out, int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, int nslices,
     const int32_t* __restrict__ slice_ids, const float* __restrict__ slice_z, int n_select_wgs,
@@ -2068,7 +2059,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     const int bh = blockIdx.x;
     int ntok;
     select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
-                                     usel_stride, sel_ids, sel_pref, sel_row, bitmap, zref_out,
+                                     usel_stride, sel_ids, sel_pref, sel_row, bitmap,
                                      nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot,
                                      bh, dyn_keys, nullptr, nullptr, 0, &ntok,
                                      SelView{nslices * r, 0, slice_ids + (size_t)bh * nslices * r,
@@ -2138,7 +2129,6 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.off_pref = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * (g.rcap + 1));
   g.off_srow = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * g.rcap);
   g.off_bitmap = o;  o = align_up(o + sizeof(uint32_t) * (size_t)heads * (g.mwords > 0 ? g.mwords : 1));
-  g.off_zref = o;    o = align_up(o + sizeof(float) * (size_t)heads);
   g.off_nsel = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads);
   g.off_part = o;    o = align_up(o + sizeof(float) * (size_t)heads * g.slots * (D + 2));
   if (g.sliced) {
@@ -2160,7 +2150,6 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   int32_t* pref = reinterpret_cast<int32_t*>(w + g.off_pref);
   int32_t* srow = reinterpret_cast<int32_t*>(w + g.off_srow);
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(w + g.off_bitmap);
-  float* zref = reinterpret_cast<float*>(w + g.off_zref);
   int32_t* nsel = reinterpret_cast<int32_t*>(w + g.off_nsel);
   float* part = reinterpret_cast<float*>(w + g.off_part);
   const T* q = static_cast<const T*>(q_);
@@ -2188,7 +2177,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part);
 #define WAVE_SELECT_ARGS                                                                           \
   q, static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, r,    \
-      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, zref, nsel, selected,                        \
+      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, nsel, selected,                        \
       static_cast<const T*>(ix.vsum), scale_log2, part, g.slots, neg_slot
     const size_t key_lds = sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512);
     if (g.fused) {
@@ -2310,7 +2299,6 @@ BudgetGeom budget_geometry(const wave_index& ix, int Hq, int topk, int est_clust
   g.off_pref = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * (g.rcap2 + 1));
   g.off_srow = o;    o = align_up(o + sizeof(int32_t) * (size_t)heads * g.rcap2);
   g.off_bitmap = o;  o = align_up(o + sizeof(uint32_t) * (size_t)heads * g.mwords);
-  g.off_zref = o;    o = align_up(o + sizeof(float) * (size_t)heads);
   if (g.sliced1 || g.sliced2) {
     g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * g.rcap2);
     g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * g.rcap2);
@@ -2335,7 +2323,6 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   int32_t* pref = reinterpret_cast<int32_t*>(w + g.off_pref);
   int32_t* srow = reinterpret_cast<int32_t*>(w + g.off_srow);
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(w + g.off_bitmap);
-  float* zref = reinterpret_cast<float*>(w + g.off_zref);
   int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
   float* slice_z = reinterpret_cast<float*>(w + g.off_slice_z);
   float* part = reinterpret_cast<float*>(w + g.off_part);
@@ -2352,7 +2339,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   auto select_ids = [&](int k, int rcap, int sliced, int32_t* ids, int32_t* nsel, int32_t* usel) {
 #define WAVE_SEL(k_)                                                                                \
   q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, k_, rcap, g.mwords, k_, ids, pref, srow,   \
-      bitmap, zref, nsel, usel, VS, scale_log2, part, slots, spare_slot
+      bitmap, nsel, usel, VS, scale_log2, part, slots, spare_slot
     if (sliced) {
       const int npos_max = g.nslices * k;
       const size_t lds_a = sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512);
