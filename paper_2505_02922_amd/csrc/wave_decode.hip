@@ -492,10 +492,9 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
 }
 
 // The fallback for more clusters than the LDS-keyed selections below take: NT
-// threads per query head; used with VPT == 0, where the scores are re-read from
-// memory in every pass (radix select, 4 passes of 8 bits, on the integer keys).
-// With VPT > 0 every thread would keep VPT scores in registers (m <= NT * VPT).
-template <typename T, int D, int NT, int VPT>
+// threads per query head, the scores re-read from memory in every pass (radix
+// select, 4 passes of 8 bits, on the integer keys).
+template <typename T, int D, int NT>
 __global__ __launch_bounds__(NT) void select_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
@@ -525,26 +524,12 @@ __global__ __launch_bounds__(NT) void select_kernel(
   __shared__ int sh_i[4];
   __shared__ float sh_f[2];
 
-  float zc[VPT > 0 ? VPT : 1];
-  if constexpr (VPT > 0) {
-#pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-      const int i = k * NT + tid;
-      zc[k] = i < m ? zz[i] : -INFINITY;
-    }
-  }
   // fn(i, v) runs for every i in [0, round_up(m, NT)), v = -inf past the end;
   // all lanes of a wave make the same calls, so fn may use wave-wide operations.
   auto scan = [&](auto fn) {
-    if constexpr (VPT > 0) {
-#pragma unroll
-      for (int k = 0; k < VPT; ++k)
-        if (k * NT < m) fn(k * NT + tid, zc[k]);
-    } else {
-      for (int base = 0; base < m; base += NT) {
-        const int i = base + tid;
-        fn(i, i < m ? zz[i] : -INFINITY);
-      }
+    for (int base = 0; base < m; base += NT) {
+      const int i = base + tid;
+      fn(i, i < m ? zz[i] : -INFINITY);
     }
   };
 
@@ -2217,7 +2202,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
         WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024,
                     sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SELECT_ARGS);
       else
-        WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SELECT_ARGS);
+        WAVE_LAUNCH("select", (select_kernel<T, D, 512>), heads, 512, 0, st, WAVE_SELECT_ARGS);
       if (g.gather_chunks > 0)
         WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                     static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), sel, nsel,
@@ -2356,7 +2341,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
       WAVE_LAUNCH("select", (select_cached_kernel<T, D, 1024, 64, false>), heads, 1024,
                   sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_SEL(k));
     } else {
-      WAVE_LAUNCH("select", (select_kernel<T, D, 512, 0>), heads, 512, 0, st, WAVE_SEL(k));
+      WAVE_LAUNCH("select", (select_kernel<T, D, 512>), heads, 512, 0, st, WAVE_SEL(k));
     }
 #undef WAVE_SEL
   };
