@@ -344,6 +344,24 @@ def decode_unit(q: np.ndarray, ix: UnitIndex, r: int, parts: Optional[dict] = No
     return A / Z, M + math.log(Z), sel
 
 
+def recall_at(q: np.ndarray, ix: UnitIndex, sel: np.ndarray, top: int = 100) -> float:
+    """Clustering accuracy as the evaluation's segment-size study measures it
+    (recall@100): of the `top` indexed tokens with the largest q . K_j, the
+    share that lies in the retrieved clusters `sel`.  Ties go to the earlier
+    row of the cluster-contiguous order."""
+    q = np.asarray(q, dtype=np.float64)
+    scores = np.asarray(ix.k_perm, dtype=np.float64) @ q
+    n = scores.size
+    top = min(int(top), n)
+    if top == 0:
+        return 1.0
+    best = np.lexsort((np.arange(n), -scores))[:top]
+    hit = np.zeros(n, dtype=bool)
+    for c in np.asarray(sel, dtype=np.int64):
+        hit[ix.offsets[c]:ix.offsets[c + 1]] = True
+    return float(hit[best].mean())
+
+
 # --------------------------------------------------------------------------
 # Whole-batch wrappers (loops over independent units; no arithmetic of their own)
 # --------------------------------------------------------------------------

@@ -390,3 +390,24 @@ def test_decode_with_estimation_budget(case):
                 pu.check_outputs(out[b, hq], lse[b, hq:hq + 1], o, np.array([l]), wl.dtype, tag)
                 if r > 0:
                     pu.check_selected(sel[b, hq], s, parts["z"], tag)
+
+
+def test_recall_measurement_matches_oracle():
+    """The recall@100 figure the segment-size study reports, computed from the device
+    index, against the oracle's on the oracle-built index (the two indexes are equal)."""
+    wl = CASES["bf16_g4"]
+    K, V, q = _inputs(wl, 2)
+    index_ref = pu.oracle_build(wl, K, V)
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    r = pu.retrieve_count(wl)
+    _, _, sel = wb.wave_attention_decode(q.cuda(), ix, r, want_selected=True)
+    torch.cuda.synchronize()
+    rec = pu.recall_at_gpu(q.cuda(), ix, sel, wl.Hq, top=100).cpu().numpy()
+    qn = q.double().numpy()
+    for b in range(wl.B):
+        for hq in range(wl.Hq):
+            ref = index_ref[(b, hq // wl.G)]
+            s_ref, _ = wo.select_clusters(qn[b, hq], ref.centroids, ref.sizes, r)
+            want = wo.recall_at(qn[b, hq], ref, s_ref, top=100)
+            assert abs(rec[b, hq] - want) <= 0.011, (b, hq, rec[b, hq], want)   # one token of 100: score ties

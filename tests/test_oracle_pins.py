@@ -294,6 +294,21 @@ def test_estimation_budget_limits():
             prev = l
 
 
+def test_recall_by_hand():
+    # Six indexed tokens in three clusters of two; scores 6, 5, 1, 4, 3, 2 in row order.
+    q = np.array([1.0, 0.0])
+    Kp = np.array([[6.0, 0], [5.0, 0], [1.0, 0], [4.0, 0], [3.0, 0], [2.0, 0]])
+    plan = wo.make_plan(6, 0, 0, 6, 3)
+    ix = wo.UnitIndex(plan, "f32", np.zeros((3, 2)), np.zeros((3, 2)), np.array([2, 2, 2]),
+                      np.array([0, 2, 4, 6]), np.arange(6), Kp, np.zeros((6, 2)), np.zeros((0, 2)),
+                      np.zeros((0, 2)), np.zeros(0, dtype=np.int64))
+    assert wo.recall_at(q, ix, np.array([0]), top=2) == 1.0          # rows 0, 1
+    assert wo.recall_at(q, ix, np.array([0]), top=3) == 2 / 3         # row 3 is in cluster 1
+    assert wo.recall_at(q, ix, np.array([1, 2]), top=4) == 0.5        # rows 3, 4 of 0, 1, 3, 4
+    assert wo.recall_at(q, ix, np.array([0, 1, 2]), top=6) == 1.0
+    assert wo.recall_at(q, ix, np.zeros(0, dtype=np.int64), top=3) == 0.0
+
+
 def dataclasses_replace(ix, **kw):
     return dataclasses.replace(ix, **kw)
 
