@@ -33,6 +33,72 @@ def _median(xs):
     return xs[len(xs) // 2]
 
 
+def segment_study() -> int:
+    """Index build time and recall@100 against the segment length (Evaluation, "Impact of
+    Different Segment Sizes"), on one llama-shaped sequence of 128K indexed tokens with one
+    centroid per 16 tokens.  The library takes at most 4096 clusters per segment, so the longest
+    segment is 64K tokens (two segments); the paper's 128K point (one global k-means) is not
+    reachable.  Prints one JSON line of its own."""
+    import torch
+    from paper_2505_02922_amd import binding as wb
+    from paper_2505_02922_amd import synth
+    from tests import parity_util as pu
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    wb.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    base = synth.WORKLOADS["llama8b_120k_b16"]
+    n_idx = 131072
+    wl0 = synth.scaled(base, name="llama8b_128k_b1", B=1, N=n_idx + base.n_sink + base.n_local)
+    K, V = synth.make_kv(wl0, device=dev)
+    n_q = 8
+    queries = [synth.make_queries(wl0, i, device=dev) for i in range(n_q)]
+    rows = []
+    for L in (1024, 2048, 4096, 8192, 16384, 32768, 65536):
+        wl = synth.scaled(wl0, segment_len=L, clusters_per_segment=L // 16)
+        ix = wb.alloc_index(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
+                            wl.segment_len, wl.clusters_per_segment, dev)
+        bws = wb.workspace(ix.build_ws_bytes, dev)
+
+        def build():
+            wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len,
+                                wl.clusters_per_segment, wl.iters, 0, ws=bws, index=ix)
+
+        build()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            build()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        r = pu.retrieve_count(wl)
+        rec = []
+        for q in queries:
+            _, _, sel = wb.wave_attention_decode(q, ix, r, want_selected=True)
+            torch.cuda.synchronize()
+            rec.append(pu.recall_at_gpu(q, ix, sel, wl.Hq, top=100).mean().item())
+        rows.append({"segment_len": L, "clusters_per_segment": L // 16, "m": ix.m, "r": r,
+                     "build_ms": round(_median(ms), 3),
+                     "recall_at_100": round(sum(rec) / len(rec), 4)})
+        print(f"segment_len {L}: build {rows[-1]['build_ms']} ms, recall@100 "
+              f"{rows[-1]['recall_at_100']}", file=sys.stderr, flush=True)
+        del ix, bws
+        torch.cuda.empty_cache()
+    print(json.dumps({"study": "segment size vs index build time vs recall@100",
+                      "config": {"workload": wl0.name, "B": 1, "Hq": wl0.Hq, "Hkv": wl0.Hkv,
+                                 "d": wl0.d, "N_indexed": n_idx, "iters": wl0.iters,
+                                 "tokens_per_cluster": 16, "query_sets": n_q,
+                                 "retrieve_frac": wl0.retrieve_frac},
+                      "dtype": wl0.dtype, "data": "synthetic", "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,11 +113,17 @@ def main() -> int:
     ap.add_argument("--only", choices=["all", "build", "decode"], default="all",
                     help="build: stop after the index build (for profiler runs); "
                          "decode: build once untimed, then only the decode phase")
+    ap.add_argument("--segment-study", action="store_true",
+                    help="instead of the benchmark: index build time and recall@100 for segment "
+                         "lengths 1K..64K on one 128K-token sequence")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: every (sequence, KV head) unit is independent and "
               "this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
         return 2
+
+    if args.segment_study:
+        return segment_study()
 
     import numpy as np
     import torch

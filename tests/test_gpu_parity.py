@@ -48,6 +48,11 @@ CASES = {
     "bf16_big_k": _small("llama8b_32k", name="bf16_big_k", N=2900, Hq=4, Hkv=1, segment_len=1400,
                          clusters_per_segment=600, n_local=60, n_components=512, iters=3,
                          retrieve_frac=0.05),
+    # the largest cluster count per segment the library takes (4096), at 4 tokens per cluster,
+    # with a ragged tail segment: the staged assign step and the two-wave counting sort
+    "bf16_max_k": _small("llama8b_32k", name="bf16_max_k", N=19500, Hq=2, Hkv=1, segment_len=16384,
+                         clusters_per_segment=4096, n_local=60, n_components=2048, iters=2,
+                         retrieve_frac=0.02),
     # d = 128 in f32 (32 lanes per row)
     "f32_d128": _small("tiny_f32", name="f32_d128", d=128, N=1500, Hq=2, Hkv=1, segment_len=512,
                        clusters_per_segment=32, n_local=30, iters=3, retrieve_abs=9),
