@@ -190,7 +190,7 @@ struct DecodeGeom {
   int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
   int est_with_slices_pct;         // sliced path: share of the estimation work in the slices' launch
   size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_nsel, off_part,
-      off_slice_ids, off_slice_z, total;
+      off_slice_ids, off_slice_z, off_tile_max, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 

@@ -33,6 +33,7 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 //    one fp32 ulp of the output).
 // ============================================================================
 constexpr int DENSE_ROWS = 256;
+constexpr int SCORE_TILE = 16;  // clusters per entry of the score pass's table of maxima
 
 // LDS of the meta-index pass for a workgroup of NT threads over NT clusters.
 template <typename T, int D, int G, int NT>
@@ -72,7 +73,8 @@ template <typename T, int D, int G, int NT>
 __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* __restrict__ C,
                                              const int32_t* __restrict__ su, float* __restrict__ z,
                                              int unit, int bh0, int m, int c0, int nrows,
-                                             const DenseLds<T, D, G, NT>& lds) {
+                                             const DenseLds<T, D, G, NT>& lds,
+                                             float* __restrict__ tile_max = nullptr) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
   constexpr int ZG = DenseLds<T, D, G, NT>::ZG;
   constexpr int U = 4;
@@ -131,6 +133,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
       const int dv = hj & 3;
       const float dg = dv == 0 ? gram[0] : (dv == 1 ? gram[1] : (dv == 2 ? gram[2] : gram[3]));
       if ((hj >> 2) == kb) cn2 = fmaxf(cn2, dg);
+      float tmx = -INFINITY;
       if (hj < G) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -139,8 +142,16 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
             const float val = sz[v] > 0 ? acc[v] : -INFINITY;
             z[(size_t)(bh0 + hj) * m + c0 + cc] = val;
             zw[cc * ZG + hj] = val;
+            tmx = fmaxf(tmx, val);
           }
         }
+      }
+      if (tile_max) {  // the tile's largest score per head (the tile is SCORE_TILE = 16 clusters)
+        static_assert(SCORE_TILE == 16, "one MFMA tile per table entry");
+        tmx = fmaxf(tmx, __shfl_xor(tmx, 16));
+        tmx = fmaxf(tmx, __shfl_xor(tmx, 32));
+        if (kb == 0 && hj < G)
+          tile_max[(size_t)(bh0 + hj) * ((m + SCORE_TILE - 1) / SCORE_TILE) + c0 / SCORE_TILE + t] = tmx;
       }
     }
     cn2 = wave_max(cn2);
@@ -353,7 +364,8 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, const T* __restrict__ C,
                                                     const int32_t* __restrict__ sizes,
                                                     float* __restrict__ z, float* __restrict__ cn2part,
-                                                    int Hkv, int m, int chunks) {
+                                                    int Hkv, int m, int chunks,
+                                                    float* __restrict__ tile_max) {
   using Lds = DenseLds<T, D, G, 256>;
   __shared__ __attribute__((aligned(16))) char lds_raw[Lds::score_bytes];
   const Lds lds(lds_raw);
@@ -362,9 +374,22 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int bh0 = b * Hq + h * G;
   const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-  dense_scores<T, D, G, 256>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds);
+  dense_scores<T, D, G, 256>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
+                             sizeof(T) == 2 ? tile_max : nullptr);
   __syncthreads();
   if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
+  if (sizeof(T) != 2 && tile_max) {  // (the bf16 pass writes them tile by tile)
+    // largest score of every run of SCORE_TILE clusters, per head (-inf: all empty)
+    constexpr int TPC = DENSE_ROWS / SCORE_TILE, ZG = Lds::ZG;
+    static_assert(TPC * G <= 256, "one thread per (tile, head)");
+    const int t = threadIdx.x % TPC, g = threadIdx.x / TPC;
+    if (g < G && SCORE_TILE * t < nrows) {
+      float mx = -INFINITY;
+      for (int j = SCORE_TILE * t; j < min(SCORE_TILE * (t + 1), nrows); ++j) mx = fmaxf(mx, lds.zw[j * ZG + g]);
+      const int ntile = (m + SCORE_TILE - 1) / SCORE_TILE;
+      tile_max[(size_t)(bh0 + g) * ntile + chunk * TPC + t] = mx;
+    }
+  }
 }
 
 // ============================================================================
@@ -2025,6 +2050,184 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
                          slots, reinterpret_cast<char*>(dyn_keys));
 }
 
+// ----------------------------------------------------------------------------
+// A cheap first stage for the slices.  The score pass left the largest score of
+// every run of SCORE_TILE clusters.  Any value T that at least r of those maxima
+// reach is a lower bound of the head's r-th largest score (r different clusters
+// score at least T), so with the fp32 error bound `guard` below it, every
+// cluster that the exact ranking could select scores at least T - guard.  T is
+// the lower edge of the bucket (upper 16 key bits) in which the count of maxima,
+// taken from the top, reaches r: one histogram sweep and a scan, no search.  A
+// slice then only lists its clusters at or above T - guard, ascending, padded
+// to r entries like the lists of the exact slice ranking.  Returns false, with
+// nothing written, when the slice holds more than r such clusters (or no T
+// exists); the caller then ranks the slice exactly.
+// The buckets are the SEL_BINS ones below the bucket of |q| max|C|, an upper
+// bound of every score.
+// ----------------------------------------------------------------------------
+template <typename T, int D, int NT, int VPT>
+__device__ __forceinline__ bool filter_slice(const T* __restrict__ q, const float* __restrict__ z,
+                                             const float* __restrict__ tile_max,
+                                             const float* __restrict__ cn2part, int cn2_chunks,
+                                             int unit, int bh, int m, int r, int base, int len,
+                                             uint32_t* skeys, int32_t* __restrict__ ids_out,
+                                             float* __restrict__ z_out) {
+  constexpr int NW = NT / 64, TBL = VPT * NW;
+  static_assert(TBL <= NT, "one table entry per thread");
+  constexpr uint32_t kKeyNegInf = 0x007fffffu;  // order_key(-inf)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const float* zz = z + (size_t)bh * m + base;
+  const int ntile = (m + SCORE_TILE - 1) / SCORE_TILE;
+  const float* tm = tile_max + (size_t)bh * ntile;
+  __shared__ int f_hist[SEL_BINS];
+  __shared__ int f_scan[NW];
+  __shared__ int f_tbl[TBL];
+  __shared__ int f_sh[4];
+  __shared__ float f_shf[2];
+
+  // |q|^2 and max |C|^2: the error bound and the bound of the scores
+  if (wave == NW - 1) {
+    float qn2 = 0.f;
+    for (int i = lane; i < D; i += 64) {
+      const float v = to_f32(q[(size_t)bh * D + i]);
+      qn2 += v * v;
+    }
+    float c2 = 0.f;
+    for (int i = lane; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
+    qn2 = wave_sum_f(qn2);
+    c2 = wave_max(c2);
+    const float qc = sqrtf(qn2) * sqrtf(c2);
+    if (lane == 0) {
+      f_shf[0] = 2.0f * 48.f * 5.9604645e-8f * qc;  // as in the exact ranking
+      f_shf[1] = qc * 1.001f;
+    }
+  }
+  // the slice's keys into LDS
+  const int nk = (len + NT - 1) / NT;  // <= VPT
+  constexpr int KB = 16;
+  for (int k0 = 0; k0 < nk; k0 += KB) {
+    float v[KB];
+#pragma unroll
+    for (int u = 0; u < KB; ++u) {
+      const int i = (k0 + u) * NT + tid;
+      v[u] = i < len ? zz[i] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < KB; ++u)
+      if (k0 + u < nk) skeys[(k0 + u) * NT + tid] = order_key(v[u] + 0.0f);
+  }
+  for (int i = tid; i < SEL_BINS; i += NT) f_hist[i] = 0;
+  if (tid < TBL) f_tbl[tid] = 0;
+  __syncthreads();
+  const float guard = f_shf[0];
+  const uint32_t top16 = order_key(f_shf[1] + 0.0f) >> 16;
+  const uint32_t lo16 = top16 >= (uint32_t)(SEL_BINS - 1) ? top16 - (SEL_BINS - 1) : 0u;
+  // histogram of the head's tile maxima
+  for (int i0 = 0; i0 < ntile; i0 += NT * 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * NT + tid;
+      v[u] = i < ntile ? tm[i] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t ky = order_key(v[u] + 0.0f);
+      if (ky > kKeyNegInf) {
+        uint32_t b16 = ky >> 16;
+        b16 = b16 > top16 ? top16 : b16;  // cannot happen for finite inputs; keeps the index in range
+        atomicAdd(&f_hist[b16 > lo16 ? b16 - lo16 : 0u], 1);
+      }
+    }
+  }
+  __syncthreads();
+  constexpr int PER = SEL_BINS / NT;
+  static_assert(PER >= 1 && PER * NT == SEL_BINS, "bins per thread");
+  int mine[PER], sum = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    mine[j] = f_hist[SEL_BINS - 1 - (tid * PER + j)];  // thread 0 holds the top bins
+    sum += mine[j];
+  }
+  if (tid == 0) f_sh[0] = -1;
+  int tot;
+  int above = block_excl_scan<NT>(sum, f_scan, tot);  // also orders the store to f_sh[0] before the ones below
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    if (above < r && above + mine[j] >= r) f_sh[0] = SEL_BINS - 1 - (tid * PER + j);  // at most one (thread, j)
+    above += mine[j];
+  }
+  __syncthreads();
+  const int bsel = f_sh[0];
+  if (bsel <= 0) return false;  // fewer than r maxima, or the bound lies in the catch-all bucket
+  const float t_edge = key_to_float((lo16 + (uint32_t)bsel) << 16);
+  uint32_t kt = order_key((t_edge - guard) + 0.0f);
+  kt = kt > kKeyNegInf + 3u ? kt - 2u : kKeyNegInf + 1u;  // two ulps for the rounding of the subtraction
+
+  // the slice's clusters at or above the bound, in ascending order
+  for (int k = 0; k < nk; ++k) {
+    const uint64_t mk = __ballot(skeys[k * NT + tid] >= kt);
+    if (lane == 0) f_tbl[k * NW + wave] = __popcll(mk);
+  }
+  __syncthreads();
+  int cnt;
+  const int cbase = block_excl_scan<NT>(tid < TBL ? f_tbl[tid] : 0, f_scan, cnt);
+  if (cnt > r) return false;
+  __syncthreads();
+  if (tid < TBL) f_tbl[tid] = cbase;
+  __syncthreads();
+  for (int k = 0; k < nk; ++k) {
+    const uint32_t ky = skeys[k * NT + tid];
+    const bool on = ky >= kt;
+    const uint64_t mk = __ballot(on);
+    if (on) {
+      const int pos = f_tbl[k * NW + wave] + __popcll(mk & lt_mask);
+      ids_out[pos] = base + k * NT + tid;
+      z_out[pos] = key_to_float(ky);
+    }
+  }
+  for (int i = cnt + tid; i < r; i += NT) {
+    ids_out[i] = -1;
+    z_out[i] = -INFINITY;
+  }
+  return true;
+}
+
+template <typename T, int D, int G, int NT, int VPT>
+__global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void filter_side_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot, int nslices, int slice_len,
+    int32_t* __restrict__ slice_ids, float* __restrict__ slice_z, int n_select_wgs,
+    const SideWork sw, const float* __restrict__ tile_max) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];  // a slice's keys, or the other roles' LDS
+  if ((int)blockIdx.x < n_select_wgs) {
+    const int bh = blockIdx.x / nslices, sl = blockIdx.x - bh * nslices;
+    const int base = sl * slice_len, len = min(slice_len, m - base);
+    const int b = bh / Hq, hq = bh - b * Hq;
+    const int unit = b * Hkv + hq / (Hq / Hkv);
+    int32_t* ids_out = slice_ids + ((size_t)bh * nslices + sl) * r;
+    float* z_out = slice_z + ((size_t)bh * nslices + sl) * r;
+    if (filter_slice<T, D, NT, VPT>(q, z, tile_max, cn2part, cn2_chunks, unit, bh, m, r, base, len,
+                                    dyn_keys, ids_out, z_out))
+      return;
+    __syncthreads();
+    int ntok;
+    select_core<T, D, NT, VPT, true>(
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
+        sel_row, bitmap, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
+        dyn_keys, nullptr, nullptr, 0, &ntok, SelView{len, base, nullptr, nullptr, 1, ids_out, z_out});
+    return;
+  }
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+                         slots, reinterpret_cast<char*>(dyn_keys));
+}
+
 template <typename T, int D, int G, int NT, int VPT>
 __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
@@ -2097,7 +2300,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   if (g.sliced) {  // the estimation terms come from 512-thread workgroups next to the slices
     g.est_rows = 512;
     g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
-    g.est_with_slices_pct = 40;  // share of the estimation ranges that ride with the slices
+    g.est_with_slices_pct = 20;  // share of the estimation ranges that ride with the slices
   }
   // Who takes the selected clusters' estimation terms out again: the retrieval
   // kernel itself (no partial of their own), except after the fused kernel and
@@ -2119,6 +2322,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   if (g.sliced) {
     g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
     g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * r);
+    g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
   }
   g.total = o;
   return g;
@@ -2147,7 +2351,8 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     const int neg_slot = est_slot0 + g.est_chunks;  // exists when g.neg_slots is 1
     if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
-                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks);
+                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
+                  reinterpret_cast<float*>(w + g.off_tile_max));
     else if (!g.fused && g.steady_chunks > 0)
       WAVE_LAUNCH("meta_index+steady", (dense_steady_kernel<T, D, G>),
                   units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
@@ -2187,9 +2392,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
         const int n_est_a = (int)((long long)n_est * g.est_with_slices_pct / 100);
         SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, n_est_a, ix.k_steady,
                     ix.v_steady, ix.p, g.steady_chunks, g.steady_rows, g.gather_chunks};
-        WAVE_LAUNCH("select_slices+side", (slices_side_kernel<T, D, G, 512, 32>),
+        WAVE_LAUNCH("select_slices+side", (filter_side_kernel<T, D, G, 512, 32>),
                     heads * g.nslices + n_est_a + units * g.steady_chunks, 512, lds_a, st,
-                    WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, sw);
+                    WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, sw,
+                    reinterpret_cast<const float*>(w + g.off_tile_max));
         sw.est_first = n_est_a;
         sw.n_est_wgs = n_est - n_est_a;
         sw.steady_chunks = 0;  // done by the first launch
@@ -2319,7 +2525,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const int slots = g.slots + 1, spare_slot = g.slots;
 
   WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q, C, ix.sizes, z,
-              cn2, ix.Hkv, m, g.score_chunks);
+              cn2, ix.Hkv, m, g.score_chunks, static_cast<float*>(nullptr));
   // the k best clusters of every head as an ascending id list (ids, nsel)
   auto select_ids = [&](int k, int rcap, int sliced, int32_t* ids, int32_t* nsel, int32_t* usel) {
 #define WAVE_SEL(k_)                                                                                \

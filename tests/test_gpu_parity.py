@@ -241,7 +241,10 @@ def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
         C[c] = Kp[offsets[c]:offsets[c + 1]].mean(0)
         VS[c] = Vp[offsets[c]:offsets[c + 1]].sum(0)
     if dup_scores:   # many clusters with the very same centroid: exact score ties
-        C[::7] = C[7]
+        C[::7] = wo.quant(C[7], dtype)
+        for c in range(0, m, 7):   # their rows are that centroid, so it still is their mean
+            if c != 7:
+                Kp[offsets[c]:offsets[c + 1]] = C[c]
     Ks = wo.quant(g.standard_normal((n_steady, d)), dtype)
     Vs = wo.quant(g.standard_normal((n_steady, d)), dtype)
     return dict(centroids=wo.quant(C, dtype), vsum=wo.quant(VS, dtype), sizes=sizes, offsets=offsets,
@@ -277,8 +280,14 @@ def test_decode_many_clusters_hand_index(m, dup, Hq):
     g = np.random.default_rng(5)
     q = torch.from_numpy(wo.quant(g.standard_normal((1, Hq, d)) * 2.0, dtype).astype(np.float32)
                          ).to(torch.bfloat16)
+    if dup:   # head 0 looks straight at the shared centroid: the tied scores are the largest
+        q[0, 0] = torch.from_numpy(wo.quant(arrs["centroids"][7] * 3.0, dtype).astype(np.float32)
+                                   ).to(torch.bfloat16)
     wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d)
-    for r in (0, 5, 300, m):
+    # r = 2000 at m = 20000: more clusters asked for than there are 16-cluster tiles, so
+    # the slices' cheap first stage has no bound to offer and every slice is ranked exactly;
+    # with the tied scores on top a slice holds more than r candidates, same fallback
+    for r in (0, 5, 300, m) + ((2000,) if m == 20000 else ()):
         _decode_and_check(wl, ix, {(0, 0): ref}, q, r, f"hand m={m}")
     # the estimation budget through every selection size class as well
     qn = q.double().numpy()
