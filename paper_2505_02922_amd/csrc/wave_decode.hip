@@ -861,19 +861,17 @@ __device__ __forceinline__ int select_core(
   // ---- this thread's scores as order-preserving integer keys -------------------
   // Error bound inputs first, so that their loads overlap with the key loads:
   // |fp32 score - exact| <= (chunk chain + reduction tree + slack) * 2^-24 * |q| |C|
-  float guard_in = 0.f;
+  // (the loads are issued here and reduced after the key loads, so that the
+  // last wave does not reach the first barrier a memory round trip late)
+  static_assert(D <= 128, "two query elements per lane");
+  float gq[2] = {0.f, 0.f}, gc[4] = {0.f, 0.f, 0.f, 0.f};
   if (wave == NW - 1) {
-    float qn2 = 0.f;
-    for (int i = lane; i < D; i += 64) {
-      const float v = to_f32(q[(size_t)bh * D + i]);
-      qn2 += v * v;
-    }
-    float c2 = 0.f;
-    for (int i = lane; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
-    qn2 = wave_sum_f(qn2);
-    c2 = wave_max(c2);
-    const float steps = 48.f;  // covers the vector chain + tree and the MFMA accumulation alike
-    guard_in = 2.0f * steps * 5.9604645e-8f * sqrtf(qn2) * sqrtf(c2);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = to_f32(q[(size_t)bh * D + min(lane + 64 * j, D - 1)]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) gc[j] = cn2part[(size_t)unit * cn2_chunks + min(lane + 64 * j, cn2_chunks - 1)];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = lane + 64 * j < D ? gq[j] : 0.f;  // (a repeated maximum is harmless)
   }
   // The keys live in LDS and every sweep is a short rolled loop (this code runs
   // once per workgroup, so unrolled sweeps over registers would cost more in
@@ -889,24 +887,44 @@ __device__ __forceinline__ int select_core(
   uint32_t hot_lo = 1, hot_hi = 0;    // hot buckets (16-bit), empty to begin with
   constexpr int KB = 16;  // loads in flight per thread
   for (int k0 = 0; k0 < nk; k0 += KB) {
+    // Unconditional loads at clamped positions, masked afterwards: a load under a
+    // lane condition is compiled into a branch with its own wait, which would
+    // serialise the KB round trips.
     float v[KB];
+    if (view.zmap) {  // scores by position; holes of the id map are -inf here
 #pragma unroll
-    for (int u = 0; u < KB; ++u) {
-      const int i = (k0 + u) * NT + tid;
-      if (view.zmap) {  // scores by position; holes of the id map are -inf here
-        v[u] = i < npos ? view.zmap[i] : -INFINITY;
-      } else {
-        const int c = i < npos ? cid(i) : -1;
-        v[u] = c >= 0 ? zz[c] : -INFINITY;
+      for (int u = 0; u < KB; ++u) v[u] = view.zmap[min((k0 + u) * NT + tid, npos - 1)];
+    } else if (!view.idmap) {
+#pragma unroll
+      for (int u = 0; u < KB; ++u) v[u] = zz[view.id_base + min((k0 + u) * NT + tid, npos - 1)];
+    } else {
+      int c[KB];
+#pragma unroll
+      for (int u = 0; u < KB; ++u) c[u] = view.idmap[min((k0 + u) * NT + tid, npos - 1)];
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        v[u] = zz[max(c[u], 0)];
+        v[u] = c[u] >= 0 ? v[u] : -INFINITY;
       }
     }
 #pragma unroll
     for (int u = 0; u < KB; ++u)
       if (k0 + u < nk) {
+        if ((k0 + u) * NT + tid >= npos) v[u] = -INFINITY;
         const uint32_t ky = order_key(v[u] + 0.0f);  // + 0.0f folds -0 into +0
         if constexpr (LDSK) skeys[(k0 + u) * NT + tid] = ky;
         else skeys16[(k0 + u) * NT + tid] = (uint16_t)(ky >> 16);
       }
+  }
+  float guard_in = 0.f;
+  if (wave == NW - 1) {
+    float qn2 = gq[0] * gq[0] + gq[1] * gq[1];
+    float c2 = fmaxf(fmaxf(gc[0], gc[1]), fmaxf(gc[2], gc[3]));
+    for (int i = lane + 256; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
+    qn2 = wave_sum_f(qn2);
+    c2 = wave_max(c2);
+    const float steps = 48.f;  // covers the vector chain + tree and the MFMA accumulation alike
+    guard_in = 2.0f * steps * 5.9604645e-8f * sqrtf(qn2) * sqrtf(c2);
   }
   // fn(k, key of cluster k * NT + tid) for every sweep; wave-uniform trip count
   auto for_k = [&](auto fn) {
@@ -976,7 +994,7 @@ __device__ __forceinline__ int select_core(
     uint32_t khi = kmax + 1;   // count(>= khi) = 0 < r_eff
     int cnt_lo = nvalid, cnt_hi = 0;
     int it = 0;
-    if (npos > SEL_HIST_MIN) {
+    if (npos > SEL_HIST_MIN || view.idmap) {
       // Stage 0, one sweep: count the valid keys by their upper 16 bits (sign,
       // exponent, 7 mantissa bits) in the SEL_BINS buckets below the maximum's
       // (everything lower shares bin 0); a scan from the top finds the bucket
@@ -1961,10 +1979,9 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
     // Estimation terms of sw.est_rows clusters of one unit for its G heads, as a
     // stream: every group of LPR lanes takes rows of value sums with their
     // scores (read back from z) and sizes and keeps an online-softmax state, the
-    // cluster's score as the logit and its size as the multiplicity.  No barrier
-    // before the final merge, so the loads of many rows are in flight.
+    // cluster's score as the logit and its size as the multiplicity.
     constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
-    constexpr int GROUPS = NWV * RPW, U = 4;
+    constexpr int GROUPS = NWV * RPW, U = 4, UH = 4;
     static_assert(G <= LPR, "one lane per head's score");
     wg = xcd_logical_block(wg, sw.n_est_wgs) + sw.est_first;
     const int unit = wg / sw.est_chunks, chunk = wg - unit * sw.est_chunks;
@@ -1972,31 +1989,53 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
     const int bh0 = b * Hq + h * G;
     const int c0 = chunk * sw.est_rows, nrows = min(sw.est_rows, m - c0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sub = lane % LPR, grp = wave * RPW + lane / LPR, gbase = lane - sub;
+    const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
     AttnState<T, D, G> st;
-    st.init(q + (size_t)bh0 * D, sub, scale_log2);  // the queries themselves are not used: scores are given
+    st.reset();  // the queries are not needed: the scores are given
     const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
-    const float* zsrc = z + (size_t)(bh0 + (sub < G ? sub : 0)) * m + c0;  // lane sub fetches head sub's score
-    const int32_t* ssrc = sw.sizes + (size_t)unit * m + c0;
+    // The range's scores and sizes are staged in LDS with coalesced loads (a
+    // group's own 4-byte reads of them would be one memory request per row and
+    // head); the value sums stream with the next pass's rows already in flight.
+    float* zs = reinterpret_cast<float*>(lds_raw);              // [G][est_rows]
+    float* ms = zs + (size_t)G * sw.est_rows;                   // [est_rows], the size as a float
+    auto load_rows = [&](int i, uint4 (&dst)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) dst[u] = load16_stream(Vu + (size_t)min(i + u * GROUPS, nrows - 1) * D);
+    };
+    uint4 vnext[U];
+    load_rows(grp, vnext);  // (grp may lie beyond a short range: the clamped rows get weight 0)
+    for (int i = threadIdx.x; i < nrows; i += NT) {
+      float zv[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) zv[g] = z[(size_t)(bh0 + g) * m + c0 + i];
+      const int sz = sw.sizes[(size_t)unit * m + c0 + i];
+#pragma unroll
+      for (int g = 0; g < G; ++g) zs[g * sw.est_rows + i] = zv[g] * scale_log2;
+      ms[i] = (float)sz;
+    }
+    __syncthreads();
     for (int i = grp; i < nrows; i += GROUPS * U) {
       uint4 vraw[U];
-      float mine[U], mult[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int ii = i + u * GROUPS;
-        const int row = ii < nrows ? ii : i;
-        vraw[u] = load16_stream(Vu + (size_t)row * D);
-        mine[u] = ii < nrows ? zsrc[row] : -INFINITY;  // beyond the range: weight 0
-        mult[u] = (float)ssrc[row];
+      for (int u = 0; u < U; ++u) vraw[u] = vnext[u];
+      if (i + GROUPS * U < nrows) load_rows(i + GROUPS * U, vnext);
+#pragma unroll
+      for (int h0 = 0; h0 < U; h0 += UH) {  // UH rows per update of the state
+        float sc[G][UH], mult[UH];
+        uint4 vh[UH];
+#pragma unroll
+        for (int u = 0; u < UH; ++u) {
+          const int ii = i + (h0 + u) * GROUPS;
+          const int row = min(ii, nrows - 1);
+          vh[u] = vraw[h0 + u];
+          mult[u] = ms[row];
+#pragma unroll
+          for (int g = 0; g < G; ++g) sc[g][u] = ii < nrows ? zs[g * sw.est_rows + row] : -INFINITY;  // beyond: weight 0
+        }
+        st.template rows_given<UH>(sc, mult, vh);
       }
-      float sc[G][U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) sc[g][u] = __shfl(mine[u], gbase + g) * scale_log2;
-      }
-      st.template rows_given<U>(sc, mult, vraw);
     }
+    __syncthreads();  // the staged scores are read no more: the merge reuses the space
     merge_groups_and_store<T, D, G, NWV>(st, reinterpret_cast<float*>(lds_raw),
                                          part + ((size_t)bh0 * slots + sw.est_slot0 + chunk) * (D + 2),
                                          (size_t)slots * (D + 2));
@@ -2086,15 +2125,37 @@ __device__ __forceinline__ bool filter_slice(const T* __restrict__ q, const floa
   __shared__ int f_sh[4];
   __shared__ float f_shf[2];
 
-  // |q|^2 and max |C|^2: the error bound and the bound of the scores
+  // |q|^2 and max |C|^2 (the error bound and the bound of the scores) and the
+  // first tile maxima: all loads are issued before any is waited for
+  static_assert(D <= 128, "two query elements per lane");
+  float gq[2] = {0.f, 0.f}, gc[4] = {0.f, 0.f, 0.f, 0.f};
   if (wave == NW - 1) {
-    float qn2 = 0.f;
-    for (int i = lane; i < D; i += 64) {
-      const float v = to_f32(q[(size_t)bh * D + i]);
-      qn2 += v * v;
-    }
-    float c2 = 0.f;
-    for (int i = lane; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = to_f32(q[(size_t)bh * D + min(lane + 64 * j, D - 1)]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) gc[j] = cn2part[(size_t)unit * cn2_chunks + min(lane + 64 * j, cn2_chunks - 1)];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = lane + 64 * j < D ? gq[j] : 0.f;  // (a repeated maximum is harmless)
+  }
+  float tm0[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) tm0[u] = tm[min(u * NT + tid, ntile - 1)];  // clamped: repeats are masked below
+  // the slice's keys into LDS
+  const int nk = (len + NT - 1) / NT;  // <= VPT
+  constexpr int KB = 16;
+  for (int k0 = 0; k0 < nk; k0 += KB) {
+    float v[KB];
+#pragma unroll
+    for (int u = 0; u < KB; ++u) v[u] = zz[min((k0 + u) * NT + tid, len - 1)];
+#pragma unroll
+    for (int u = 0; u < KB; ++u)
+      if (k0 + u < nk)
+        skeys[(k0 + u) * NT + tid] = order_key(((k0 + u) * NT + tid < len ? v[u] : -INFINITY) + 0.0f);
+  }
+  if (wave == NW - 1) {
+    float qn2 = gq[0] * gq[0] + gq[1] * gq[1];
+    float c2 = fmaxf(fmaxf(gc[0], gc[1]), fmaxf(gc[2], gc[3]));
+    for (int i = lane + 256; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
     qn2 = wave_sum_f(qn2);
     c2 = wave_max(c2);
     const float qc = sqrtf(qn2) * sqrtf(c2);
@@ -2102,20 +2163,6 @@ __device__ __forceinline__ bool filter_slice(const T* __restrict__ q, const floa
       f_shf[0] = 2.0f * 48.f * 5.9604645e-8f * qc;  // as in the exact ranking
       f_shf[1] = qc * 1.001f;
     }
-  }
-  // the slice's keys into LDS
-  const int nk = (len + NT - 1) / NT;  // <= VPT
-  constexpr int KB = 16;
-  for (int k0 = 0; k0 < nk; k0 += KB) {
-    float v[KB];
-#pragma unroll
-    for (int u = 0; u < KB; ++u) {
-      const int i = (k0 + u) * NT + tid;
-      v[u] = i < len ? zz[i] : -INFINITY;
-    }
-#pragma unroll
-    for (int u = 0; u < KB; ++u)
-      if (k0 + u < nk) skeys[(k0 + u) * NT + tid] = order_key(v[u] + 0.0f);
   }
   for (int i = tid; i < SEL_BINS; i += NT) f_hist[i] = 0;
   if (tid < TBL) f_tbl[tid] = 0;
@@ -2127,13 +2174,10 @@ __device__ __forceinline__ bool filter_slice(const T* __restrict__ q, const floa
   for (int i0 = 0; i0 < ntile; i0 += NT * 8) {
     float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int i = i0 + u * NT + tid;
-      v[u] = i < ntile ? tm[i] : -INFINITY;
-    }
+    for (int u = 0; u < 8; ++u) v[u] = i0 == 0 ? tm0[u] : tm[min(i0 + u * NT + tid, ntile - 1)];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const uint32_t ky = order_key(v[u] + 0.0f);
+      const uint32_t ky = order_key((i0 + u * NT + tid < ntile ? v[u] : -INFINITY) + 0.0f);
       if (ky > kKeyNegInf) {
         uint32_t b16 = ky >> 16;
         b16 = b16 > top16 ? top16 : b16;  // cannot happen for finite inputs; keeps the index in range
@@ -2300,7 +2344,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   if (g.sliced) {  // the estimation terms come from 512-thread workgroups next to the slices
     g.est_rows = 512;
     g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
-    g.est_with_slices_pct = 20;  // share of the estimation ranges that ride with the slices
+    g.est_with_slices_pct = 10;  // share of the estimation ranges that ride with the slices
   }
   // Who takes the selected clusters' estimation terms out again: the retrieval
   // kernel itself (no partial of their own), except after the fused kernel and
@@ -2385,7 +2429,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
         const int npos_max = g.nslices * r;
         size_t lds_a = sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512);
         size_t lds_b = sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512);
-        const size_t lds_side = sizeof(float) * 8 * G * (D + 2);  // the side roles' final merge
+        // the side roles' final merge; the staged scores and sizes of an estimation range,
+        // (G + 1) * est_rows floats, use the same space before it
+        size_t lds_side = sizeof(float) * 8 * G * (D + 2);
+        if (lds_side < sizeof(float) * (G + 1) * (size_t)g.est_rows) lds_side = sizeof(float) * (G + 1) * (size_t)g.est_rows;
         if (lds_a < lds_side) lds_a = lds_side;
         if (lds_b < lds_side) lds_b = lds_side;
         const int n_est = units * g.est_chunks;
