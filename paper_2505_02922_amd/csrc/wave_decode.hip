@@ -69,7 +69,7 @@ struct DenseLds {
 // A: scores of clusters [c0, c0 + nrows) of one unit for its G heads, written to
 // z and left in lds.zw; every wave leaves the largest squared centroid norm it
 // saw in lds.red[wave][2 G].  The caller synchronises.
-template <typename T, int D, int G, int NT>
+template <typename T, int D, int G, int NT, bool PREFETCH = false>
 __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* __restrict__ C,
                                              const int32_t* __restrict__ su, float* __restrict__ z,
                                              int unit, int bh0, int m, int c0, int nrows,
@@ -108,16 +108,32 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
     const int lrow = lane / CPR, lch = lane % CPR;
     float cn2 = 0.f;
     const int ntile = (nrows + 15) / 16;
-    for (int t = wave; t < ntile; t += NWV) {
-      uint4 raw[NL];
+    // PREFETCH: the next tile's rows are requested before this tile is worked on
+    // (for short-lived workgroups, where few other waves cover the round trip).
+    auto load_tile = [&](int t, uint4 (&raw)[NL], int (&sz)[4]) {
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
         const int rr = min(16 * t + RPL * u + lrow, nrows - 1);
         raw[u] = load16_stream(Cu + (size_t)rr * D + lch * 8);
       }
-      int sz[4];
 #pragma unroll
       for (int v = 0; v < 4; ++v) sz[v] = su[min(16 * t + 4 * kb + v, nrows - 1)];
+    };
+    uint4 nraw[NL];
+    int nsz[4];
+    if (PREFETCH && wave < ntile) load_tile(wave, nraw, nsz);
+    for (int t = wave; t < ntile; t += NWV) {
+      uint4 raw[NL];
+      int sz[4];
+      if constexpr (PREFETCH) {
+#pragma unroll
+        for (int u = 0; u < NL; ++u) raw[u] = nraw[u];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sz[v] = nsz[v];
+        if (t + NWV < ntile) load_tile(t + NWV, nraw, nsz);
+      } else {
+        load_tile(t, raw, sz);
+      }
 #pragma unroll
       for (int u = 0; u < NL; ++u) store16(&tile[(RPL * u + lrow) * PITCH + lch * 16], raw[u]);
       __builtin_amdgcn_wave_barrier();  // the tile is wave-private: LDS executes a wave's accesses in order
@@ -350,7 +366,7 @@ __global__ __launch_bounds__(256, 4) void dense_kernel(const T* __restrict__ q, 
   const int bh0 = b * Hq + h * G;
   const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
   const int32_t* su = sizes + (size_t)unit * m + c0;
-  dense_scores<T, D, G, 256>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+  dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
   __syncthreads();
   if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
   dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
@@ -374,8 +390,8 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int bh0 = b * Hq + h * G;
   const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-  dense_scores<T, D, G, 256>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
-                             sizeof(T) == 2 ? tile_max : nullptr);
+  dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
+                                   sizeof(T) == 2 ? tile_max : nullptr);
   __syncthreads();
   if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
   if (sizeof(T) != 2 && tile_max) {  // (the bf16 pass writes them tile by tile)
@@ -1940,7 +1956,7 @@ __global__ __launch_bounds__(256) void dense_steady_kernel(
     const int bh0 = b * Hq + h * G;
     const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
     const int32_t* su = sizes + (size_t)unit * m + c0;
-    dense_scores<T, D, G, 256>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+    dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
     __syncthreads();
     if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
     dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
