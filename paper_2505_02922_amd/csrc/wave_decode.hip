@@ -1518,7 +1518,9 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
 // All NT threads of the workgroup must call this (it contains barriers).  Thread
 // t owns output dimension t % D and every (NT / D)-th partial result.
 // p: the head's `slots` partial results (max, sum, acc[D]).
-template <int D, int NT>
+// WIDE (the stand-alone merge launch, many slots): (max, sum) pairs as single
+// unconditional loads kept in registers, eight accumulation loads in flight.
+template <int D, int NT, bool WIDE = false>
 __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
                                            float* __restrict__ out_head, float* __restrict__ lse_head) {
   constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
@@ -1527,10 +1529,21 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
   __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
   __shared__ float red[NWV];
   __shared__ float accs[NSG * D];
-  // global maximum over the non-empty slots (independent loads, all in flight)
+  // global maximum over the non-empty slots; (max, sum) of a slot arrive as one
+  // unconditional 8-byte load (a load under a lane condition would be waited for
+  // on its own), and the first NT slots' pairs stay in registers for the weights
   float mloc = kNegBig;
-  for (int s = tid; s < slots; s += NT)
-    if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  float2 first = make_float2(kNegBig, 0.f);
+  if constexpr (WIDE) {
+    for (int s = tid; s < slots; s += NT) {
+      const float2 ml = *reinterpret_cast<const float2*>(p + (size_t)s * STR);
+      if (s == tid) first = ml;
+      if (ml.y != 0.f) mloc = fmaxf(mloc, ml.x);
+    }
+  } else {
+    for (int s = tid; s < slots; s += NT)
+      if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+  }
   mloc = wave_max(mloc);
   if ((tid & 63) == 0) red[tid >> 6] = mloc;
   __syncthreads();
@@ -1541,22 +1554,52 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
   for (int base = 0; base < slots; base += TILE) {
     const int n = min(TILE, slots - base);
     __syncthreads();
-    for (int s = tid; s < n; s += NT) {
-      const float ls = p[(size_t)(base + s) * STR + 1];
-      const float w = ls != 0.f ? exp2f(p[(size_t)(base + s) * STR] - M) : 0.f;
+    for (int s = tid; s < n; s += NT) {  // TILE <= NT: at most one slot per thread
+      float2 ml;
+      if constexpr (WIDE) {
+        ml = base + s == tid ? first : *reinterpret_cast<const float2*>(p + (size_t)(base + s) * STR);
+      } else {
+        ml.y = p[(size_t)(base + s) * STR + 1];
+        ml.x = ml.y != 0.f ? p[(size_t)(base + s) * STR] : M;
+      }
+      const float w = ml.y != 0.f ? exp2f(ml.x - M) : 0.f;
       wgt[s] = w;
-      zloc = fmaf(ls, w, zloc);
+      zloc = fmaf(ml.y, w, zloc);
     }
     __syncthreads();
     const float* pe = p + (size_t)base * STR + 2 + e;
     int s = sg;
-    for (; s + 3 * NSG < n; s += 4 * NSG) {
-      A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
-      A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
-      A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
-      A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
+    if constexpr (!WIDE) {
+      for (; s + 3 * NSG < n; s += 4 * NSG) {
+        A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
+        A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
+        A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
+        A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
+      }
+      for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
+      continue;
     }
-    for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
+    for (; s + 7 * NSG < n; s += 8 * NSG) {  // eight independent loads in flight
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = pe[(size_t)(s + u * NSG) * STR];
+      A0 = fmaf(v[0], wgt[s + 0 * NSG], A0);
+      A1 = fmaf(v[1], wgt[s + 1 * NSG], A1);
+      A2 = fmaf(v[2], wgt[s + 2 * NSG], A2);
+      A3 = fmaf(v[3], wgt[s + 3 * NSG], A3);
+      A0 = fmaf(v[4], wgt[s + 4 * NSG], A0);
+      A1 = fmaf(v[5], wgt[s + 5 * NSG], A1);
+      A2 = fmaf(v[6], wgt[s + 6 * NSG], A2);
+      A3 = fmaf(v[7], wgt[s + 7 * NSG], A3);
+    }
+    {  // the remaining slots, up to seven per thread, again with unconditional loads
+      float v[7];
+#pragma unroll
+      for (int u = 0; u < 7; ++u) v[u] = pe[(size_t)min(s + u * NSG, n - 1) * STR];
+#pragma unroll
+      for (int u = 0; u < 7; ++u)
+        if (s + u * NSG < n) A0 = fmaf(v[u], wgt[s + u * NSG], A0);
+    }
   }
   zloc = wave_sum_f(zloc);
   __syncthreads();
@@ -1758,7 +1801,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(const float* __res
                                                               int slot_stride, float* __restrict__ out,
                                                               float* __restrict__ lse) {
   const int bh = blockIdx.x;  // a head's partials are slot_stride slots apart; the first `slots` count
-  merge_head<D, MERGE_THREADS>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
+  merge_head<D, MERGE_THREADS, true>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
                                lse + bh);
 }
 
