@@ -2400,10 +2400,23 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
               (long long)g.nslices * r <= 16384) ? 1 : 0;
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and (see below) the selected clusters' estimation terms with a minus sign
-  if (g.sliced) {  // the estimation terms come from 512-thread workgroups next to the slices
-    g.est_rows = 512;
+  if (g.sliced) {
+    // The estimation terms come from 512-thread workgroups in the launch that ranks the
+    // union of the slices' lists.  A range is sized so that those workgroups and the
+    // ranking ones are all resident at once (2 workgroups per CU up to 4 heads per KV
+    // head, else 1): a second round of long-lived workgroups would double the launch.
+    const int G = Hq / ix.Hkv;
+    const int resident = 256 * (G <= 4 ? 2 : 1);
+    int chunks = (resident - heads) / units;
+    if (chunks < 1) chunks = 1;
+    int rows = (m + chunks - 1) / chunks;
+    rows = (rows + 63) / 64 * 64;
+    const int rows_max = 10240 / (G + 1) / 64 * 64;  // staged scores and sizes: (G + 1) * rows floats of LDS
+    if (rows > rows_max) rows = rows_max;
+    if (rows < 512) rows = 512;
+    g.est_rows = rows;
     g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
-    g.est_with_slices_pct = 10;  // share of the estimation ranges that ride with the slices
+    g.est_with_slices_pct = 0;  // share of the estimation ranges in the slices' launch instead
   }
   // Who takes the selected clusters' estimation terms out again: the retrieval
   // kernel itself (no partial of their own), except after the fused kernel and
