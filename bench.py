@@ -263,7 +263,7 @@ def main() -> int:
     bytes_k = {                      # algorithmic bytes by kernel (either launch split)
         "meta_index": meta, "steady": steady_b, "gather": gather_b, "select_gather": gather_b,
         "select_gather_steady": gather_b + steady_b, "select": 0, "merge": 0,
-        "scores": meta // 2, "select_slices+side": 0, "select+side": meta // 2 + steady_b,
+        "scores": meta // 2, "select_slices+side": steady_b, "select+side": meta // 2,
         "gather+merge": gather_b, "meta_index+steady": meta + steady_b,
     }
     step_bytes = meta + steady_b + gather_b
