@@ -419,6 +419,7 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
 constexpr int CAND_CAP = 1024;
 constexpr int SURV_CAP = 256;  // scores left for the single-wave end of the threshold search
 constexpr int SEL_BINS = 2048; // buckets of the one-sweep histogram that starts the threshold search
+constexpr int SEL_TOP_BINS = 256;  // of which are counted one by one when there are few scores
 constexpr int SEL_HIST_MIN = 6144;  // below this many scores plain halving steps are as fast
 
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -1017,14 +1018,21 @@ __device__ __forceinline__ int select_core(
       // that holds the r-th largest key, which replaces most halving steps.
       const uint32_t top16 = kmax >> 16;
       const uint32_t lo16 = top16 >= (uint32_t)(SEL_BINS - 1) ? top16 - (SEL_BINS - 1) : 0u;
+      // LDS atomics run at about a lane per clock, so with few scores only the
+      // top SEL_TOP_BINS buckets (two binades below the maximum) are counted one
+      // by one; the keys below them are counted by ballot into bin 0.
+      const uint32_t first_bin = npos <= 16384 ? (uint32_t)(SEL_BINS - SEL_TOP_BINS) : 1u;
       for (int i = tid; i < SEL_BINS; i += NT) hist[i] = 0;
       __syncthreads();
+      int low = 0;
       for_k([&](int, uint32_t ky) {
-        if (ky > kKeyNegInf) {
-          const uint32_t b16 = ky >> 16;
-          atomicAdd(&hist[b16 > lo16 ? b16 - lo16 : 0u], 1);
-        }
+        const bool valid = ky > kKeyNegInf;
+        const uint32_t b16 = ky >> 16;
+        const uint32_t rel = b16 > lo16 ? b16 - lo16 : 0u;
+        if (valid && rel >= first_bin) atomicAdd(&hist[rel], 1);
+        low += __popcll(__ballot(valid && rel < first_bin));
       });
+      if (lane == 0 && low > 0) atomicAdd(&hist[0], low);
       __syncthreads();
       constexpr int PER = SEL_BINS / NT;
       static_assert(PER >= 1 && PER * NT == SEL_BINS, "bins per thread");
@@ -1050,7 +1058,8 @@ __device__ __forceinline__ int select_core(
       cnt_hi = sh_i[1];
       cnt_lo = sh_i[3];
       if (bsel > 0) klo = (lo16 + (uint32_t)bsel) << 16;                  // count(>= klo) = cnt_lo
-      if (bsel < SEL_BINS - 1) khi = (lo16 + (uint32_t)bsel + 1u) << 16;  // count(>= khi) = cnt_hi
+      if (bsel < SEL_BINS - 1)                                            // count(>= khi) = cnt_hi
+        khi = (lo16 + (bsel > 0 ? (uint32_t)bsel + 1u : first_bin)) << 16;
       __syncthreads();  // sh_i is reused below
     }
     if constexpr (!LDSK) {
@@ -1867,7 +1876,6 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   };
   const bool steady_first = ((blockIdx.x / stagger_period) & 1) == 0;
   if (p > 0 && steady_first) steady_rows();
-
   int ntok;
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
