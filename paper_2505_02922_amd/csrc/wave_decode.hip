@@ -1890,8 +1890,6 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   const int nsel_all = sh_n[0], total = sh_n[1];
 
   const bool staged = nsel_all <= FUSED_STAGE;
-  const int32_t* pref = staged ? s_pref : sel_pref + (size_t)bh * (rcap + 1);
-  const int32_t* srow = staged ? s_row : sel_row + (size_t)bh * rcap;
   const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
   const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
   for (int base = 0; base < total; base += TILE) {
@@ -1899,12 +1897,18 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
     __syncthreads();
     if ((int)threadIdx.x < n) {
       const int t = base + threadIdx.x;
-      int a = 0, e = nsel_all;  // largest a with pref[a] <= t
-      while (e - a > 1) {
-        const int mid = (a + e) >> 1;
-        if (pref[mid] <= t) a = mid; else e = mid;
-      }
-      rowidx[threadIdx.x] = srow[a] + (t - pref[a]);
+      // largest a with pref[a] <= t; two copies so that the staged tables are read
+      // with LDS instructions (one pointer for both would make every read a flat load)
+      auto row_of = [&](const int32_t* pf, const int32_t* sr) {
+        int a = 0, e = nsel_all;
+        while (e - a > 1) {
+          const int mid = (a + e) >> 1;
+          if (pf[mid] <= t) a = mid; else e = mid;
+        }
+        return sr[a] + (t - pf[a]);
+      };
+      rowidx[threadIdx.x] = staged ? row_of(s_pref, s_row)
+                                   : row_of(sel_pref + (size_t)bh * (rcap + 1), sel_row + (size_t)bh * rcap);
     }
     __syncthreads();
     for (int i = grp; i < n; i += GROUPS * U) {
