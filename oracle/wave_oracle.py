@@ -22,7 +22,9 @@ every cluster retrieved equals brute force; singleton clusters and
 identical-key clusters make estimation exact; zone weights sum to one; the
 Jensen bound of the estimation section; shift invariance; meta-index
 conservation laws; k-means objective monotonicity and brute-force optimum on
-tiny inputs; splitmix64 published outputs; bf16 rounding against enumeration.
+tiny inputs; splitmix64 published outputs; bf16 rounding against enumeration;
+the incremental update against a fresh build of the grown context when the
+segments line up, against itself in one step or two, and against brute force.
 Parity unpinned: the size of the approximation error against full attention at
 the paper's budgets (the paper gives task accuracies on datasets only).
 """
@@ -262,6 +264,63 @@ def build_unit(K: np.ndarray, V: np.ndarray, plan: Plan, T: int, seed: int, b: i
     if keep_exact:
         return ix, C, VS
     return ix
+
+
+# --------------------------------------------------------------------------
+# Incremental update of one unit's index
+# --------------------------------------------------------------------------
+def append_unit(ix: UnitIndex, K_new: np.ndarray, V_new: np.ndarray, n_local_min: int, U: int,
+                k_u: int, T: int, seed: int, b: int, h: int) -> UnitIndex:
+    """Index update during decoding ("Lightweight Index Construction", last
+    paragraph).  New tokens join the local window of the steady zone.  Whenever
+    the window holds a whole update segment of U tokens beyond its n_local_min
+    most recent ones, its U oldest tokens are clustered on their own, exactly as
+    a segment of the initial build (same seeding rule with the segment's number,
+    same iterations), into min(k_u, U) clusters that are appended to the index;
+    nothing indexed before is touched.  Reading taken: the window is flushed in
+    whole segments, oldest first, as many as fit; the remainder (between
+    n_local_min and n_local_min + U - 1 tokens) stays local.  Returns the new
+    index; `ix` is not modified."""
+    K_new = np.asarray(K_new, dtype=np.float64)
+    V_new = np.asarray(V_new, dtype=np.float64)
+    plan, dtype = ix.plan, ix.dtype
+    ns = plan.n_sink
+    d = ix.k_steady.shape[1]
+    WK = np.concatenate([ix.k_steady[ns:], K_new.reshape(-1, d)])   # positions local_start ...
+    WV = np.concatenate([ix.v_steady[ns:], V_new.reshape(-1, d)])
+    F = max(0, (WK.shape[0] - int(n_local_min)) // int(U))
+    ks = min(int(k_u), int(U))
+    new_plan = Plan(plan.N + K_new.reshape(-1, d).shape[0], ns, plan.local_start + F * U,
+                    list(plan.seg_start), list(plan.seg_len), list(plan.seg_k),
+                    list(plan.seg_cluster_base))
+    C, VS, sizes = [ix.centroids], [ix.vsum], [np.asarray(ix.sizes, dtype=np.int64)]
+    perm, kp, vp, asg = [ix.perm], [ix.k_perm], [ix.v_perm], [ix.assign]
+    for f in range(F):
+        s, lo, base = plan.S + f, plan.local_start + f * U, plan.m + f * ks
+        new_plan.seg_start.append(lo)
+        new_plan.seg_len.append(U)
+        new_plan.seg_k.append(ks)
+        new_plan.seg_cluster_base.append(base)
+        Kseg, Vseg = WK[f * U:(f + 1) * U], WV[f * U:(f + 1) * U]
+        a = kmeans_segment(Kseg, init_indices(seed, b, h, s, U, ks), T, dtype)
+        Cs, VSs, ss = np.zeros((ks, d)), np.zeros((ks, d)), np.zeros(ks, dtype=np.int64)
+        order = []
+        for i in range(ks):
+            members = np.nonzero(a == i)[0]                    # ascending positions
+            ss[i] = members.size
+            if members.size:
+                Cs[i] = Kseg[members].sum(axis=0) / members.size
+                VSs[i] = Vseg[members].sum(axis=0)
+            order.append(members)
+        order = np.concatenate(order)
+        C.append(quant(Cs, dtype)); VS.append(quant(VSs, dtype)); sizes.append(ss)
+        perm.append(order + lo); kp.append(Kseg[order]); vp.append(Vseg[order]); asg.append(a + base)
+    sizes = np.concatenate(sizes)
+    return UnitIndex(new_plan, dtype, np.concatenate(C), np.concatenate(VS), sizes,
+                     np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64), np.concatenate(perm),
+                     np.concatenate(kp), np.concatenate(vp),
+                     np.concatenate([ix.k_steady[:ns], WK[F * U:]]),
+                     np.concatenate([ix.v_steady[:ns], WV[F * U:]]), np.concatenate(asg))
 
 
 # --------------------------------------------------------------------------

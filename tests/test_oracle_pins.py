@@ -313,6 +313,83 @@ def dataclasses_replace(ix, **kw):
     return dataclasses.replace(ix, **kw)
 
 
+# ---------------------------------------------------------------- incremental update pins
+def _grown_context(seed, dtype, N0, n_new, d=16, ncomp=10):
+    g = _rng(seed)
+    means = g.standard_normal((ncomp, d))
+    K = wo.quant(means[g.integers(0, ncomp, N0 + n_new)] + 0.3 * g.standard_normal((N0 + n_new, d)), dtype)
+    V = wo.quant(g.standard_normal((N0 + n_new, d)), dtype)
+    q = wo.quant(means[2] + 0.5 * g.standard_normal(d), dtype)
+    return K, V, q
+
+
+def _same_index(a, b):
+    for name in ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_perm", "k_steady",
+                 "v_steady", "assign"):
+        assert np.array_equal(getattr(a, name), getattr(b, name)), name
+    assert (a.plan.N, a.plan.local_start, a.plan.seg_start, a.plan.seg_len, a.plan.seg_k) == \
+           (b.plan.N, b.plan.local_start, b.plan.seg_start, b.plan.seg_len, b.plan.seg_k)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_append_equals_a_fresh_build_when_the_segments_line_up(dtype):
+    """Update segments as long as the build's, an indexed range that is a whole number of
+    them: the grown index must be, array by array, the index built from scratch over the
+    grown context with the local window the update leaves (Wave Index, "Lightweight Index
+    Construction": new clusters are appended, nothing is re-clustered)."""
+    ns, nl, L, k, T = 2, 5, 32, 4, 4
+    N0, n_new = ns + 2 * L + nl, 75          # window 5 + 75 = 80 = 2 segments + 16 local
+    K, V, _ = _grown_context(11, dtype, N0, n_new)
+    base = wo.build_unit(K[:N0], V[:N0], wo.make_plan(N0, ns, nl, L, k), T, 9, 1, 2, dtype)
+    grown = wo.append_unit(base, K[N0:], V[N0:], nl, L, k, T, 9, 1, 2)
+    fresh = wo.build_unit(K, V, wo.make_plan(N0 + n_new, ns, 16, L, k), T, 9, 1, 2, dtype)
+    assert grown.plan.S == 4 and grown.k_steady.shape[0] == ns + 16
+    _same_index(grown, fresh)
+
+
+def test_append_in_one_step_or_in_two_is_the_same():
+    ns, nl, L, k, U, ku, T = 3, 7, 40, 5, 16, 3, 3
+    N0, n_new = 130, 61
+    K, V, _ = _grown_context(12, "f32", N0, n_new)
+    base = wo.build_unit(K[:N0], V[:N0], wo.make_plan(N0, ns, nl, L, k), T, 5, 0, 0, "f32")
+    once = wo.append_unit(base, K[N0:], V[N0:], nl, U, ku, T, 5, 0, 0)
+    half = wo.append_unit(base, K[N0:N0 + 22], V[N0:N0 + 22], nl, U, ku, T, 5, 0, 0)
+    twice = wo.append_unit(half, K[N0 + 22:], V[N0 + 22:], nl, U, ku, T, 5, 0, 0)
+    _same_index(once, twice)
+    assert once.plan.S == base.plan.S + (nl + n_new - nl) // U
+    # the index before the update is a prefix of the index after it
+    for name in ("centroids", "vsum", "sizes", "perm", "k_perm", "v_perm"):
+        assert np.array_equal(getattr(once, name)[:getattr(base, name).shape[0]], getattr(base, name))
+
+
+@pytest.mark.parametrize("n_new", [1, 9, 40])
+def test_append_keeps_every_token_once(n_new):
+    """Without a full update segment only the window grows; with one, its tokens move into
+    the index.  Either way every token of the grown context is in exactly one place, the
+    meta index still obeys its conservation laws, and retrieving every cluster gives
+    brute-force attention over the grown context."""
+    ns, nl, L, k, U, ku, T = 2, 6, 48, 6, 16, 4, 3
+    N0 = 120
+    K, V, q = _grown_context(13, "f32", N0, n_new)
+    base = wo.build_unit(K[:N0], V[:N0], wo.make_plan(N0, ns, nl, L, k), T, 3, 0, 1, "f32")
+    ix = wo.append_unit(base, K[N0:], V[N0:], nl, U, ku, T, 3, 0, 1)
+    F = n_new // U
+    assert ix.plan.S == base.plan.S + F and ix.plan.m == base.plan.m + F * ku
+    assert ix.k_steady.shape[0] == ns + nl + n_new - F * U
+    where = np.concatenate([np.arange(ns), ix.perm, np.arange(ix.plan.local_start, N0 + n_new)])
+    assert np.array_equal(np.sort(where), np.arange(N0 + n_new))
+    assert np.array_equal(ix.k_perm, K[ix.perm]) and np.array_equal(ix.k_steady[ns:], K[ix.plan.local_start:])
+    assert ix.sizes.sum() == ix.perm.size == ix.offsets[-1]
+    for c in range(base.plan.m, ix.plan.m):
+        rows = slice(ix.offsets[c], ix.offsets[c + 1])
+        if ix.sizes[c]:
+            assert np.allclose(ix.centroids[c], ix.k_perm[rows].mean(axis=0), atol=1e-6)
+            assert np.allclose(ix.vsum[c], ix.v_perm[rows].sum(axis=0), atol=1e-6)
+    o, lse, _ = wo.decode_unit(q, ix, r=ix.plan.m)
+    of, lsef = wo.full_attention(q, K, V)
+    assert np.allclose(o, of, rtol=0, atol=1e-12) and abs(lse - lsef) < 1e-12
+
+
 def test_selection_order_and_ties():
     q = np.array([1.0, 0.0])
     C = np.array([[3.0, 0], [5.0, 0], [5.0, 1], [9.0, 0], [1.0, 0]])
