@@ -79,6 +79,12 @@ typedef struct {
   void *k_perm, *v_perm;        /* DEVICE [B,Hkv,N_idx,d] dtype, rows ordered by       */
                                 /*        (segment, cluster, original position)        */
   void *k_steady, *v_steady;    /* DEVICE [B,Hkv,p,d] dtype: sink rows then local rows */
+  int32_t appended_segments;    /* update segments appended by wave_index_append (0 for */
+                                /* a freshly built index); they follow the S - this     */
+                                /* many segments of the build                           */
+  int32_t update_segment_len;   /* their length U and ...                               */
+  int32_t update_clusters;      /* ... clusters per update segment (min(k_u, U) each)   */
+  int32_t reserved2_;
 } wave_index;
 
 enum { WAVE_INDEX_BUFFERS = 9 };
@@ -93,6 +99,35 @@ enum { WAVE_INDEX_BUFFERS = 9 };
 wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
                             size_t *build_workspace_bytes, int Hq, int topk_clusters,
                             size_t *decode_workspace_bytes);
+
+/* Index update during decoding ("Lightweight Index Construction", last
+ * paragraph): n_new new tokens per unit join the local window of the steady
+ * zone; whenever the window holds a whole update segment of U tokens beyond
+ * its n_local_min most recent ones, its U oldest tokens are clustered on their
+ * own (as a segment of the build: same seeding rule with the segment's number,
+ * same arithmetic) into min(k_u, U) clusters, which are appended to the index.
+ * Nothing indexed before changes.  The result is written as a NEW index with
+ * arrays of its own (this library's arrays are dense per unit, so an index with
+ * more clusters has other strides); when no segment is flushed only the steady
+ * rows differ from the old index.
+ *
+ * wave_index_append_plan (host only): fills *new_ix (dimensions, derived
+ * fields; N = old N + n_new, n_local = what stays in the window), the byte
+ * sizes of its nine buffers and the workspace wave_index_append needs.  An
+ * index that already holds update segments takes the same U and k_u again.
+ *
+ * wave_index_append: old_ix read only; K_new, V_new DEVICE [B,Hkv,n_new,d]
+ * dtype (may be NULL when n_new = 0); new_ix as planned, with its nine DEVICE
+ * buffers (written; must not overlap old_ix's); workspace DEVICE, 256-byte
+ * aligned.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
+ * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
+wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,
+                                   int update_segment_len, int update_clusters, wave_index *new_ix,
+                                   size_t bytes[WAVE_INDEX_BUFFERS], size_t *workspace_bytes);
+wave_status wave_index_append(const wave_index *old_ix, const void *K_new, const void *V_new,
+                              int n_new, int n_local_min, int update_segment_len,
+                              int update_clusters, int iters, uint64_t seed, wave_index *new_ix,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Index construction ("Index Organization", "Lightweight Index Construction"):
  * per unit and per segment of L tokens, spherical k-means on the centred,

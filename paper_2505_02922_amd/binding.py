@@ -21,7 +21,8 @@ BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_pe
                 "v_steady")
 STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
                 4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
-EXPORTS = ("wave_index_plan", "wave_index_build", "wave_attention_decode",
+EXPORTS = ("wave_index_plan", "wave_index_build", "wave_index_append_plan", "wave_index_append",
+           "wave_attention_decode",
            "wave_attention_decode_budget_workspace", "wave_attention_decode_budget",
            "wave_full_attention_workspace", "wave_full_attention_decode", "wave_init_indices",
            "wave_kmeans_assign_step", "wave_calibration_copy", "wave_calibration_read",
@@ -39,7 +40,9 @@ class wave_index(ctypes.Structure):
                 ("sizes", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
                 ("perm", ctypes.c_void_p), ("k_perm", ctypes.c_void_p),
                 ("v_perm", ctypes.c_void_p), ("k_steady", ctypes.c_void_p),
-                ("v_steady", ctypes.c_void_p)]
+                ("v_steady", ctypes.c_void_p),
+                ("appended_segments", ctypes.c_int32), ("update_segment_len", ctypes.c_int32),
+                ("update_clusters", ctypes.c_int32), ("reserved2_", ctypes.c_int32)]
 
 
 class WaveError(RuntimeError):
@@ -64,6 +67,11 @@ def lib() -> ctypes.CDLL:
         L.wave_index_plan.argtypes = [ctypes.POINTER(wave_index), ctypes.POINTER(sz),
                                       ctypes.POINTER(sz), i32, i32, ctypes.POINTER(sz)]
         L.wave_index_build.argtypes = [vp, vp, ctypes.POINTER(wave_index), i32, u64, vp, sz, vp]
+        L.wave_index_append_plan.argtypes = [ctypes.POINTER(wave_index), i32, i32, i32, i32,
+                                             ctypes.POINTER(wave_index), ctypes.POINTER(sz),
+                                             ctypes.POINTER(sz)]
+        L.wave_index_append.argtypes = [ctypes.POINTER(wave_index), vp, vp, i32, i32, i32, i32, i32,
+                                        u64, ctypes.POINTER(wave_index), vp, sz, vp]
         L.wave_attention_decode.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32, vp,
                                             vp, vp, vp, sz, vp]
         L.wave_attention_decode_budget_workspace.argtypes = [ctypes.POINTER(wave_index), i32, i32, i32]
@@ -121,7 +129,8 @@ class Index:
 
     def __getattr__(self, name):
         if name in ("B", "Hkv", "d", "N", "n_sink", "n_local", "segment_len",
-                    "clusters_per_segment", "S", "m", "N_idx", "p"):
+                    "clusters_per_segment", "S", "m", "N_idx", "p", "appended_segments",
+                    "update_segment_len", "update_clusters"):
             return getattr(self.c, name)
         if name in BUFFER_NAMES:
             return self.t[name]
@@ -189,6 +198,44 @@ def wave_index_build(K: torch.Tensor, V: torch.Tensor, n_sink: int, n_local: int
         raise WaveError(st, "wave_index_build")
     ix._keepalive = (K, V, ws)
     return ix
+
+
+def wave_index_append(ix: Index, K_new: Optional[torch.Tensor], V_new: Optional[torch.Tensor],
+                      n_local_min: int, update_segment_len: int, update_clusters: int, iters: int,
+                      seed: int) -> Index:
+    """K_new, V_new: [B, Hkv, n_new, d] device tensors of the index's dtype (None for no new
+    tokens).  Plans and allocates the grown index, enqueues the update on the current stream
+    and returns the new index (valid after a stream sync); `ix` is left as it is."""
+    n_new = 0 if K_new is None else K_new.shape[2]
+    if n_new:
+        assert K_new.is_cuda and V_new.is_cuda and K_new.shape == V_new.shape and K_new.dtype == ix.dtype
+        assert K_new.shape[:2] == (ix.B, ix.Hkv) and K_new.shape[3] == ix.d
+        K_new, V_new = K_new.contiguous(), V_new.contiguous()
+    c = wave_index()
+    sizes = (ctypes.c_size_t * WAVE_INDEX_BUFFERS)()
+    wsb = ctypes.c_size_t(0)
+    st = lib().wave_index_append_plan(ctypes.byref(ix.c), n_new, n_local_min, update_segment_len,
+                                      update_clusters, ctypes.byref(c), sizes, ctypes.byref(wsb))
+    if st != 0:
+        raise WaveError(st, "wave_index_append_plan")
+    device = ix.t["k_steady"].device if ix.t["k_steady"].numel() else ix.t["k_perm"].device
+    tensors = {}
+    for name, nbytes in zip(BUFFER_NAMES, sizes):
+        dt = torch.int32 if name in ("sizes", "offsets", "perm") else ix.dtype
+        t = torch.empty(_shapes(c)[name], dtype=dt, device=device)
+        assert t.numel() * t.element_size() == nbytes, (name, t.shape, nbytes)
+        tensors[name] = t
+        setattr(c, name, _ptr(t))
+    ws = workspace(wsb.value, device)
+    st = lib().wave_index_append(ctypes.byref(ix.c), _ptr(K_new) if n_new else None,
+                                 _ptr(V_new) if n_new else None, n_new, n_local_min,
+                                 update_segment_len, update_clusters, iters, seed, ctypes.byref(c),
+                                 ws.data_ptr(), ws.numel(), _stream())
+    if st != 0:
+        raise WaveError(st, "wave_index_append")
+    out = Index(c, tensors, ix.dtype, 0)
+    out._keepalive = (K_new, V_new, ws, ix)
+    return out
 
 
 def decode_workspace_bytes(ix: Index, Hq: int, topk_clusters: int) -> int:

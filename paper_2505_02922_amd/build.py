@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libwave.so")
-SOURCES = ["wave_api.hip", "wave_decode.hip", "wave_build.hip"]
+SOURCES = ["wave_api.hip", "wave_decode.hip", "wave_build.hip", "wave_append.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",
          "-Wno-unused-function",
          # packed fp32 instructions are kept out of the generated code

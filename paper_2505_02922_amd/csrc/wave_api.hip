@@ -103,6 +103,11 @@ static wave_status check_dims(const wave_index* ix) {
   if (ix->segment_len < 1 || ix->clusters_per_segment < 1) return WAVE_ERR_ARG;
   if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
   if (ix->clusters_per_segment > 4096) return WAVE_ERR_SHAPE;
+  if (ix->appended_segments < 0) return WAVE_ERR_ARG;
+  if (ix->appended_segments > 0) {
+    if (ix->update_segment_len < 1 || ix->update_clusters < 1) return WAVE_ERR_ARG;
+    if (ix->update_clusters > 4096) return WAVE_ERR_SHAPE;
+  }
   return WAVE_OK;
 }
 
@@ -117,9 +122,17 @@ static Derived derive(const wave_index& ix) {
   d.N_idx = d.local_start - d.ns;
   d.p = d.ns + (ix.N - d.local_start);
   const int L = ix.segment_len, k = ix.clusters_per_segment;
-  d.S = (d.N_idx + L - 1) / L;
-  const int full = d.N_idx / L, tail = d.N_idx - full * L;
-  d.m = full * (k < L ? k : L) + (tail > 0 ? (k < tail ? k : tail) : 0);
+  // the build's segments tile the indexed range without the update segments behind them
+  const int A = ix.appended_segments, U = ix.update_segment_len;
+  const int ku = ix.update_clusters < U ? ix.update_clusters : U;
+  long long built = (long long)d.N_idx - (long long)A * U;
+  if (A == 0) built = d.N_idx;
+  if (built < 0) built = -1;  // inconsistent: no plan matches
+  const int nb = (int)built;
+  d.S = (nb + L - 1) / L + A;
+  const int full = nb / L, tail = nb - full * L;
+  d.m = full * (k < L ? k : L) + (tail > 0 ? (k < tail ? k : tail) : 0) + (A > 0 ? A * ku : 0);
+  if (built < 0) d.m = -1;
   return d;
 }
 
@@ -190,6 +203,7 @@ wave_status wave_index_build(const void* K, const void* V, wave_index* ix, int i
   if (st != WAVE_OK) return st;
   if (!K || !V || iters < 1) return WAVE_ERR_ARG;
   if (!aligned16(K) || !aligned16(V)) return WAVE_ERR_ARG;
+  if (ix->appended_segments != 0) return WAVE_ERR_SHAPE;  // the build tiles the whole range with L
   if (!planned_fields_match(*ix)) return WAVE_ERR_SHAPE;
   st = check_index_buffers(*ix);
   if (st != WAVE_OK) return st;
@@ -197,6 +211,121 @@ wave_status wave_index_build(const void* K, const void* V, wave_index* ix, int i
   if (g.total > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total))
     return WAVE_ERR_WORKSPACE;
   return launch_build(K, V, *ix, iters, seed, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// ----------------------------------------------------------------------------
+// Incremental update
+// ----------------------------------------------------------------------------
+extern "C++" {
+namespace wave {
+AppendGeom append_geometry(const wave_index& old_ix, int n_new, int n_local_min, int U, int k_u) {
+  AppendGeom g{};
+  const Derived d = derive(old_ix);
+  g.lc_old = old_ix.N - d.local_start;
+  const long long window = (long long)g.lc_old + n_new - n_local_min;
+  g.F = window > 0 ? (int)(window / U) : 0;
+  g.ks = k_u < U ? k_u : U;
+  wave_index& mi = g.mini;
+  mi = wave_index{};
+  mi.dtype = old_ix.dtype;
+  mi.B = old_ix.B;
+  mi.Hkv = old_ix.Hkv;
+  mi.d = old_ix.d;
+  mi.N = g.F * U;
+  mi.segment_len = U;
+  mi.clusters_per_segment = k_u;
+  mi.S = g.F;
+  mi.m = g.F * g.ks;
+  mi.N_idx = g.F * U;
+  const size_t es = old_ix.dtype == WAVE_BF16 ? 2 : 4, units = (size_t)old_ix.B * old_ix.Hkv;
+  const size_t rows = units * (size_t)mi.N_idx * old_ix.d * es, crow = units * (size_t)mi.m * old_ix.d * es;
+  size_t o = 0;
+  g.off_k = o;       o = align_up(o + rows);
+  g.off_v = o;       o = align_up(o + rows);
+  g.off_c = o;       o = align_up(o + crow);
+  g.off_vs = o;      o = align_up(o + crow);
+  g.off_sizes = o;   o = align_up(o + units * (size_t)mi.m * 4);
+  g.off_offsets = o; o = align_up(o + units * ((size_t)mi.m + 1) * 4);
+  g.off_perm = o;    o = align_up(o + units * (size_t)mi.N_idx * 4);
+  g.off_kp = o;      o = align_up(o + rows);
+  g.off_vp = o;      o = align_up(o + rows);
+  g.off_build = o;
+  if (g.F > 0) o = align_up(o + build_geometry(mi).total);
+  g.total = g.F > 0 ? o : 0;
+  return g;
+}
+}  // namespace wave
+}  // extern "C++"
+
+static wave_status plan_append(const wave_index* old_ix, int n_new, int n_local_min, int U, int k_u,
+                               wave_index* out) {
+  wave_status st = check_dims(old_ix);
+  if (st != WAVE_OK) return st;
+  if (!out || n_new < 0 || n_local_min < 0 || U < 1 || k_u < 1) return WAVE_ERR_ARG;
+  if (k_u > 4096) return WAVE_ERR_SHAPE;
+  if (!planned_fields_match(*old_ix)) return WAVE_ERR_SHAPE;
+  if (old_ix->N < old_ix->n_sink) return WAVE_ERR_SHAPE;  // the sink zone itself is still filling
+  if (old_ix->appended_segments > 0 &&
+      (U != old_ix->update_segment_len || k_u != old_ix->update_clusters))
+    return WAVE_ERR_SHAPE;
+  if ((long long)old_ix->N + n_new >= (1ll << 31)) return WAVE_ERR_SHAPE;
+  const AppendGeom g = append_geometry(*old_ix, n_new, n_local_min, U, k_u);
+  wave_index nw = *old_ix;
+  nw.centroids = nw.vsum = nullptr;
+  nw.sizes = nw.offsets = nw.perm = nullptr;
+  nw.k_perm = nw.v_perm = nw.k_steady = nw.v_steady = nullptr;
+  nw.N = old_ix->N + n_new;
+  nw.n_local = g.lc_old + n_new - g.F * U;
+  nw.appended_segments = old_ix->appended_segments + g.F;
+  nw.update_segment_len = U;
+  nw.update_clusters = k_u;
+  *out = nw;
+  return WAVE_OK;
+}
+
+wave_status wave_index_append_plan(const wave_index* old_ix, int n_new, int n_local_min,
+                                   int update_segment_len, int update_clusters, wave_index* new_ix,
+                                   size_t bytes[WAVE_INDEX_BUFFERS], size_t* workspace_bytes) {
+  wave_index nw;
+  wave_status st = plan_append(old_ix, n_new, n_local_min, update_segment_len, update_clusters, &nw);
+  if (st != WAVE_OK) return st;
+  if (!new_ix || !bytes) return WAVE_ERR_ARG;
+  st = wave_index_plan(&nw, bytes, nullptr, 0, 0, nullptr);
+  if (st != WAVE_OK) return st;
+  *new_ix = nw;
+  if (workspace_bytes)
+    *workspace_bytes = append_geometry(*old_ix, n_new, n_local_min, update_segment_len, update_clusters).total;
+  return WAVE_OK;
+}
+
+wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const void* V_new,
+                              int n_new, int n_local_min, int update_segment_len,
+                              int update_clusters, int iters, uint64_t seed, wave_index* new_ix,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  wave_index want;
+  wave_status st = plan_append(old_ix, n_new, n_local_min, update_segment_len, update_clusters, &want);
+  if (st != WAVE_OK) return st;
+  if (!new_ix || iters < 1) return WAVE_ERR_ARG;
+  if (n_new > 0 && (!K_new || !V_new || !aligned16(K_new) || !aligned16(V_new))) return WAVE_ERR_ARG;
+  st = check_dims(new_ix);
+  if (st != WAVE_OK) return st;
+  if (new_ix->dtype != want.dtype || new_ix->B != want.B || new_ix->Hkv != want.Hkv ||
+      new_ix->d != want.d || new_ix->N != want.N || new_ix->n_sink != want.n_sink ||
+      new_ix->n_local != want.n_local || new_ix->segment_len != want.segment_len ||
+      new_ix->clusters_per_segment != want.clusters_per_segment ||
+      new_ix->appended_segments != want.appended_segments ||
+      new_ix->update_segment_len != want.update_segment_len ||
+      new_ix->update_clusters != want.update_clusters || !planned_fields_match(*new_ix))
+    return WAVE_ERR_SHAPE;
+  st = check_index_buffers(*old_ix);
+  if (st != WAVE_OK) return st;
+  st = check_index_buffers(*new_ix);
+  if (st != WAVE_OK) return st;
+  const AppendGeom g = append_geometry(*old_ix, n_new, n_local_min, update_segment_len, update_clusters);
+  if (g.total > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total))
+    return WAVE_ERR_WORKSPACE;
+  return launch_append(*old_ix, K_new, V_new, n_new, iters, seed, *new_ix, g, workspace,
+                       static_cast<hipStream_t>(hip_stream));
 }
 
 wave_status wave_attention_decode(const void* q, const wave_index* ix, int Hq, int topk_clusters,

@@ -130,12 +130,13 @@ constexpr int KMAX = 4096;
 template <typename T, int D>
 __global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
                                                    int S, int L, int kk, int N_idx, int Hkv,
-                                                   uint64_t seed) {
+                                                   uint64_t seed, int seg_id_base) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
   __shared__ int target[KMAX], chosen[KMAX];
-  const uint64_t st0 = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s);
+  // (seg_id_base: the segments of an index update continue the numbering of the build)
+  const uint64_t st0 = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s + seg_id_base);
   for (int i = threadIdx.x; i < si.k_s; i += 256) {
     uint64_t st = st0 + (uint64_t)i * 0x9E3779B97F4A7C15ull;  // state before draw i
     const uint64_t draw = splitmix64_next(st);
@@ -860,7 +861,7 @@ static void launch_assign(const T* xhat, const T* chat, int32_t* assign, int32_t
 
 template <typename T, int D>
 static wave_status build_td(const void* K_, const void* V_, const wave_index& ix, int iters,
-                            uint64_t seed, void* ws, hipStream_t st) {
+                            uint64_t seed, void* ws, hipStream_t st, int seg_id_base) {
   const T* K = static_cast<const T*>(K_);
   const T* V = static_cast<const T*>(V_);
   const int units = ix.B * ix.Hkv;
@@ -906,7 +907,7 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
                 N_idx, ns, (int)rows);
   }
   WAVE_LAUNCH("init", (init_kernel<T, D>), g.segs, 256, 0, st, xhat, chat, S, L, kk, N_idx, ix.Hkv,
-              seed);
+              seed, seg_id_base);
 
   int W = SORT_HIST_INTS / kk;
   if (W > 16) W = 16;
@@ -932,13 +933,13 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
 }
 
 wave_status launch_build(const void* K, const void* V, const wave_index& ix, int iters, uint64_t seed,
-                         void* ws, hipStream_t st) {
+                         void* ws, hipStream_t st, int seg_id_base) {
   if (ix.dtype == WAVE_BF16) {
-    if (ix.d == 128) return build_td<bf16_t, 128>(K, V, ix, iters, seed, ws, st);
-    if (ix.d == 64) return build_td<bf16_t, 64>(K, V, ix, iters, seed, ws, st);
+    if (ix.d == 128) return build_td<bf16_t, 128>(K, V, ix, iters, seed, ws, st, seg_id_base);
+    if (ix.d == 64) return build_td<bf16_t, 64>(K, V, ix, iters, seed, ws, st, seg_id_base);
   } else {
-    if (ix.d == 128) return build_td<float, 128>(K, V, ix, iters, seed, ws, st);
-    if (ix.d == 64) return build_td<float, 64>(K, V, ix, iters, seed, ws, st);
+    if (ix.d == 128) return build_td<float, 128>(K, V, ix, iters, seed, ws, st, seg_id_base);
+    if (ix.d == 64) return build_td<float, 64>(K, V, ix, iters, seed, ws, st, seg_id_base);
   }
   return WAVE_ERR_SHAPE;
 }

@@ -30,9 +30,57 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 14 int32 fields then 9 pointers
-    assert ctypes.sizeof(wb.wave_index) == 14 * 4 + 9 * 8
+    # 14 int32 fields, 9 pointers, 4 int32 fields (the index update's)
+    assert ctypes.sizeof(wb.wave_index) == 14 * 4 + 9 * 8 + 4 * 4
     assert wb.wave_index.centroids.offset == 56
+    assert wb.wave_index.appended_segments.offset == 56 + 72
+
+
+@pytest.mark.parametrize("N0,ns,nl,L,k,n_new,U,ku", [(5000, 4, 64, 1024, 64, 1, 256, 16),
+                                                     (5000, 4, 64, 1024, 64, 255, 256, 16),
+                                                     (5000, 4, 64, 1024, 64, 256, 256, 16),
+                                                     (5000, 4, 64, 1024, 64, 1500, 256, 300),
+                                                     (70, 4, 64, 1024, 64, 700, 128, 8),
+                                                     (5000, 0, 0, 1024, 64, 600, 128, 8)])
+def test_append_plan_matches_oracle_layout(N0, ns, nl, L, k, n_new, U, ku):
+    """Host only: the planned dimensions of a grown index against the oracle's bookkeeping,
+    once in one step and once in two."""
+    c0, _, _, _ = wb.wave_index_plan(torch.bfloat16, 2, 3, 128, N0, ns, nl, L, k)
+    L_ = wb.lib()
+
+    def plan(c_old, n):
+        c = wb.wave_index()
+        sizes = (ctypes.c_size_t * 9)()
+        wsb = ctypes.c_size_t(0)
+        st = L_.wave_index_append_plan(ctypes.byref(c_old), n, nl, U, ku, ctypes.byref(c), sizes,
+                                       ctypes.byref(wsb))
+        assert st == 0, st
+        return c, list(sizes), wsb.value
+
+    p0 = wo.make_plan(N0, ns, nl, L, k)
+    lc0 = N0 - p0.local_start
+    F = max(0, (lc0 + n_new - nl) // U)
+    c1, sizes, wsb = plan(c0, n_new)
+    assert c1.N == N0 + n_new and c1.appended_segments == F
+    assert c1.n_local == lc0 + n_new - F * U and c1.p == p0.n_sink + c1.n_local
+    assert (c1.S, c1.m, c1.N_idx) == (p0.S + F, p0.m + F * min(ku, U), p0.N_idx + F * U)
+    assert sizes[2] == 6 * c1.m * 4 and sizes[5] == 6 * c1.N_idx * 256 and sizes[7] == 6 * c1.p * 256
+    assert (wsb > 0) == (F > 0)
+    half = n_new // 2
+    ca, _, _ = plan(c0, half)
+    cb, _, _ = plan(ca, n_new - half)
+    assert (cb.N, cb.n_local, cb.S, cb.m, cb.N_idx, cb.appended_segments) == \
+           (c1.N, c1.n_local, c1.S, c1.m, c1.N_idx, c1.appended_segments)
+    # decode accepts the grown index's dimensions (workspace planning goes through the same checks)
+    sizes2 = (ctypes.c_size_t * 9)()
+    dws = ctypes.c_size_t(0)
+    assert L_.wave_index_plan(ctypes.byref(c1), sizes2, None, 12, 7, ctypes.byref(dws)) == 0 and dws.value > 0
+    # another update segment length on an index that already has update segments is refused
+    if F > 0:
+        c = wb.wave_index()
+        st = L_.wave_index_append_plan(ctypes.byref(c1), 5, nl, U + 1, ku, ctypes.byref(c),
+                                       (ctypes.c_size_t * 9)(), None)
+        assert st == 2
 
 
 @pytest.mark.parametrize("N,ns,nl,L,k", [(4096, 4, 64, 2048, 128), (32768, 4, 1024, 8192, 512),

@@ -425,3 +425,44 @@ def test_recall_measurement_matches_oracle():
             s_ref, _ = wo.select_clusters(qn[b, hq], ref.centroids, ref.sizes, r)
             want = wo.recall_at(qn[b, hq], ref, s_ref, top=100)
             assert abs(rec[b, hq] - want) <= 0.011, (b, hq, rec[b, hq], want)   # one token of 100: score ties
+
+
+@pytest.mark.parametrize("case,n_news,U,ku", [("bf16_g4", (300, 37, 1000), 256, 16),
+                                              ("tiny_f32", (5, 200), 64, 8),
+                                              ("bf16_d64", (130,), 128, 200)])
+def test_index_append_matches_oracle_then_decode(case, n_news, U, ku):
+    """Incremental index update through the C ABI, several times in a row (without and with
+    flushed update segments, more clusters asked for than an update segment has tokens):
+    every array of the grown index against the oracle's, then decode on it."""
+    wl = CASES[case]
+    total_new = sum(n_news)
+    big = synth.scaled(wl, N=wl.N + total_new)
+    Kall, Vall, _ = _inputs(big, 1)
+    K0, V0 = Kall[:, :, :wl.N].contiguous(), Vall[:, :, :wl.N].contiguous()
+    ref = pu.oracle_build(wl, K0, V0)
+    ix = wb.wave_index_build(K0.cuda(), V0.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    pos = wl.N
+    for n_new in n_news:
+        Kn, Vn = Kall[:, :, pos:pos + n_new].contiguous(), Vall[:, :, pos:pos + n_new].contiguous()
+        ix = wb.wave_index_append(ix, Kn.cuda(), Vn.cuda(), wl.n_local, U, ku, wl.iters, 0)
+        torch.cuda.synchronize()
+        for (b, h), u in ref.items():
+            ref[(b, h)] = wo.append_unit(u, Kn[b, h].double().numpy(), Vn[b, h].double().numpy(),
+                                         wl.n_local, U, ku, wl.iters, 0, b, h)
+        pos += n_new
+        u0 = ref[(0, 0)]
+        assert (ix.N, ix.S, ix.m, ix.N_idx, ix.p) == (u0.plan.N, u0.plan.S, u0.plan.m, u0.plan.N_idx,
+                                                      u0.k_steady.shape[0])
+        for (b, h), u in ref.items():
+            for name in ("sizes", "offsets", "perm"):
+                assert np.array_equal(getattr(ix, name)[b, h].cpu().numpy(), getattr(u, name)), (n_new, b, h, name)
+            for name in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
+                got = getattr(ix, name)[b, h].float().cpu().numpy().astype(np.float64)
+                assert np.array_equal(got, getattr(u, name)), (n_new, b, h, name)
+    assert ix.appended_segments > 0
+    q = synth.make_queries(big, 2)
+    wl_now = synth.scaled(big, n_local=ix.n_local)
+    r = pu.retrieve_count(wl)
+    _decode_and_check(wl_now, ix, ref, q, r, f"append {case}")
+    _decode_and_check(wl_now, ix, ref, q, ix.m, f"append {case} all")
