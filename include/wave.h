@@ -118,7 +118,10 @@ wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
  *
  * wave_index_append: old_ix read only; K_new, V_new DEVICE [B,Hkv,n_new,d]
  * dtype (may be NULL when n_new = 0); new_ix as planned, with its nine DEVICE
- * buffers (written; must not overlap old_ix's); workspace DEVICE, 256-byte
+ * buffers (written; must not overlap old_ix's, except that an update which
+ * flushes no segment -- the plan's appended_segments equals the old one --
+ * may name old_ix's own seven arrays of the clustered part, which are then left
+ * as they are; the steady buffers are always new); workspace DEVICE, 256-byte
  * aligned.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
  * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
 wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,

@@ -205,7 +205,9 @@ def wave_index_append(ix: Index, K_new: Optional[torch.Tensor], V_new: Optional[
                       seed: int) -> Index:
     """K_new, V_new: [B, Hkv, n_new, d] device tensors of the index's dtype (None for no new
     tokens).  Plans and allocates the grown index, enqueues the update on the current stream
-    and returns the new index (valid after a stream sync); `ix` is left as it is."""
+    and returns the new index (valid after a stream sync); `ix` is left as it is.  When no
+    update segment is flushed the new index shares the arrays of the clustered part with `ix`
+    and only its steady rows are new."""
     n_new = 0 if K_new is None else K_new.shape[2]
     if n_new:
         assert K_new.is_cuda and V_new.is_cuda and K_new.shape == V_new.shape and K_new.dtype == ix.dtype
@@ -220,9 +222,13 @@ def wave_index_append(ix: Index, K_new: Optional[torch.Tensor], V_new: Optional[
         raise WaveError(st, "wave_index_append_plan")
     device = ix.t["k_steady"].device if ix.t["k_steady"].numel() else ix.t["k_perm"].device
     tensors = {}
+    keep = c.appended_segments == ix.c.appended_segments   # nothing flushed: the clustered part is shared
     for name, nbytes in zip(BUFFER_NAMES, sizes):
         dt = torch.int32 if name in ("sizes", "offsets", "perm") else ix.dtype
-        t = torch.empty(_shapes(c)[name], dtype=dt, device=device)
+        if keep and name not in ("k_steady", "v_steady"):
+            t = ix.t[name]
+        else:
+            t = torch.empty(_shapes(c)[name], dtype=dt, device=device)
         assert t.numel() * t.element_size() == nbytes, (name, t.shape, nbytes)
         tensors[name] = t
         setattr(c, name, _ptr(t))

@@ -322,6 +322,16 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
   st = check_index_buffers(*new_ix);
   if (st != WAVE_OK) return st;
   const AppendGeom g = append_geometry(*old_ix, n_new, n_local_min, update_segment_len, update_clusters);
+  {  // the seven arrays of the clustered part may be the old ones only if nothing is appended to them
+    const void* a[7] = {old_ix->centroids, old_ix->vsum, old_ix->sizes, old_ix->offsets, old_ix->perm,
+                        old_ix->k_perm, old_ix->v_perm};
+    const void* b[7] = {new_ix->centroids, new_ix->vsum, new_ix->sizes, new_ix->offsets, new_ix->perm,
+                        new_ix->k_perm, new_ix->v_perm};
+    for (int i = 0; i < 7; ++i)
+      if (g.F > 0 && a[i] && a[i] == b[i]) return WAVE_ERR_ARG;
+    if (old_ix->k_steady && (old_ix->k_steady == new_ix->k_steady || old_ix->v_steady == new_ix->v_steady))
+      return WAVE_ERR_ARG;
+  }
   if (g.total > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total))
     return WAVE_ERR_WORKSPACE;
   return launch_append(*old_ix, K_new, V_new, n_new, iters, seed, *new_ix, g, workspace,

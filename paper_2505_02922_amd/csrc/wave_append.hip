@@ -92,7 +92,7 @@ static int grid_for(size_t items) {
 template <typename C>
 static void copy_units(void* dst, const void* src, size_t n, size_t dst_stride, size_t src_stride,
                        size_t dst_off, int units, hipStream_t st) {
-  if (n == 0) return;
+  if (n == 0 || dst == src) return;  // (an update that flushes nothing may keep the old arrays)
   WAVE_LAUNCH("append_copy", (copy_units_kernel<C>), grid_for(n * units), 256, 0, st,
               static_cast<C*>(dst), static_cast<const C*>(src), n, dst_stride, src_stride, dst_off, units);
 }
