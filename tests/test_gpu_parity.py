@@ -427,14 +427,21 @@ def test_recall_measurement_matches_oracle():
             assert abs(rec[b, hq] - want) <= 0.011, (b, hq, rec[b, hq], want)   # one token of 100: score ties
 
 
+# a context shorter than its steady zone: nothing is indexed before the first update
+_SHORT = _small("tiny_f32", name="f32_short", N=50, n_sink=4, n_local=64, segment_len=2048,
+                clusters_per_segment=128, iters=3, retrieve_abs=2)
+
+
 @pytest.mark.parametrize("case,n_news,U,ku", [("bf16_g4", (300, 37, 1000), 256, 16),
                                               ("tiny_f32", (5, 200), 64, 8),
-                                              ("bf16_d64", (130,), 128, 200)])
+                                              ("bf16_d64", (130,), 128, 200),
+                                              (_SHORT, (10, 100), 32, 4)])
 def test_index_append_matches_oracle_then_decode(case, n_news, U, ku):
     """Incremental index update through the C ABI, several times in a row (without and with
-    flushed update segments, more clusters asked for than an update segment has tokens):
-    every array of the grown index against the oracle's, then decode on it."""
-    wl = CASES[case]
+    flushed update segments, more clusters asked for than an update segment has tokens, an
+    index with no clusters yet): every array of the grown index against the oracle's, then
+    decode on it."""
+    wl = CASES[case] if isinstance(case, str) else case
     total_new = sum(n_news)
     big = synth.scaled(wl, N=wl.N + total_new)
     Kall, Vall, _ = _inputs(big, 1)
@@ -464,5 +471,5 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku):
     q = synth.make_queries(big, 2)
     wl_now = synth.scaled(big, n_local=ix.n_local)
     r = pu.retrieve_count(wl)
-    _decode_and_check(wl_now, ix, ref, q, r, f"append {case}")
-    _decode_and_check(wl_now, ix, ref, q, ix.m, f"append {case} all")
+    _decode_and_check(wl_now, ix, ref, q, r, f"append {wl.name}")
+    _decode_and_check(wl_now, ix, ref, q, ix.m, f"append {wl.name} all")
