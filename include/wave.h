@@ -77,14 +77,19 @@ typedef struct {
                                 /*        v_perm are [offsets[c], offsets[c+1])        */
   int32_t *perm;                /* DEVICE [B,Hkv,N_idx] original position of each row  */
   void *k_perm, *v_perm;        /* DEVICE [B,Hkv,N_idx,d] dtype, rows ordered by       */
-                                /*        (segment, cluster, original position)        */
+                                /*        (segment, cluster, original position); with  */
+                                /*        row_capacity > 0 the three have row_capacity */
+                                /*        rows per unit, the first N_idx in use        */
   void *k_steady, *v_steady;    /* DEVICE [B,Hkv,p,d] dtype: sink rows then local rows */
   int32_t appended_segments;    /* update segments appended by wave_index_append (0 for */
                                 /* a freshly built index); they follow the S - this     */
                                 /* many segments of the build                           */
   int32_t update_segment_len;   /* their length U and ...                               */
   int32_t update_clusters;      /* ... clusters per update segment (min(k_u, U) each)   */
-  int32_t reserved2_;
+  int32_t row_capacity;         /* rows allocated per unit in perm, k_perm and v_perm:   */
+                                /* 0 means N_idx (dense); a larger value, set by the    */
+                                /* caller before wave_index_plan, leaves room for       */
+                                /* wave_index_append to add rows in place               */
 } wave_index;
 
 enum { WAVE_INDEX_BUFFERS = 9 };
@@ -118,11 +123,14 @@ wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
  *
  * wave_index_append: old_ix read only; K_new, V_new DEVICE [B,Hkv,n_new,d]
  * dtype (may be NULL when n_new = 0); new_ix as planned, with its nine DEVICE
- * buffers (written; must not overlap old_ix's, except that an update which
- * flushes no segment -- the plan's appended_segments equals the old one --
- * may name old_ix's own seven arrays of the clustered part, which are then left
- * as they are; the steady buffers are always new); workspace DEVICE, 256-byte
- * aligned.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
+ * buffers (written; must not overlap old_ix's, with two exceptions: an update
+ * which flushes no segment -- the plan's appended_segments equals the old one
+ * -- may name old_ix's own seven arrays of the clustered part, which are then
+ * left as they are; and perm, k_perm, v_perm may be old_ix's when both indexes
+ * have the same row_capacity >= the new N_idx: the new rows are then written
+ * behind the old ones in place and old_ix stays valid; the steady buffers are
+ * always new); workspace DEVICE, 256-byte aligned.  The plan keeps old_ix's
+ * row_capacity while the grown index fits in it and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
  * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
 wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,
                                    int update_segment_len, int update_clusters, wave_index *new_ix,

@@ -103,7 +103,7 @@ static wave_status check_dims(const wave_index* ix) {
   if (ix->segment_len < 1 || ix->clusters_per_segment < 1) return WAVE_ERR_ARG;
   if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
   if (ix->clusters_per_segment > 4096) return WAVE_ERR_SHAPE;
-  if (ix->appended_segments < 0) return WAVE_ERR_ARG;
+  if (ix->appended_segments < 0 || ix->row_capacity < 0) return WAVE_ERR_ARG;
   if (ix->appended_segments > 0) {
     if (ix->update_segment_len < 1 || ix->update_clusters < 1) return WAVE_ERR_ARG;
     if (ix->update_clusters > 4096) return WAVE_ERR_SHAPE;
@@ -138,6 +138,7 @@ static Derived derive(const wave_index& ix) {
 
 static bool planned_fields_match(const wave_index& ix) {
   const Derived d = derive(ix);
+  if (ix.row_capacity > 0 && ix.row_capacity < d.N_idx) return false;
   return ix.S == d.S && ix.m == d.m && ix.N_idx == d.N_idx && ix.p == d.p;
 }
 
@@ -157,6 +158,7 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   if (!bytes) return WAVE_ERR_ARG;
   const Derived d = derive(*ix);
   if ((long long)ix->B * ix->Hkv * ((long long)d.m + 1) >= (1ll << 31)) return WAVE_ERR_SHAPE;
+  if (d.m < 0 || (ix->row_capacity > 0 && ix->row_capacity < d.N_idx)) return WAVE_ERR_SHAPE;
   ix->S = d.S;
   ix->m = d.m;
   ix->N_idx = d.N_idx;
@@ -167,8 +169,9 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   bytes[1] = units * d.m * ix->d * es;
   bytes[2] = units * d.m * sizeof(int32_t);
   bytes[3] = units * ((size_t)d.m + 1) * sizeof(int32_t);
-  bytes[4] = units * d.N_idx * sizeof(int32_t);
-  bytes[5] = units * d.N_idx * ix->d * es;
+  const size_t rows = ix->row_capacity > 0 ? (size_t)ix->row_capacity : (size_t)d.N_idx;
+  bytes[4] = units * rows * sizeof(int32_t);
+  bytes[5] = units * rows * ix->d * es;
   bytes[6] = bytes[5];
   bytes[7] = units * d.p * ix->d * es;
   bytes[8] = bytes[7];
@@ -279,6 +282,7 @@ static wave_status plan_append(const wave_index* old_ix, int n_new, int n_local_
   nw.appended_segments = old_ix->appended_segments + g.F;
   nw.update_segment_len = U;
   nw.update_clusters = k_u;
+  if ((long long)old_ix->N_idx + (long long)g.F * U > old_ix->row_capacity) nw.row_capacity = 0;
   *out = nw;
   return WAVE_OK;
 }
@@ -316,7 +320,7 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
       new_ix->appended_segments != want.appended_segments ||
       new_ix->update_segment_len != want.update_segment_len ||
       new_ix->update_clusters != want.update_clusters || !planned_fields_match(*new_ix))
-    return WAVE_ERR_SHAPE;
+    return WAVE_ERR_SHAPE;  // (row_capacity of new_ix is the caller's choice, checked against its N_idx)
   st = check_index_buffers(*old_ix);
   if (st != WAVE_OK) return st;
   st = check_index_buffers(*new_ix);
@@ -327,8 +331,9 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
                         old_ix->k_perm, old_ix->v_perm};
     const void* b[7] = {new_ix->centroids, new_ix->vsum, new_ix->sizes, new_ix->offsets, new_ix->perm,
                         new_ix->k_perm, new_ix->v_perm};
+    const bool in_place = new_ix->row_capacity > 0 && new_ix->row_capacity == old_ix->row_capacity;
     for (int i = 0; i < 7; ++i)
-      if (g.F > 0 && a[i] && a[i] == b[i]) return WAVE_ERR_ARG;
+      if (g.F > 0 && a[i] && a[i] == b[i] && !(in_place && i >= 4)) return WAVE_ERR_ARG;
     if (old_ix->k_steady && (old_ix->k_steady == new_ix->k_steady || old_ix->v_steady == new_ix->v_steady))
       return WAVE_ERR_ARG;
   }

@@ -11,7 +11,10 @@
 // tokens are built as an index of their own by the build's kernels, with their
 // segments numbered after the old ones for the seeding rule; (4) that index is
 // appended: centroids, value sums, sizes and rows as they are, offsets shifted
-// by the old row count, positions by the window's first position.
+// by the old row count, positions by the window's first position.  When the
+// row arrays (perm, k_perm, v_perm) of both indexes are the same buffers with
+// room left (row_capacity), step (1) skips them and step (4) writes the new
+// rows behind the old ones in place.
 #include "wave_common.h"
 
 namespace wave {
@@ -116,9 +119,10 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
   else if (nw.offsets)  // no clusters before and no array for them: the first offset of every unit is 0
     WAVE_LAUNCH("append_copy", set_first_kernel, grid_for(units), 256, 0, st, nw.offsets,
                 (size_t)nw.m + 1, units);
-  copy_units<int32_t>(nw.perm, o.perm, (size_t)o.N_idx, (size_t)nw.N_idx, (size_t)o.N_idx, 0, units, st);
-  copy_units<uint4>(nw.k_perm, o.k_perm, (size_t)o.N_idx * rowc, (size_t)nw.N_idx * rowc, (size_t)o.N_idx * rowc, 0, units, st);
-  copy_units<uint4>(nw.v_perm, o.v_perm, (size_t)o.N_idx * rowc, (size_t)nw.N_idx * rowc, (size_t)o.N_idx * rowc, 0, units, st);
+  const size_t rs_new = (size_t)row_stride(nw), rs_old = (size_t)row_stride(o);  // rows per unit
+  copy_units<int32_t>(nw.perm, o.perm, (size_t)o.N_idx, rs_new, rs_old, 0, units, st);
+  copy_units<uint4>(nw.k_perm, o.k_perm, (size_t)o.N_idx * rowc, rs_new * rowc, rs_old * rowc, 0, units, st);
+  copy_units<uint4>(nw.v_perm, o.v_perm, (size_t)o.N_idx * rowc, rs_new * rowc, rs_old * rowc, 0, units, st);
 
   // (2) sink rows and the window
   {
@@ -162,10 +166,10 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
               o.N_idx);
   // positions: window row w is token (old N - old local count) + w
   WAVE_LAUNCH("append_copy", copy_units_add_kernel, grid_for((size_t)mi.N_idx * units), 256, 0, st, nw.perm,
-              mi.perm, (size_t)mi.N_idx, (size_t)nw.N_idx, (size_t)mi.N_idx, (size_t)o.N_idx, (size_t)0, units,
+              mi.perm, (size_t)mi.N_idx, rs_new, (size_t)mi.N_idx, (size_t)o.N_idx, (size_t)0, units,
               o.N - g.lc_old);
-  copy_units<uint4>(nw.k_perm, mi.k_perm, (size_t)mi.N_idx * rowc, (size_t)nw.N_idx * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
-  copy_units<uint4>(nw.v_perm, mi.v_perm, (size_t)mi.N_idx * rowc, (size_t)nw.N_idx * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
+  copy_units<uint4>(nw.k_perm, mi.k_perm, (size_t)mi.N_idx * rowc, rs_new * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
+  copy_units<uint4>(nw.v_perm, mi.v_perm, (size_t)mi.N_idx * rowc, rs_new * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 

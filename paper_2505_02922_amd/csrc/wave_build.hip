@@ -713,7 +713,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     const int32_t* __restrict__ count, const int32_t* __restrict__ start, T* __restrict__ centroids,
     T* __restrict__ vsum, int32_t* __restrict__ sizes, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, T* __restrict__ k_perm, T* __restrict__ v_perm, int S, int L, int kk,
-    int N, int N_idx, int n_sink, int m, int nclusters) {
+    int N, int N_idx, int n_sink, int m, int nclusters, int row_stride) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   const int gc = blockIdx.x * GROUPS + grp;
@@ -724,6 +724,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
   const int n = count[gc], st = start[gc];
   const int cid = si.s * kk + c;  // only the last segment can have fewer than kk clusters
   const size_t urow = (size_t)si.unit * N_idx;
+  const size_t orow = (size_t)si.unit * row_stride;  // rows per unit in perm / k_perm / v_perm
   const int row0 = si.seg_start + st;
   if (sub == 0) {
     sizes[(size_t)si.unit * m + cid] = n;
@@ -742,9 +743,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     const uint4 k0 = load16(Ku + (size_t)pa * D), v0 = load16(Vu + (size_t)pa * D);
     const uint4 k1 = load16(Ku + (size_t)pb * D), v1 = load16(Vu + (size_t)pb * D);
     float f[EPC];
-    store16(k_perm + (urow + row0 + i) * D + sub * EPC, k0);
-    store16(v_perm + (urow + row0 + i) * D + sub * EPC, v0);
-    if (sub == 0) perm[urow + row0 + i] = n_sink + si.seg_start + pa;
+    store16(k_perm + (orow + row0 + i) * D + sub * EPC, k0);
+    store16(v_perm + (orow + row0 + i) * D + sub * EPC, v0);
+    if (sub == 0) perm[orow + row0 + i] = n_sink + si.seg_start + pa;
     unpack<T>(k0, f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
@@ -752,9 +753,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(
 #pragma unroll
     for (int e = 0; e < EPC; ++e) va[e] += (double)f[e];
     if (i + 1 < n) {
-      store16(k_perm + (urow + row0 + i + 1) * D + sub * EPC, k1);
-      store16(v_perm + (urow + row0 + i + 1) * D + sub * EPC, v1);
-      if (sub == 0) perm[urow + row0 + i + 1] = n_sink + si.seg_start + pb;
+      store16(k_perm + (orow + row0 + i + 1) * D + sub * EPC, k1);
+      store16(v_perm + (orow + row0 + i + 1) * D + sub * EPC, v1);
+      if (sub == 0) perm[orow + row0 + i + 1] = n_sink + si.seg_start + pb;
       unpack<T>(k1, f);
 #pragma unroll
       for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
@@ -928,7 +929,7 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
               static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,
               static_cast<T*>(ix.k_perm), static_cast<T*>(ix.v_perm), S, L, kk, ix.N, N_idx, ns, ix.m,
-              ncl);
+              ncl, row_stride(ix));
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 

@@ -1643,8 +1643,8 @@ __global__ __launch_bounds__(256) void gather_kernel(
     const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
     const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ nsel_arr,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int N_idx, int m, int rcap, int chunks, int slots, float scale_log2, int own_neg,
-    float* __restrict__ part) {
+    int Hq, int Hkv, int N_idx /* rows per unit in k_perm / v_perm */, int m, int rcap, int chunks,
+    int slots, float scale_log2, int own_neg, float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
   const int bh = wg / chunks, chunk = wg - bh * chunks;
@@ -2501,7 +2501,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
     if (g.fused) {
       WAVE_LAUNCH("select_gather_steady", (select_gather_kernel<T, D, 512, 32, true>), heads, 512,
                   key_lds, st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
-                  static_cast<const T*>(ix.v_perm), ix.N_idx, static_cast<const T*>(ix.k_steady),
+                  static_cast<const T*>(ix.v_perm), row_stride(ix), static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, 2, out, lse);
     } else {
       if (g.sliced) {
@@ -2543,7 +2543,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       if (g.gather_chunks > 0)
         WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                     static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), sel, nsel,
-                    ix.offsets, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, ix.N_idx, m, g.rcap,
+                    ix.offsets, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
                     g.gather_chunks, g.slots, scale_log2, g.neg_in_gather, part);
     }
 #undef WAVE_SELECT_ARGS
@@ -2692,7 +2692,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (g.gather_chunks > 0)
     WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1,
-                ix.offsets, z, VS, Hq, ix.Hkv, ix.N_idx, m, g.rcap1, g.gather_chunks, slots, scale_log2, 0,
+                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, g.rcap1, g.gather_chunks, slots, scale_log2, 0,
                 part + (size_t)g.steady_chunks * (D + 2));
   if (g.est_chunks > 0)
     WAVE_LAUNCH("estimate", (est_gather_kernel<T, D>), heads * g.est_chunks, 256, 0, st, ids2, nsel2, ids1,

@@ -105,7 +105,7 @@ def recall_at_gpu(q, ix, sel, Hq, top=100):
     out = torch.zeros(B, Hq, device=q.device)
     for b in range(B):
         for h in range(Hkv):
-            Kp = ix.k_perm[b, h].float()                                  # [N_idx, d]
+            Kp = ix.k_perm[b, h, :ix.N_idx].float()                       # [N_idx, d]
             off = ix.offsets[b, h].to(torch.int64)                        # [m + 1]
             n = Kp.shape[0]
             k = min(top, n)

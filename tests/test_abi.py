@@ -99,6 +99,25 @@ def test_plan_matches_oracle_layout(N, ns, nl, L, k):
     assert dws > 0 and (bws > 0) == (p.m > 0)
 
 
+def test_row_capacity_in_the_plan():
+    """Room for more permuted rows than the index holds: sizes of perm / k_perm / v_perm follow the
+    capacity, too small a capacity is refused, and the plan of an update keeps it while it fits."""
+    c, sizes, _, _ = wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, row_capacity=6000)
+    assert c.N_idx == 4932 and c.row_capacity == 6000
+    assert sizes[4] == 6 * 6000 * 4 and sizes[5] == sizes[6] == 6 * 6000 * 256
+    assert sizes[0] == 6 * c.m * 256                      # the meta index stays dense
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, row_capacity=4000)
+    assert e.value.status == 2
+    L_ = wb.lib()
+    for n_new, keeps in ((1024, True), (1100, False)):    # 4 or 5 update segments of 256 rows
+        cn = wb.wave_index()
+        st = L_.wave_index_append_plan(ctypes.byref(c), n_new, 64, 256, 16, ctypes.byref(cn),
+                                       (ctypes.c_size_t * 9)(), None)
+        assert st == 0 and cn.N_idx == 4932 + 256 * (n_new // 256)
+        assert cn.row_capacity == (6000 if keeps else 0), (n_new, cn.row_capacity)
+
+
 def test_status_strings():
     for code in range(7):
         assert len(wb.lib().wave_status_string(code)) > 0
