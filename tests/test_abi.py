@@ -110,7 +110,7 @@ def test_row_capacity_in_the_plan():
         wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, row_capacity=4000)
     assert e.value.status == 2
     L_ = wb.lib()
-    for n_new, keeps in ((1024, True), (1100, False)):    # 4 or 5 update segments of 256 rows
+    for n_new, keeps in ((1024, True), (1300, False)):    # 4 or 5 update segments of 256 rows
         cn = wb.wave_index()
         st = L_.wave_index_append_plan(ctypes.byref(c), n_new, 64, 256, 16, ctypes.byref(cn),
                                        (ctypes.c_size_t * 9)(), None)
