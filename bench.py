@@ -367,7 +367,8 @@ def main() -> int:
     # the same with room for the new rows in the permuted key/value arrays (row_capacity): the
     # rows are added in place and only the meta index and the steady rows are rewritten
     ixc = wb.alloc_index(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
-                         wl.segment_len, wl.clusters_per_segment, dev, row_capacity=ix.N_idx + U_UPD)
+                         wl.segment_len, wl.clusters_per_segment, dev, row_capacity=ix.N_idx + U_UPD,
+                         steady_capacity=ix.p + U_UPD)
     bws3 = wb.workspace(ixc.build_ws_bytes, dev)
     wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
                         wl.iters, 0, ws=bws3, index=ixc)
@@ -384,7 +385,18 @@ def main() -> int:
         upd_cap_ms.append(e0.elapsed_time(e1))
         assert ix2.k_perm.data_ptr() == ixc.k_perm.data_ptr() and ix2.m == ix.m + U_UPD // 16
         del ix2
-    del ixc
+    # one new token per sequence (a decode step's own key and value): with room in the steady
+    # buffers its rows go behind the window and nothing else is touched
+    ixt = ixc
+    wb.wave_profile_enable(True)
+    for i in range(8):
+        ixt = wb.wave_index_append(ixt, Kn[:, :, i:i + 1], Vn[:, :, i:i + 1], wl.n_local, U_UPD,
+                                   U_UPD // 16, wl.iters, 0)
+        assert ixt.k_steady.data_ptr() == ixc.k_steady.data_ptr() and ixt.p == ix.p + i + 1
+    tok_prof = wb.wave_profile_read()
+    wb.wave_profile_enable(False)
+    tok_ms = [sum(v[0] for v in tok_prof.values()) / 8]
+    del ixt, ixc
     torch.cuda.empty_cache()
     update_info = {
         "new_tokens_per_sequence": U_UPD, "update_segment_len": U_UPD, "update_clusters": U_UPD // 16,
@@ -397,6 +409,12 @@ def main() -> int:
             "share_of_the_decode_steps_it_follows": round(_median(upd_cap_ms) / (U_UPD * ms_per_step), 5),
             "note": "row_capacity leaves room in perm / k_perm / v_perm: new rows go behind the old "
                     "ones, only the meta index and the steady rows are rewritten"},
+        "one_token_in_place": {
+            "ms": round(_median(tok_ms), 4),
+            "share_of_a_decode_step": round(_median(tok_ms) / ms_per_step, 4),
+            "note": "steady_capacity leaves room behind the local window: the token's key and value "
+                    "rows are written there, every other array is shared with the index before "
+                    "(kernel time by the library's event profiler; one small launch)"},
     }
     del Kn, Vn
 

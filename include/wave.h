@@ -69,7 +69,8 @@ typedef struct {
   int32_t S, m, N_idx;          /* derived: segments, clusters and indexed tokens per  */
                                 /* unit; N_idx = N - (steady tokens)                   */
   int32_t p;                    /* derived: steady tokens = min(N, n_sink) + local part */
-  int32_t reserved_;
+  int32_t steady_capacity;      /* rows allocated per unit in k_steady and v_steady: 0  */
+                                /* means p (dense); see row_capacity                    */
   void *centroids;              /* DEVICE [B,Hkv,m,d] dtype: mean of raw member keys   */
   void *vsum;                   /* DEVICE [B,Hkv,m,d] dtype: sum of member values      */
   int32_t *sizes;               /* DEVICE [B,Hkv,m]     0 = empty cluster              */
@@ -81,6 +82,7 @@ typedef struct {
                                 /*        row_capacity > 0 the three have row_capacity */
                                 /*        rows per unit, the first N_idx in use        */
   void *k_steady, *v_steady;    /* DEVICE [B,Hkv,p,d] dtype: sink rows then local rows */
+                                /*        (steady_capacity rows per unit if that is set) */
   int32_t appended_segments;    /* update segments appended by wave_index_append (0 for */
                                 /* a freshly built index); they follow the S - this     */
                                 /* many segments of the build                           */
@@ -128,9 +130,12 @@ wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
  * -- may name old_ix's own seven arrays of the clustered part, which are then
  * left as they are; and perm, k_perm, v_perm may be old_ix's when both indexes
  * have the same row_capacity >= the new N_idx: the new rows are then written
- * behind the old ones in place and old_ix stays valid; the steady buffers are
- * always new); workspace DEVICE, 256-byte aligned.  The plan keeps old_ix's
- * row_capacity while the grown index fits in it and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
+ * behind the old ones in place and old_ix stays valid; likewise k_steady and
+ * v_steady may be old_ix's when no segment is flushed and both indexes have
+ * the same steady_capacity >= the new p: only the new tokens' rows are then
+ * written, behind the old window); workspace DEVICE, 256-byte aligned.  The
+ * plan keeps old_ix's row_capacity and steady_capacity while the grown index
+ * fits in them and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
  * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
 wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,
                                    int update_segment_len, int update_clusters, wave_index *new_ix,

@@ -35,7 +35,7 @@ class wave_index(ctypes.Structure):
                 ("n_local", ctypes.c_int32), ("segment_len", ctypes.c_int32),
                 ("clusters_per_segment", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("m", ctypes.c_int32), ("N_idx", ctypes.c_int32), ("p", ctypes.c_int32),
-                ("reserved_", ctypes.c_int32),
+                ("steady_capacity", ctypes.c_int32),
                 ("centroids", ctypes.c_void_p), ("vsum", ctypes.c_void_p),
                 ("sizes", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
                 ("perm", ctypes.c_void_p), ("k_perm", ctypes.c_void_p),
@@ -130,7 +130,7 @@ class Index:
     def __getattr__(self, name):
         if name in ("B", "Hkv", "d", "N", "n_sink", "n_local", "segment_len",
                     "clusters_per_segment", "S", "m", "N_idx", "p", "appended_segments",
-                    "update_segment_len", "update_clusters", "row_capacity"):
+                    "update_segment_len", "update_clusters", "row_capacity", "steady_capacity"):
             return getattr(self.c, name)
         if name in BUFFER_NAMES:
             return self.t[name]
@@ -140,21 +140,22 @@ class Index:
 def _shapes(c: wave_index) -> Dict[str, Tuple[int, ...]]:
     u = (c.B, c.Hkv)
     rows = c.row_capacity if c.row_capacity > 0 else c.N_idx   # the first N_idx rows are in use
+    prow = c.steady_capacity if c.steady_capacity > 0 else c.p  # the first p rows are in use
     return {"centroids": u + (c.m, c.d), "vsum": u + (c.m, c.d), "sizes": u + (c.m,),
             "offsets": u + (c.m + 1,), "perm": u + (rows,), "k_perm": u + (rows, c.d),
-            "v_perm": u + (rows, c.d), "k_steady": u + (c.p, c.d), "v_steady": u + (c.p, c.d)}
+            "v_perm": u + (rows, c.d), "k_steady": u + (prow, c.d), "v_steady": u + (prow, c.d)}
 
 
 def wave_index_plan(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
                     segment_len: int, clusters_per_segment: int, Hq: Optional[int] = None,
-                    topk_clusters: int = 0, row_capacity: int = 0
+                    topk_clusters: int = 0, row_capacity: int = 0, steady_capacity: int = 0
                     ) -> Tuple[wave_index, List[int], int, Optional[int]]:
     """Returns (struct with derived fields, byte sizes of the nine buffers,
     build workspace bytes, decode workspace bytes or None)."""
     c = wave_index()
     c.dtype, c.B, c.Hkv, c.d, c.N = _dtype_code(dtype), B, Hkv, d, N
     c.n_sink, c.n_local, c.segment_len, c.clusters_per_segment = n_sink, n_local, segment_len, clusters_per_segment
-    c.row_capacity = row_capacity
+    c.row_capacity, c.steady_capacity = row_capacity, steady_capacity
     sizes = (ctypes.c_size_t * WAVE_INDEX_BUFFERS)()
     bws, dws = ctypes.c_size_t(0), ctypes.c_size_t(0)
     st = lib().wave_index_plan(ctypes.byref(c), sizes, ctypes.byref(bws), Hq or 0, topk_clusters,
@@ -166,11 +167,12 @@ def wave_index_plan(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink
 
 def alloc_index(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
                 segment_len: int, clusters_per_segment: int, device="cuda",
-                row_capacity: int = 0) -> Index:
+                row_capacity: int = 0, steady_capacity: int = 0) -> Index:
     """Plans and allocates an empty index on the device (row_capacity > 0: room for that many
     permuted rows per unit, so that index updates can add rows in place)."""
     c, sizes, bws, _ = wave_index_plan(dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
-                                       clusters_per_segment, row_capacity=row_capacity)
+                                       clusters_per_segment, row_capacity=row_capacity,
+                                       steady_capacity=steady_capacity)
     tensors = {}
     for name, nbytes in zip(BUFFER_NAMES, sizes):
         dt = torch.int32 if name in ("sizes", "offsets", "perm") else dtype
@@ -188,14 +190,15 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
 def wave_index_build(K: torch.Tensor, V: torch.Tensor, n_sink: int, n_local: int, segment_len: int,
                      clusters_per_segment: int, iters: int, seed: int,
                      ws: Optional[torch.Tensor] = None, index: Optional[Index] = None,
-                     row_capacity: int = 0) -> Index:
+                     row_capacity: int = 0, steady_capacity: int = 0) -> Index:
     """K, V: [B, Hkv, N, d] device tensors (f32 or bf16).  Enqueues the build on
     the current stream and returns the index (valid after a stream sync)."""
     assert K.is_cuda and V.is_cuda and K.shape == V.shape and K.dtype == V.dtype
     K, V = K.contiguous(), V.contiguous()
     B, Hkv, N, d = K.shape
     ix = index or alloc_index(K.dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
-                              clusters_per_segment, K.device, row_capacity=row_capacity)
+                              clusters_per_segment, K.device, row_capacity=row_capacity,
+                              steady_capacity=steady_capacity)
     if ws is None:
         ws = workspace(ix.build_ws_bytes, K.device)
     st = lib().wave_index_build(K.data_ptr(), V.data_ptr(), ctypes.byref(ix.c), iters, seed,
@@ -232,7 +235,10 @@ def wave_index_append(ix: Index, K_new: Optional[torch.Tensor], V_new: Optional[
     in_place = c.row_capacity > 0 and c.row_capacity == ix.c.row_capacity   # rows added behind the old ones
     for name, nbytes in zip(BUFFER_NAMES, sizes):
         dt = torch.int32 if name in ("sizes", "offsets", "perm") else ix.dtype
-        if (keep and name not in ("k_steady", "v_steady")) or (in_place and name in ("perm", "k_perm", "v_perm")):
+        steady_in_place = (keep and c.steady_capacity > 0 and c.steady_capacity == ix.c.steady_capacity
+                           and name in ("k_steady", "v_steady"))   # the new tokens' rows behind the window
+        if ((keep and name not in ("k_steady", "v_steady")) or steady_in_place
+                or (in_place and name in ("perm", "k_perm", "v_perm"))):
             t = ix.t[name]
         else:
             t = torch.empty(_shapes(c)[name], dtype=dt, device=device)

@@ -103,7 +103,7 @@ static wave_status check_dims(const wave_index* ix) {
   if (ix->segment_len < 1 || ix->clusters_per_segment < 1) return WAVE_ERR_ARG;
   if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
   if (ix->clusters_per_segment > 4096) return WAVE_ERR_SHAPE;
-  if (ix->appended_segments < 0 || ix->row_capacity < 0) return WAVE_ERR_ARG;
+  if (ix->appended_segments < 0 || ix->row_capacity < 0 || ix->steady_capacity < 0) return WAVE_ERR_ARG;
   if (ix->appended_segments > 0) {
     if (ix->update_segment_len < 1 || ix->update_clusters < 1) return WAVE_ERR_ARG;
     if (ix->update_clusters > 4096) return WAVE_ERR_SHAPE;
@@ -139,6 +139,7 @@ static Derived derive(const wave_index& ix) {
 static bool planned_fields_match(const wave_index& ix) {
   const Derived d = derive(ix);
   if (ix.row_capacity > 0 && ix.row_capacity < d.N_idx) return false;
+  if (ix.steady_capacity > 0 && ix.steady_capacity < d.p) return false;
   return ix.S == d.S && ix.m == d.m && ix.N_idx == d.N_idx && ix.p == d.p;
 }
 
@@ -159,6 +160,7 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   const Derived d = derive(*ix);
   if ((long long)ix->B * ix->Hkv * ((long long)d.m + 1) >= (1ll << 31)) return WAVE_ERR_SHAPE;
   if (d.m < 0 || (ix->row_capacity > 0 && ix->row_capacity < d.N_idx)) return WAVE_ERR_SHAPE;
+  if (ix->steady_capacity > 0 && ix->steady_capacity < d.p) return WAVE_ERR_SHAPE;
   ix->S = d.S;
   ix->m = d.m;
   ix->N_idx = d.N_idx;
@@ -173,7 +175,7 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   bytes[4] = units * rows * sizeof(int32_t);
   bytes[5] = units * rows * ix->d * es;
   bytes[6] = bytes[5];
-  bytes[7] = units * d.p * ix->d * es;
+  bytes[7] = units * (ix->steady_capacity > 0 ? (size_t)ix->steady_capacity : (size_t)d.p) * ix->d * es;
   bytes[8] = bytes[7];
   if (build_workspace_bytes) *build_workspace_bytes = build_geometry(*ix).total;
   if (decode_workspace_bytes) {
@@ -283,6 +285,7 @@ static wave_status plan_append(const wave_index* old_ix, int n_new, int n_local_
   nw.update_segment_len = U;
   nw.update_clusters = k_u;
   if ((long long)old_ix->N_idx + (long long)g.F * U > old_ix->row_capacity) nw.row_capacity = 0;
+  if (old_ix->n_sink + nw.n_local > old_ix->steady_capacity) nw.steady_capacity = 0;
   *out = nw;
   return WAVE_OK;
 }
@@ -334,7 +337,12 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
     const bool in_place = new_ix->row_capacity > 0 && new_ix->row_capacity == old_ix->row_capacity;
     for (int i = 0; i < 7; ++i)
       if (g.F > 0 && a[i] && a[i] == b[i] && !(in_place && i >= 4)) return WAVE_ERR_ARG;
-    if (old_ix->k_steady && (old_ix->k_steady == new_ix->k_steady || old_ix->v_steady == new_ix->v_steady))
+    const bool steady_in_place = g.F == 0 && new_ix->steady_capacity > 0 &&
+                                 new_ix->steady_capacity == old_ix->steady_capacity;
+    if (old_ix->k_steady && !steady_in_place &&
+        (old_ix->k_steady == new_ix->k_steady || old_ix->v_steady == new_ix->v_steady))
+      return WAVE_ERR_ARG;
+    if (steady_in_place && (old_ix->k_steady == new_ix->k_steady) != (old_ix->v_steady == new_ix->v_steady))
       return WAVE_ERR_ARG;
   }
   if (g.total > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total))

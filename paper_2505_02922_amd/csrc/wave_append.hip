@@ -56,14 +56,16 @@ __global__ __launch_bounds__(256) void route_window_kernel(
     const char* __restrict__ ks_old, const char* __restrict__ vs_old, const char* __restrict__ k_new,
     const char* __restrict__ v_new, char* __restrict__ k_flush, char* __restrict__ v_flush,
     char* __restrict__ ks_out, char* __restrict__ vs_out, int ns, int lc_old, int n_new, int flush,
-    int p_old, int p_out, int units) {
+    int p_old, int p_out, int units, int first) {
+  // p_old, p_out: rows per unit of the old and the new steady buffers; first: rows before it are
+  // already in place (the new buffers are the old ones and nothing is flushed)
   constexpr int CPR = ROWB / 16;
-  const size_t rows_u = (size_t)ns + lc_old + n_new;
+  const size_t rows_u = (size_t)ns + lc_old + n_new - first;
   const size_t total = rows_u * units * CPR, step = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += step) {
     const size_t row = i / CPR, ch = i - row * CPR;
     const size_t u = row / rows_u;
-    const int j = (int)(row - u * rows_u);
+    const int j = (int)(row - u * rows_u) + first;
     const char *sk, *sv;
     if (j < ns + lc_old) {
       sk = ks_old + ((size_t)u * p_old + j) * ROWB;
@@ -126,14 +128,16 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
 
   // (2) sink rows and the window
   {
-    const size_t chunks = ((size_t)ns + g.lc_old + n_new) * units * rowc;
+    // with the old steady buffers as the new ones (no flush, room left) only the new tokens move
+    const int first = nw.k_steady == o.k_steady ? ns + g.lc_old : 0;
+    const size_t chunks = ((size_t)ns + g.lc_old + n_new - first) * units * rowc;
     if (chunks > 0) {
 #define WAVE_ROUTE(ROWB)                                                                              \
   WAVE_LAUNCH("append_window", (route_window_kernel<ROWB>), grid_for(chunks), 256, 0, st,             \
               static_cast<const char*>(o.k_steady), static_cast<const char*>(o.v_steady),             \
               static_cast<const char*>(K_new), static_cast<const char*>(V_new), w + g.off_k,          \
               w + g.off_v, static_cast<char*>(nw.k_steady), static_cast<char*>(nw.v_steady), ns,      \
-              g.lc_old, n_new, flush, o.p, nw.p, units)
+              g.lc_old, n_new, flush, steady_stride(o), steady_stride(nw), units, first)
       const size_t rowb = (size_t)D * es;
       if (rowb == 128) WAVE_ROUTE(128);
       else if (rowb == 256) WAVE_ROUTE(256);

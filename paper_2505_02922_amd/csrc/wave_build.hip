@@ -779,14 +779,15 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void steady_copy_kernel(const T* __restrict__ K, const T* __restrict__ V,
                                                           T* __restrict__ ks, T* __restrict__ vs, int N,
                                                           int ns, int local_start, int p,
-                                                          int rows_total) {
+                                                          int p_stride, int rows_total) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   for (int row = blockIdx.x * GROUPS + grp; row < rows_total; row += gridDim.x * GROUPS) {
     const int unit = row / p, i = row - unit * p;
     const int src = i < ns ? i : local_start + (i - ns);
-    store16(ks + (size_t)row * D + sub * EPC, load16(K + ((size_t)unit * N + src) * D + sub * EPC));
-    store16(vs + (size_t)row * D + sub * EPC, load16(V + ((size_t)unit * N + src) * D + sub * EPC));
+    const size_t dst = (size_t)unit * p_stride + i;  // p_stride: rows per unit in the steady buffers
+    store16(ks + dst * D + sub * EPC, load16(K + ((size_t)unit * N + src) * D + sub * EPC));
+    store16(vs + dst * D + sub * EPC, load16(V + ((size_t)unit * N + src) * D + sub * EPC));
   }
 }
 
@@ -873,7 +874,7 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     const int grid = (rows + 15) / 16 < 65536 ? (rows + 15) / 16 : 65536;
     WAVE_LAUNCH("steady_copy", (steady_copy_kernel<T, D>), grid, 256, 0, st, K, V,
                 static_cast<T*>(ix.k_steady), static_cast<T*>(ix.v_steady), ix.N, ns, local_start, ix.p,
-                rows);
+                steady_stride(ix), rows);
   }
   if (ix.m == 0) {
     // nothing to cluster: the offsets array is the single entry offsets[0] = 0 per unit

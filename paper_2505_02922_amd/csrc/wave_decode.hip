@@ -1832,7 +1832,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot, const T* __restrict__ k_perm,
     const T* __restrict__ v_perm, int N_idx, const T* __restrict__ k_steady,
-    const T* __restrict__ v_steady, int p, int stagger_period, float* __restrict__ out,
+    const T* __restrict__ v_steady, int p, int p_stride, int stagger_period, float* __restrict__ out,
     float* __restrict__ lse) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
   constexpr int GROUPS = NWV * RPW, U = 4, TILE = NT;
@@ -1858,8 +1858,8 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   // other period streams its steady rows first and the rest does it last: one
   // neighbour streams while the other selects.
   auto steady_rows = [&]() {
-    const T* Ks = k_steady + (size_t)unit * p * D + sub * EPC;
-    const T* Vs = v_steady + (size_t)unit * p * D + sub * EPC;
+    const T* Ks = k_steady + (size_t)unit * p_stride * D + sub * EPC;
+    const T* Vs = v_steady + (size_t)unit * p_stride * D + sub * EPC;
     for (int i = grp; i < p; i += GROUPS * U) {
       uint4 kraw[U], vraw[U];
       bool valid[U];
@@ -1944,7 +1944,7 @@ template <typename T, int D, int G, int NT>
 __device__ __forceinline__ void steady_rows_partial(const T* __restrict__ q,
                                                     const T* __restrict__ k_steady,
                                                     const T* __restrict__ v_steady, int unit, int bh0,
-                                                    int p, int r0, int r1, float scale_log2,
+                                                    int p_stride, int r0, int r1, float scale_log2,
                                                     float* smem, float* __restrict__ part_head0,
                                                     size_t head_stride) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
@@ -1953,8 +1953,8 @@ __device__ __forceinline__ void steady_rows_partial(const T* __restrict__ q,
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
   AttnState<T, D, G> st;
   st.init(q + (size_t)bh0 * D, sub, scale_log2);
-  const T* Ku = k_steady + (size_t)unit * p * D + sub * EPC;
-  const T* Vu = v_steady + (size_t)unit * p * D + sub * EPC;
+  const T* Ku = k_steady + (size_t)unit * p_stride * D + sub * EPC;  // p_stride: rows per unit
+  const T* Vu = v_steady + (size_t)unit * p_stride * D + sub * EPC;
   for (int i = r0 + grp; i < r1; i += GROUPS * U) {
     uint4 kraw[U], vraw[U];
     bool valid[U];
@@ -1975,8 +1975,8 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
                                                      const T* __restrict__ k_steady,
                                                      const T* __restrict__ v_steady, int Hkv, int p,
-                                                     int chunks, int rows_per_chunk, int slots,
-                                                     int slot0, float scale_log2,
+                                                     int p_stride, int chunks, int rows_per_chunk,
+                                                     int slots, int slot0, float scale_log2,
                                                      float* __restrict__ part) {
   const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
   const int unit = wg / chunks, chunk = wg - unit * chunks;
@@ -1984,7 +1984,7 @@ __global__ __launch_bounds__(256) void steady_kernel(const T* __restrict__ q,
   __shared__ float smem[4 * G * (D + 2)];
   const int bh0 = b * Hq + h * G;
   const int r0 = chunk * rows_per_chunk, r1 = min(p, r0 + rows_per_chunk);
-  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p, r0, r1, scale_log2, smem,
+  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p_stride, r0, r1, scale_log2, smem,
                                     part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
                                     (size_t)slots * (D + 2));
 }
@@ -1997,7 +1997,7 @@ __global__ __launch_bounds__(256) void dense_steady_kernel(
     const int32_t* __restrict__ sizes, float* __restrict__ z, float* __restrict__ cn2part, int Hkv,
     int m, int chunks, int slots, int slot0, float scale_log2, float* __restrict__ part,
     int n_dense_wgs, const T* __restrict__ k_steady, const T* __restrict__ v_steady, int p,
-    int steady_chunks, int steady_rows, int steady_slot0) {
+    int p_stride, int steady_chunks, int steady_rows, int steady_slot0) {
   using Lds = DenseLds<T, D, G, 256>;
   constexpr size_t kSteadyBytes = sizeof(float) * 4 * G * (D + 2);
   __shared__ __attribute__((aligned(16))) char
@@ -2024,7 +2024,7 @@ __global__ __launch_bounds__(256) void dense_steady_kernel(
   const int b = unit / Hkv, h = unit - b * Hkv;
   const int bh0 = b * Hq + h * G;
   const int r0 = chunk * steady_rows, r1 = min(p, r0 + steady_rows);
-  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p, r0, r1, scale_log2,
+  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p_stride, r0, r1, scale_log2,
                                     reinterpret_cast<float*>(lds_raw),
                                     part + ((size_t)bh0 * slots + steady_slot0 + chunk) * (D + 2),
                                     (size_t)slots * (D + 2));
@@ -2038,7 +2038,7 @@ struct SideWork {
   int est_rows, est_chunks, est_slot0, est_first, n_est_wgs;
   const void* k_steady;
   const void* v_steady;
-  int p, steady_chunks, steady_rows, steady_slot0;
+  int p, p_stride, steady_chunks, steady_rows, steady_slot0;
 };
 
 template <typename T, int D, int G, int NT>
@@ -2118,7 +2118,7 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
   const int bh0 = b * Hq + h * G;
   const int r0 = chunk * sw.steady_rows, r1 = min(sw.p, r0 + sw.steady_rows);
   steady_rows_partial<T, D, G, NT>(q, static_cast<const T*>(sw.k_steady),
-                                   static_cast<const T*>(sw.v_steady), unit, bh0, sw.p, r0, r1,
+                                   static_cast<const T*>(sw.v_steady), unit, bh0, sw.p_stride, r0, r1,
                                    scale_log2, reinterpret_cast<float*>(lds_raw),
                                    part + ((size_t)bh0 * slots + sw.steady_slot0 + chunk) * (D + 2),
                                    (size_t)slots * (D + 2));
@@ -2487,7 +2487,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
                   ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part,
                   units * g.score_chunks, static_cast<const T*>(ix.k_steady),
-                  static_cast<const T*>(ix.v_steady), ix.p, g.steady_chunks, g.steady_rows,
+                  static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows,
                   g.gather_chunks);
     else
       WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
@@ -2502,7 +2502,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       WAVE_LAUNCH("select_gather_steady", (select_gather_kernel<T, D, 512, 32, true>), heads, 512,
                   key_lds, st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
                   static_cast<const T*>(ix.v_perm), row_stride(ix), static_cast<const T*>(ix.k_steady),
-                  static_cast<const T*>(ix.v_steady), ix.p, 2, out, lse);
+                  static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 2, out, lse);
     } else {
       if (g.sliced) {
         int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
@@ -2522,7 +2522,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
         const int n_est = units * g.est_chunks;
         const int n_est_a = (int)((long long)n_est * g.est_with_slices_pct / 100);
         SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, n_est_a, ix.k_steady,
-                    ix.v_steady, ix.p, g.steady_chunks, g.steady_rows, g.gather_chunks};
+                    ix.v_steady, ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows, g.gather_chunks};
         WAVE_LAUNCH("select_slices+side", (filter_side_kernel<T, D, G, 512, 32>),
                     heads * g.nslices + n_est_a + units * g.steady_chunks, 512, lds_a, st,
                     WAVE_SELECT_ARGS, g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, sw,
@@ -2555,6 +2555,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (m == 0 && g.steady_chunks > 0)  // with clusters, the steady pieces ride with an earlier launch
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
+                steady_stride(ix),
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
   if (!g.fused)  // the fused kernel normalises each head itself
     WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part,
@@ -2666,7 +2667,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
       const int npos_max = g.nslices * k;
       const size_t lds_a = sizeof(uint32_t) * 512 * (size_t)((g.slice_len + 511) / 512);
       const size_t lds_b = sizeof(uint32_t) * 512 * (size_t)((npos_max + 511) / 512);
-      SideWork none{ix.sizes, 512, 1, 0, 0, 0, ix.k_steady, ix.v_steady, ix.p, 0, 64, 0};
+      SideWork none{ix.sizes, 512, 1, 0, 0, 0, ix.k_steady, ix.v_steady, ix.p, steady_stride(ix), 0, 64, 0};
       WAVE_LAUNCH("select_slices", (slices_side_kernel<T, D, G, 512, 32>), heads * g.nslices, 512, lds_a,
                   st, WAVE_SEL(k), g.nslices, g.slice_len, slice_ids, slice_z, heads * g.nslices, none);
       WAVE_LAUNCH("select", (combine_side_kernel<T, D, G, 512, 32>), heads, 512, lds_b, st, WAVE_SEL(k),
@@ -2688,6 +2689,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (g.steady_chunks > 0)
     WAVE_LAUNCH("steady", (steady_kernel<T, D, G>), units * g.steady_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
+                steady_stride(ix),
                 g.steady_chunks, g.steady_rows, slots, 0, scale_log2, part);
   if (g.gather_chunks > 0)
     WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
@@ -2723,7 +2725,7 @@ static wave_status full_tdg(const void* q, const void* K, const void* V, int B, 
   float* part = static_cast<float*>(ws);
   const float scale_log2 = kLog2e / sqrtf((float)D);
   WAVE_LAUNCH("full_attention", (steady_kernel<T, D, G>), units * chunks, 256, 0, st,
-              static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), Hkv, N,
+              static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), Hkv, N, N,
               chunks, FULL_ATTN_ROWS, chunks, 0, scale_log2, part);
   WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, chunks, chunks, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;

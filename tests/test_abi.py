@@ -109,7 +109,17 @@ def test_row_capacity_in_the_plan():
     with pytest.raises(wb.WaveError) as e:
         wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, row_capacity=4000)
     assert e.value.status == 2
+    c2, sizes2, _, _ = wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, steady_capacity=100)
+    assert c2.p == 68 and sizes2[7] == sizes2[8] == 6 * 100 * 256
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, steady_capacity=67)
+    assert e.value.status == 2
     L_ = wb.lib()
+    for n_new, stays in ((32, True), (33, False)):         # 68 + 32 rows fill the room exactly
+        cn = wb.wave_index()
+        st = L_.wave_index_append_plan(ctypes.byref(c2), n_new, 64, 256, 16, ctypes.byref(cn),
+                                       (ctypes.c_size_t * 9)(), None)
+        assert st == 0 and cn.p == 68 + n_new and cn.steady_capacity == (100 if stays else 0)
     for n_new, keeps in ((1024, True), (1300, False)):    # 4 or 5 update segments of 256 rows
         cn = wb.wave_index()
         st = L_.wave_index_append_plan(ctypes.byref(c), n_new, 64, 256, 16, ctypes.byref(cn),

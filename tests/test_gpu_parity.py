@@ -432,18 +432,18 @@ _SHORT = _small("tiny_f32", name="f32_short", N=50, n_sink=4, n_local=64, segmen
                 clusters_per_segment=128, iters=3, retrieve_abs=2)
 
 
-@pytest.mark.parametrize("case,n_news,U,ku,cap", [("bf16_g4", (300, 37, 1000), 256, 16, 0),
-                                                  ("bf16_g4", (300, 37, 1000), 256, 16, 5400),
-                                                  ("tiny_f32", (5, 200), 64, 8, 0),
-                                                  ("tiny_f32", (5, 200), 64, 8, 8192),
-                                                  ("bf16_d64", (130,), 128, 200, 0),
-                                                  (_SHORT, (10, 100), 32, 4, 0)])
-def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap):
+@pytest.mark.parametrize("case,n_news,U,ku,cap,scap", [("bf16_g4", (300, 37, 1000), 256, 16, 0, 0),
+                                                       ("bf16_g4", (300, 37, 1, 1000), 256, 16, 5400, 480),
+                                                       ("tiny_f32", (5, 200), 64, 8, 0, 0),
+                                                       ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140),
+                                                       ("bf16_d64", (130,), 128, 200, 0, 0),
+                                                       (_SHORT, (10, 100), 32, 4, 0, 0)])
+def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap):
     """Incremental index update through the C ABI, several times in a row (without and with
     flushed update segments, more clusters asked for than an update segment has tokens, an
-    index with no clusters yet; once with room for the new rows, which are then added in
-    place, and once with room that runs out on the way): every array of the grown index
-    against the oracle's, then decode on it."""
+    index with no clusters yet; once with room for the new rows and the new steady rows,
+    which are then added in place, and once with room that runs out on the way): every array
+    of the grown index against the oracle's, then decode on it."""
     wl = CASES[case] if isinstance(case, str) else case
     total_new = sum(n_news)
     big = synth.scaled(wl, N=wl.N + total_new)
@@ -451,8 +451,8 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap):
     K0, V0 = Kall[:, :, :wl.N].contiguous(), Vall[:, :, :wl.N].contiguous()
     ref = pu.oracle_build(wl, K0, V0)
     ix = wb.wave_index_build(K0.cuda(), V0.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
-                             wl.clusters_per_segment, wl.iters, 0, row_capacity=cap)
-    first, shared_rows = ix, 0
+                             wl.clusters_per_segment, wl.iters, 0, row_capacity=cap, steady_capacity=scap)
+    first, shared_rows, shared_steady = ix, 0, 0
     pos = wl.N
     for n_new in n_news:
         Kn, Vn = Kall[:, :, pos:pos + n_new].contiguous(), Vall[:, :, pos:pos + n_new].contiguous()
@@ -460,6 +460,7 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap):
         ix = wb.wave_index_append(ix, Kn.cuda(), Vn.cuda(), wl.n_local, U, ku, wl.iters, 0)
         torch.cuda.synchronize()
         shared_rows += int(ix.k_perm.data_ptr() == before.k_perm.data_ptr() and ix.m > before.m)
+        shared_steady += int(ix.k_steady.data_ptr() == before.k_steady.data_ptr())
         for (b, h), u in ref.items():
             ref[(b, h)] = wo.append_unit(u, Kn[b, h].double().numpy(), Vn[b, h].double().numpy(),
                                          wl.n_local, U, ku, wl.iters, 0, b, h)
@@ -473,10 +474,14 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap):
                 got = got[:ix.N_idx] if name == "perm" else got
                 assert np.array_equal(got, getattr(u, name)), (n_new, b, h, name)
             for name in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
-                got = getattr(ix, name)[b, h].float().cpu().numpy().astype(np.float64)
-                got = got[:ix.N_idx] if name in ("k_perm", "v_perm") else got
+                t = getattr(ix, name)[b, h]
+                t = t[:ix.N_idx] if name in ("k_perm", "v_perm") else t    # rows in use
+                t = t[:ix.p] if name in ("k_steady", "v_steady") else t
+                got = t.float().cpu().numpy().astype(np.float64)
                 assert np.array_equal(got, getattr(u, name)), (n_new, b, h, name)
     assert ix.appended_segments > 0
+    if scap:
+        assert shared_steady >= 1     # an update without a flush wrote its rows behind the old window
     if cap == 8192:
         assert shared_rows >= 1 and ix.row_capacity == cap      # the rows were added in place
     if cap == 5400:
