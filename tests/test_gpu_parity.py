@@ -251,19 +251,22 @@ def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
                 perm=np.arange(n), k_perm=Kp, v_perm=Vp, k_steady=Ks, v_steady=Vs), n
 
 
-@pytest.mark.parametrize("m,dup,Hq", [(3000, True, 2), (20000, False, 2), (40000, True, 2),
-                                      (70000, False, 2), (20000, True, 7)])
-def test_decode_many_clusters_hand_index(m, dup, Hq):
+@pytest.mark.parametrize("m,dup,Hq,dtype", [(3000, True, 2, "bf16"), (20000, False, 2, "bf16"),
+                                            (40000, True, 2, "bf16"), (70000, False, 2, "bf16"),
+                                            (20000, True, 7, "bf16"), (20000, True, 3, "f32")])
+def test_decode_many_clusters_hand_index(m, dup, Hq, dtype):
     """Every size class of the selection (32-bit keys in LDS, slices + union, 16-bit keys
     in LDS, and the streaming fallback), with and without exact score ties; once with 7
-    query heads on the KV head (the estimation and steady work beside the slices at G = 7)."""
-    d, dtype, p, Hkv = 128, "bf16", 8, 1
+    query heads on the KV head (the estimation and steady work beside the slices at G = 7)
+    and once in f32 through the slices (scores and tile maxima without MFMA)."""
+    d, p, Hkv = 128, 8, 1
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     arrs, n = _hand_index(m, d, dtype, p, seed=m, dup_scores=dup)
     # Dimensions whose plan has exactly m clusters: segments of 4 tokens with one
     # cluster each.  The hand index then fills sizes/offsets as it likes (0..3 rows
     # per cluster); rows beyond its n are padding that no offset points at.
     L = 4
-    c, sizes_b, bws, dws = wb.wave_index_plan(torch.bfloat16, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1)
+    c, sizes_b, bws, dws = wb.wave_index_plan(tdt, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1)
     assert c.m == m
     # rows of k_perm/v_perm are allocated for N_idx = 4 m >= n; pad the hand rows
     pad = c.N_idx - n
@@ -272,18 +275,18 @@ def test_decode_many_clusters_hand_index(m, dup, Hq):
     arrs["perm"] = np.arange(c.N_idx)
     tens = {k: torch.from_numpy(np.asarray(v)[None, None].astype(
         np.int32 if k in ("sizes", "offsets", "perm") else np.float32)) for k, v in arrs.items()}
-    ix = wb.index_from_arrays(torch.bfloat16, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1, tens)
+    ix = wb.index_from_arrays(tdt, 1, Hkv, d, 4 * m + p, 4, p - 4, L, 1, tens)
     plan = wo.make_plan(4 * m + p, 4, p - 4, L, 1)
     ref = wo.UnitIndex(plan, dtype, arrs["centroids"], arrs["vsum"], arrs["sizes"], arrs["offsets"],
                        arrs["perm"], arrs["k_perm"], arrs["v_perm"], arrs["k_steady"],
                        arrs["v_steady"], np.zeros(0, dtype=np.int64))
     g = np.random.default_rng(5)
     q = torch.from_numpy(wo.quant(g.standard_normal((1, Hq, d)) * 2.0, dtype).astype(np.float32)
-                         ).to(torch.bfloat16)
+                         ).to(tdt)
     if dup:   # head 0 looks straight at the shared centroid: the tied scores are the largest
         q[0, 0] = torch.from_numpy(wo.quant(arrs["centroids"][7] * 3.0, dtype).astype(np.float32)
-                                   ).to(torch.bfloat16)
-    wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d)
+                                   ).to(tdt)
+    wl = _small("llama8b_32k", name="hand", B=1, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype)
     # r = 2000 at m = 20000: more clusters asked for than there are 16-cluster tiles, so
     # the slices' cheap first stage has no bound to offer and every slice is ranked exactly;
     # with the tied scores on top a slice holds more than r candidates, same fallback
