@@ -251,15 +251,16 @@ def _hand_index(m, d, dtype, n_steady, seed, dup_scores=False):
                 perm=np.arange(n), k_perm=Kp, v_perm=Vp, k_steady=Ks, v_steady=Vs), n
 
 
-@pytest.mark.parametrize("m,dup,Hq,dtype", [(3000, True, 2, "bf16"), (20000, False, 2, "bf16"),
-                                            (40000, True, 2, "bf16"), (70000, False, 2, "bf16"),
-                                            (20000, True, 7, "bf16"), (20000, True, 3, "f32")])
-def test_decode_many_clusters_hand_index(m, dup, Hq, dtype):
+@pytest.mark.parametrize("m,dup,Hq,dtype,d", [(3000, True, 2, "bf16", 128), (20000, False, 2, "bf16", 128),
+                                              (40000, True, 2, "bf16", 128), (70000, False, 2, "bf16", 128),
+                                              (20000, True, 7, "bf16", 128), (20000, True, 3, "f32", 128),
+                                              (20000, False, 4, "bf16", 64), (70000, True, 2, "f32", 64)])
+def test_decode_many_clusters_hand_index(m, dup, Hq, dtype, d):
     """Every size class of the selection (32-bit keys in LDS, slices + union, 16-bit keys
     in LDS, and the streaming fallback), with and without exact score ties; once with 7
     query heads on the KV head (the estimation and steady work beside the slices at G = 7)
     and once in f32 through the slices (scores and tile maxima without MFMA)."""
-    d, p, Hkv = 128, 8, 1
+    p, Hkv = 8, 1
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     arrs, n = _hand_index(m, d, dtype, p, seed=m, dup_scores=dup)
     # Dimensions whose plan has exactly m clusters: segments of 4 tokens with one
