@@ -327,15 +327,50 @@ def test_full_size_workload_sampled_units(name, units):
     torch.cuda.synchronize()
     plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
     qn = q.double().cpu().numpy()
+    refs = {}
     for (b, h) in units:
         ref = wo.build_unit(K[b, h].double().cpu().numpy(), V[b, h].double().cpu().numpy(), plan,
                             wl.iters, 0, b, h, wl.dtype)
+        refs[(b, h)] = ref
         tag = f"{name} b={b} h={h}"
         assert np.array_equal(ix.sizes[b, h].cpu().numpy(), ref.sizes), tag
         assert np.array_equal(ix.offsets[b, h].cpu().numpy(), ref.offsets), tag
         assert np.array_equal(ix.perm[b, h].cpu().numpy(), ref.perm), tag
         for nm in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
             assert np.array_equal(ix.t[nm][b, h].float().cpu().numpy(),
+                                  getattr(ref, nm).astype(np.float32)), (tag, nm)
+        for g in range(wl.G):
+            hq = h * wl.G + g
+            parts = {}
+            o, l, s = wo.decode_unit(qn[b, hq], ref, r, parts)
+            pu.check_outputs(out[b, hq].cpu().numpy(), lse[b, hq:hq + 1].cpu().numpy(), o,
+                             np.array([l]), wl.dtype, f"{tag} hq={hq}")
+            pu.check_selected(sel[b, hq].cpu().numpy(), s, parts["z"], f"{tag} hq={hq}")
+    if name != "llama8b_120k_b16":
+        return
+    # the index update at full size: one update segment of 1024 new tokens per sequence
+    # (the paper's update segment size), 64 clusters, on the whole batch; sampled units
+    # against the oracle's update of its own index, then decode on the grown index
+    del out, lse, sel
+    U, ku = 1024, 64
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(17)
+    Kn = (K[:, :, -U:] + 0.05 * torch.randn(wl.B, wl.Hkv, U, wl.d, generator=gen, device=dev).to(K.dtype)).contiguous()
+    Vn = torch.randn(wl.B, wl.Hkv, U, wl.d, generator=gen, device=dev).to(V.dtype)
+    ix2 = wb.wave_index_append(ix, Kn, Vn, wl.n_local, U, ku, wl.iters, 0)
+    torch.cuda.synchronize()
+    assert (ix2.N, ix2.m, ix2.N_idx, ix2.n_local) == (wl.N + U, ix.m + ku, ix.N_idx + U, wl.n_local)
+    out, lse, sel = wb.wave_attention_decode(q, ix2, r, want_selected=True)
+    torch.cuda.synchronize()
+    for (b, h) in units:
+        ref = wo.append_unit(refs[(b, h)], Kn[b, h].double().cpu().numpy(), Vn[b, h].double().cpu().numpy(),
+                             wl.n_local, U, ku, wl.iters, 0, b, h)
+        tag = f"{name} grown b={b} h={h}"
+        assert np.array_equal(ix2.sizes[b, h].cpu().numpy(), ref.sizes), tag
+        assert np.array_equal(ix2.offsets[b, h].cpu().numpy(), ref.offsets), tag
+        assert np.array_equal(ix2.perm[b, h].cpu().numpy(), ref.perm), tag
+        for nm in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
+            assert np.array_equal(ix2.t[nm][b, h].float().cpu().numpy(),
                                   getattr(ref, nm).astype(np.float32)), (tag, nm)
         for g in range(wl.G):
             hq = h * wl.G + g
