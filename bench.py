@@ -343,6 +343,26 @@ def main() -> int:
                     "ms_per_step": round(ms_per_step, 4),
                     "rel_l2_diff_to_full_attention": full_info["rel_l2_diff_of_outputs"]})
     full_info["zone_budgets"] = budgets
+    # retrieval-zone sweep (the same query set; every other cluster estimated)
+    sweep = []
+    for frac in (0.0, 0.005, 0.01, 0.018, 0.036, 0.072):
+        rr = int(round(frac * ix.m))
+        sws = wb.workspace(wb.decode_workspace_bytes(ix, wl.Hq, rr), dev)
+        sout, slse = torch.empty_like(out), torch.empty_like(lse)
+        for i in range(2):
+            wb.wave_attention_decode(queries[0], ix, rr, out=sout, lse=slse, ws=sws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(10):
+            wb.wave_attention_decode(queries[0], ix, rr, out=sout, lse=slse, ws=sws)
+        e1.record()
+        torch.cuda.synchronize()
+        sweep.append({"retrieved_share_of_clusters": frac, "r": rr,
+                      "ms_per_step": round(e0.elapsed_time(e1) / 10, 4),
+                      "rel_l2_diff_to_full_attention": float((sout - fout).norm() / fout.norm())})
+        del sws
+    full_info["retrieval_sweep"] = sweep
 
     # ---------------- index update during decoding (context) ----------------
     # One update segment of 1024 new tokens per sequence (the paper's update segment size),
