@@ -215,3 +215,57 @@ def test_init_indices_match_the_oracle():
         assert got == want, (seed, b, h, s, L_s, k_s)
     with pytest.raises(wb.WaveError):
         wb.wave_init_indices(0, 0, 0, 0, 10, 11)
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The package (binding, build script, input generators) neither imports nor names the
+    oracle: only tests, the smoke check and the benchmark's baseline leg may."""
+    pkg = os.path.join(ROOT, "paper_2505_02922_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(base, f)).read()
+                assert "wave_oracle" not in text and "import oracle" not in text and "from oracle" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_append_refuses_bad_arguments_on_the_host():
+    """Returns before anything is launched (no GPU here)."""
+    L_ = wb.lib()
+    c0, _, _, _ = wb.wave_index_plan(torch.bfloat16, 1, 2, 128, 5000, 4, 64, 1024, 64)
+    cn = wb.wave_index()
+    sizes = (ctypes.c_size_t * 9)()
+    wsb = ctypes.c_size_t(0)
+    plan = lambda n, nl, U, ku: L_.wave_index_append_plan(ctypes.byref(c0), n, nl, U, ku, ctypes.byref(cn),
+                                                          sizes, ctypes.byref(wsb))
+    assert plan(-1, 64, 256, 16) == 1 and plan(10, -1, 256, 16) == 1
+    assert plan(10, 64, 0, 16) == 1 and plan(10, 64, 256, 0) == 1
+    assert plan(10, 64, 256, 5000) == 2
+    assert plan(300, 64, 256, 16) == 0 and cn.appended_segments == 1 and wsb.value > 0
+    fake = ctypes.c_void_p(0x1000)
+    for name in wb.BUFFER_NAMES:
+        setattr(c0, name, 0x1000)
+        setattr(cn, name, 0x2000)
+    app = lambda new, ws, wsbytes, iters=3: L_.wave_index_append(
+        ctypes.byref(c0), fake, fake, 300, 64, 256, 16, iters, 0, ctypes.byref(new), ws, wsbytes, None)
+    assert app(cn, fake, wsb.value - 1) == 4            # workspace too small
+    assert app(cn, None, wsb.value) == 4                # no workspace
+    assert app(cn, fake, wsb.value, iters=0) == 1
+    cn.m += 1                                           # not the plan of this update
+    assert app(cn, fake, wsb.value) == 2
+    cn.m -= 1
+    cn.k_perm = c0.k_perm                               # rows in place without room for them
+    assert app(cn, fake, wsb.value) == 1
+    cn.k_perm = 0x2000
+    c0.appended_segments = 0
+    # an index that holds update segments cannot be rebuilt by the plain build
+    cn2 = wb.wave_index()
+    ctypes.memmove(ctypes.byref(cn2), ctypes.byref(cn), ctypes.sizeof(wb.wave_index))
+    assert L_.wave_index_build(fake, fake, ctypes.byref(cn2), 3, 0, fake, 1 << 30, None) == 2
