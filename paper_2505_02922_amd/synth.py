@@ -59,6 +59,14 @@ class Workload:
     def torch_dtype(self) -> torch.dtype:
         return {"f32": torch.float32, "bf16": torch.bfloat16}[self.dtype]
 
+    def retrieve_count(self, m: int) -> int:
+        """The workload's retrieval budget r for an index of m clusters per KV head: the
+        absolute count if one is given, else the fraction of m rounded to the nearest integer
+        (the paper's 150 of 8192 clusters = 1.8 %)."""
+        if self.retrieve_abs is not None:
+            return self.retrieve_abs
+        return int(math.floor(self.retrieve_frac * m + 0.5))
+
 
 def _wl(**kw) -> Workload:
     return Workload(**kw)

@@ -92,34 +92,3 @@ def check_assign(a_gpu: np.ndarray, xhat: np.ndarray, chat: np.ndarray, what: st
         assert abs(top - scores[j, a_gpu[j]]) <= TIE_REL * abs(top), \
             f"{what}: point {j}: gpu {a_gpu[j]} oracle {a_ref[j]} gap {top - scores[j, a_gpu[j]]}"
     return bad.size
-
-
-def recall_at_gpu(q, ix, sel, Hq, top=100):
-    """recall@top per query head from the device index, with torch ops (a measurement,
-    not part of the library): of the `top` indexed tokens with the largest q . K_j, the
-    share lying in the head's selected clusters.  q [B,Hq,d], sel [B,Hq,r] (-1 padded).
-    Returns a [B,Hq] float tensor."""
-    import torch
-    B, Hkv = ix.B, ix.Hkv
-    G = Hq // Hkv
-    out = torch.zeros(B, Hq, device=q.device)
-    for b in range(B):
-        for h in range(Hkv):
-            Kp = ix.k_perm[b, h, :ix.N_idx].float()                       # [N_idx, d]
-            off = ix.offsets[b, h].to(torch.int64)                        # [m + 1]
-            n = Kp.shape[0]
-            k = min(top, n)
-            if k == 0:
-                out[b, h * G:(h + 1) * G] = 1.0
-                continue
-            # cluster of every row: offsets are ascending, empty clusters repeat a value
-            row_cluster = torch.searchsorted(off, torch.arange(n, device=q.device), right=True) - 1
-            for g in range(G):
-                hq = h * G + g
-                scores = Kp @ q[b, hq].float()
-                best = torch.topk(scores, k).indices
-                ids = sel[b, hq].to(torch.int64)
-                chosen = torch.zeros(ix.m + 1, dtype=torch.bool, device=q.device)
-                chosen[ids[ids >= 0]] = True
-                out[b, hq] = chosen[row_cluster[best]].float().mean()
-    return out

@@ -228,6 +228,39 @@ def test_product_path_does_not_touch_the_oracle():
                 assert "wave_oracle" not in text and "import oracle" not in text and "from oracle" not in text, f
 
 
+def test_bench_touches_the_oracle_only_in_its_cpu_baseline_leg():
+    """bench.py may import the oracle (or the test helpers that import it) only inside
+    cpu_baseline(): everything timed or reported for the GPU path runs without it."""
+    import ast
+    tree = ast.parse(open(os.path.join(ROOT, "bench.py")).read())
+
+    def names_oracle(node):
+        if isinstance(node, ast.Import):
+            return any(a.name.split(".")[0] in ("oracle", "tests") for a in node.names)
+        if isinstance(node, ast.ImportFrom):
+            return (node.module or "").split(".")[0] in ("oracle", "tests")
+        return False
+
+    inside = set()
+    for fn in ast.walk(tree):
+        if isinstance(fn, ast.FunctionDef) and fn.name == "cpu_baseline":
+            inside = {id(n) for n in ast.walk(fn)}
+    assert inside, "bench.py has no cpu_baseline()"
+    hits = [n for n in ast.walk(tree) if names_oracle(n)]
+    assert hits and all(id(n) in inside for n in hits), [n.lineno for n in hits if id(n) not in inside]
+    text = open(os.path.join(ROOT, "bench.py")).read()
+    assert text.count("wave_oracle") == 1
+
+
+def test_workload_retrieve_count_matches_the_oracle():
+    from oracle import wave_oracle as wo
+    from paper_2505_02922_amd import synth
+    for wl in synth.WORKLOADS.values():
+        for m in (1, 37, 256, 2048, 4096, 7680, 8192, 65536):
+            want = wl.retrieve_abs if wl.retrieve_abs is not None else wo.retrieve_count(wl.retrieve_frac, m)
+            assert wl.retrieve_count(m) == want
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

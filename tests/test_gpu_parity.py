@@ -456,7 +456,8 @@ def test_recall_measurement_matches_oracle():
     r = pu.retrieve_count(wl)
     _, _, sel = wb.wave_attention_decode(q.cuda(), ix, r, want_selected=True)
     torch.cuda.synchronize()
-    rec = pu.recall_at_gpu(q.cuda(), ix, sel, wl.Hq, top=100).cpu().numpy()
+    import bench
+    rec = bench.recall_at_gpu(q.cuda(), ix, sel, wl.Hq, top=100).cpu().numpy()
     qn = q.double().numpy()
     for b in range(wl.B):
         for hq in range(wl.Hq):

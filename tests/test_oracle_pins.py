@@ -113,6 +113,12 @@ def test_plan_ragged_and_degenerate():
     p = wo.make_plan(122880, 4, 1024, 8192, 512)
     assert (p.S, p.seg_len[-1], p.m) == (15, 7164, 7680)
     assert wo.retrieve_count(0.018, p.m) == 138
+    # nearest, not floor: 2 % of 4096 clusters is 81.92 -> 82; the paper's own 150 of 8192 is
+    # 1.83 % and 1.8 % of 8192 is 147.456 -> 147; halves go up (0.5 -> 1)
+    assert wo.retrieve_count(0.02, 4096) == 82
+    assert wo.retrieve_count(0.018, 8192) == 147
+    assert wo.retrieve_count(0.01, 65536) == 655 and wo.retrieve_count(0.5, 1) == 1
+    assert wo.retrieve_count(0.0, 100) == 0 and wo.retrieve_count(1.0, 100) == 100
     p = wo.make_plan(50, 4, 64, 2048, 128)       # N <= p: nothing to index
     assert p.m == 0 and p.N_idx == 0 and p.steady_positions.tolist() == list(range(50))
     p = wo.make_plan(100, 4, 64, 2048, 128)      # one short segment, k capped by its length
