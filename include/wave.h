@@ -188,6 +188,28 @@ wave_status wave_attention_decode(const void *q, const wave_index *ix, int Hq, i
                                   int32_t *selected, void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
+/* wave_attention_decode for callers that cannot allocate device memory or hand a
+ * workspace over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and kernels as
+ * wave_attention_decode, without the workspace: the step's scratch (scores,
+ * selected ids, partial results) lives in a static device array of
+ * WAVE_STATIC_SCRATCH_BYTES inside the library, which every GPU the library
+ * runs on holds from the first call on it until the process ends.  The call
+ * allocates and frees nothing.  A step whose scratch would not fit (the size is
+ * what wave_index_plan reports as decode_workspace_bytes) is refused with
+ * WAVE_ERR_WORKSPACE before anything is launched; the five benchmark workloads
+ * fit (the largest, 64 sequences x 28 query heads x 4096 clusters, needs 47 MB).
+ * All calls on one GPU share the one array: calls that overlap in time on the
+ * same GPU (two streams, two threads) race; order them on one stream or by
+ * events.  Nothing in the array has to be zero when a step starts, so nothing is
+ * cleared between calls.  wave_attention_decode_static_capacity returns
+ * WAVE_STATIC_SCRATCH_BYTES. */
+#define WAVE_STATIC_SCRATCH_BYTES (64u << 20)
+size_t wave_attention_decode_static_capacity(void);
+wave_status wave_attention_decode_static(const void *q, const wave_index *ix, int Hq,
+                                         int topk_clusters, int n_sink, int n_local, float *out,
+                                         float *lse, int32_t *selected, void *hip_stream);
+
 /* The decode step with a budget for the estimation zone, as in the paper's
  * evaluation (parameter paragraph: an estimation zone of 23.2 % of the clusters
  * so that the three zones cover about a quarter of the context) and its

@@ -22,7 +22,8 @@ BUFFER_NAMES = ("centroids", "vsum", "sizes", "offsets", "perm", "k_perm", "v_pe
 STATUS_NAMES = {0: "WAVE_OK", 1: "WAVE_ERR_ARG", 2: "WAVE_ERR_SHAPE", 3: "WAVE_ERR_DTYPE",
                 4: "WAVE_ERR_WORKSPACE", 5: "WAVE_ERR_STEADY_MISMATCH", 6: "WAVE_ERR_HIP"}
 EXPORTS = ("wave_index_plan", "wave_index_build", "wave_index_append_plan", "wave_index_append",
-           "wave_attention_decode",
+           "wave_attention_decode", "wave_attention_decode_static_capacity",
+           "wave_attention_decode_static",
            "wave_attention_decode_budget_workspace", "wave_attention_decode_budget",
            "wave_full_attention_workspace", "wave_full_attention_decode", "wave_init_indices",
            "wave_kmeans_assign_step", "wave_calibration_copy", "wave_calibration_read",
@@ -74,6 +75,9 @@ def lib() -> ctypes.CDLL:
                                         u64, ctypes.POINTER(wave_index), vp, sz, vp]
         L.wave_attention_decode.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32, vp,
                                             vp, vp, vp, sz, vp]
+        L.wave_attention_decode_static_capacity.argtypes = []
+        L.wave_attention_decode_static.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32,
+                                                   vp, vp, vp, vp]
         L.wave_attention_decode_budget_workspace.argtypes = [ctypes.POINTER(wave_index), i32, i32, i32]
         L.wave_attention_decode_budget.argtypes = [vp, ctypes.POINTER(wave_index), i32, i32, i32, i32,
                                                    i32, vp, vp, vp, vp, sz, vp]
@@ -93,6 +97,7 @@ def lib() -> ctypes.CDLL:
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = i32
         L.wave_full_attention_workspace.restype = sz
+        L.wave_attention_decode_static_capacity.restype = sz
         L.wave_attention_decode_budget_workspace.restype = sz
         _lib = L
     return _lib
@@ -293,6 +298,27 @@ def wave_attention_decode(q: torch.Tensor, ix: Index, topk_clusters: int, n_sink
                                      ws.data_ptr(), ws.numel(), _stream())
     if st != 0:
         raise WaveError(st, "wave_attention_decode")
+    return out, lse, selected
+
+
+def wave_attention_decode_static_capacity() -> int:
+    return int(lib().wave_attention_decode_static_capacity())
+
+
+def wave_attention_decode_static(q: torch.Tensor, ix: Index, topk_clusters: int, out: torch.Tensor,
+                                 lse: torch.Tensor, selected: Optional[torch.Tensor] = None):
+    """wave_attention_decode without a workspace (the library's static scratch array): the
+    caller passes every buffer, nothing is allocated here or in the library."""
+    assert q.is_cuda and q.dtype == ix.dtype and q.is_contiguous()
+    B, Hq, d = q.shape
+    assert out.shape == (B, Hq, d) and out.dtype == torch.float32 and out.is_contiguous()
+    assert lse.shape == (B, Hq) and lse.dtype == torch.float32 and lse.is_contiguous()
+    st = lib().wave_attention_decode_static(
+        q.data_ptr(), ctypes.byref(ix.c), Hq, topk_clusters, ix.n_sink, ix.n_local, out.data_ptr(),
+        lse.data_ptr(), selected.data_ptr() if selected is not None and topk_clusters > 0 else None,
+        _stream())
+    if st != 0:
+        raise WaveError(st, "wave_attention_decode_static")
     return out, lse, selected
 
 

@@ -4,6 +4,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "wave_common.h"
 
 namespace wave {
@@ -367,6 +370,66 @@ wave_status wave_attention_decode(const void* q, const wave_index* ix, int Hq, i
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total)
     return WAVE_ERR_WORKSPACE;
   return launch_decode(q, *ix, Hq, topk_clusters, out, lse, selected, workspace,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+// ----------------------------------------------------------------------------
+// Decode without a caller workspace: the scratch memory is a static device array.
+// Every GPU the library runs on holds its own copy at its own address, found once
+// per device with hipGetSymbolAddress; after that only that address is used (the
+// array's name is a host-side stand-in, not a device address).
+// ----------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)WAVE_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// The device-side address of `scratch` on the current device (nullptr on error).
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  void* addr = nullptr;
+  if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) return nullptr;
+  if (reinterpret_cast<uintptr_t>(addr) & 255u) return nullptr;
+  g_scratch_ptr[dev].store(addr, std::memory_order_release);
+  return addr;
+}
+}  // namespace
+
+extern "C" {
+
+size_t wave_attention_decode_static_capacity(void) { return kStaticScratchBytes; }
+
+wave_status wave_attention_decode_static(const void* q, const wave_index* ix, int Hq, int topk_clusters,
+                                         int n_sink, int n_local, float* out, float* lse,
+                                         int32_t* selected, void* hip_stream) {
+  wave_status st = check_dims(ix);
+  if (st != WAVE_OK) return st;
+  if (!q || !out || !lse || topk_clusters < 0) return WAVE_ERR_ARG;
+  if (!aligned16(q)) return WAVE_ERR_ARG;
+  if (Hq < ix->Hkv || Hq % ix->Hkv != 0 || Hq / ix->Hkv > 8) return WAVE_ERR_SHAPE;
+  if (!planned_fields_match(*ix)) return WAVE_ERR_SHAPE;
+  if (n_sink != ix->n_sink || n_local != ix->n_local) return WAVE_ERR_STEADY_MISMATCH;
+  st = check_index_buffers(*ix);
+  if (st != WAVE_OK) return st;
+  // The step's scratch layout is the one of wave_attention_decode; a step that needs more
+  // than the static array holds is refused here, before anything is launched.
+  const DecodeGeom g = decode_geometry(*ix, Hq, topk_clusters);
+  if (g.total > kStaticScratchBytes) return WAVE_ERR_WORKSPACE;
+  void* ws = static_scratch();
+  if (!ws) return WAVE_ERR_HIP;
+  return launch_decode(q, *ix, Hq, topk_clusters, out, lse, selected, ws,
                        static_cast<hipStream_t>(hip_stream));
 }
 

@@ -187,6 +187,19 @@ def test_entry_points_refuse_bad_arguments_on_the_host():
     assert dec(8, 4, 4, 64, dws - 1) == 4
     # a larger topk needs a larger workspace than the one planned for topk = 4
     assert dec(8, 60, 4, 64, dws) == 4
+    # the entry point with the static scratch array: same checks, and a step that does not fit
+    sdec = lambda Hq, topk, ns, nl: L.wave_attention_decode_static(fake, ctypes.byref(c), Hq, topk, ns, nl,
+                                                                   fake, fake, None, None)
+    assert sdec(8, 4, 4, 65) == 5 and sdec(7, 4, 4, 64) == 2 and sdec(8, -1, 4, 64) == 1
+    assert L.wave_attention_decode_static(None, ctypes.byref(c), 8, 4, 4, 64, fake, fake, None, None) == 1
+    assert L.wave_attention_decode_static_capacity() == 64 << 20
+    cb, _, _, dwb = wb.wave_index_plan(torch.bfloat16, 64, 8, 128, 8192 * 32 + 1028, 4, 1024, 8192, 512,
+                                       Hq=32, topk_clusters=100)
+    assert dwb > 64 << 20
+    for name in wb.BUFFER_NAMES:
+        setattr(cb, name, 0x1000)
+    assert L.wave_attention_decode_static(fake, ctypes.byref(cb), 32, 100, 4, 1024, fake, fake, None,
+                                          None) == 4
     # full attention: workspace size formula, bad shapes, small workspace
     need = L.wave_full_attention_workspace(2, 8, 5000, 128)
     assert need >= 4 * 2 * 8 * 5 * 130 and need % 256 == 0
