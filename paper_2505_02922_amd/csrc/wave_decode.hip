@@ -16,6 +16,20 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 
+// Phase timestamps for tuning (builds with -DWAVE_TRACE only): thread 0 of a selecting
+// workgroup writes the 100 MHz wall clock into the head's selection bitmap words, which the
+// filtered selection does not otherwise use.
+#ifdef WAVE_TRACE
+#define WAVE_STAMP(buf, k)                                                                  \
+  do {                                                                                      \
+    if (threadIdx.x == 0) reinterpret_cast<unsigned long long*>(buf)[k] = wall_clock64();   \
+  } while (0)
+#else
+#define WAVE_STAMP(buf, k) \
+  do {                     \
+  } while (0)
+#endif
+
 // ============================================================================
 // 1. Meta-index pass: one workgroup takes DENSE_ROWS clusters of one unit for
 //    all G query heads of that KV head and makes a single trip over their
@@ -266,8 +280,8 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
     float mx = lds.red[0][g];
 #pragma unroll
     for (int w = 1; w < NWV; ++w) mx = fmaxf(mx, lds.red[w][g]);
-    zmax[g] = mx > -INFINITY ? mx : 0.f;   // a range of empty clusters only: every weight is 0
-    if (threadIdx.x == 0) lds.zref_s[g] = zmax[g];
+    if (threadIdx.x == 0) lds.zref_s[g] = mx;   // -inf: a range of empty clusters only
+    zmax[g] = mx > -INFINITY ? mx : 0.f;          // (every weight is 0 then)
     const float ref2 = zmax[g] * scale_log2;
     float ls = 0.f;
     for (int i = threadIdx.x; i < nrows; i += NT) {
@@ -338,7 +352,7 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
     const int g = idx / STR, e = idx - g * STR;
     float v = 0.f;
     if (e == 0) {
-      v = lds.zref_s[g] * scale_log2;
+      v = lds.zref_s[g] > -INFINITY ? lds.zref_s[g] * scale_log2 : kNegBig;  // no cluster: an empty partial
     } else if (e == 1) {
 #pragma unroll
       for (int w = 0; w < NWV; ++w) v += lds.red[w][G + g];
@@ -523,7 +537,7 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
   for (int e = threadIdx.x; e < STR; e += NT) {
     float v;
     if (e == 0) {
-      v = ref2;
+      v = nsel > 0 ? ref2 : kNegBig;  // nothing selected: an empty partial
     } else {
       v = 0.f;
 #pragma unroll
@@ -537,16 +551,15 @@ __device__ __forceinline__ void negative_partial(const T* __restrict__ vsum_u,
 // threads per query head, the scores re-read from memory in every pass (radix
 // select, 4 passes of 8 bits, on the integer keys).
 template <typename T, int D, int NT>
-__global__ __launch_bounds__(NT) void select_kernel(
+__device__ __forceinline__ void select_streaming(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
-    float* __restrict__ part, int slots, int neg_slot) {
+    float* __restrict__ part, int slots, int neg_slot, int bh /* b * Hq + hq */, int write_neg = 1) {
   constexpr int NW = NT / 64;
-  const int bh = blockIdx.x;  // b * Hq + hq
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
   const int unit = b * Hkv + hq / G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -803,10 +816,25 @@ __global__ __launch_bounds__(NT) void select_kernel(
       nsel_out[bh] = min(nsel, rcap);
     }
     __syncthreads();  // ids[] complete
-    negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, min(nsel, rcap),
-                               nvalid > 0 ? zmax : 0.f, scale_log2,
-                               part + ((size_t)bh * slots + neg_slot) * (D + 2));
+    if (write_neg)
+      negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, min(nsel, rcap),
+                                 nvalid > 0 ? zmax : 0.f, scale_log2,
+                                 part + ((size_t)bh * slots + neg_slot) * (D + 2));
   }
+}
+
+template <typename T, int D, int NT>
+__global__ __launch_bounds__(NT) void select_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    int32_t* __restrict__ nsel_out,
+    int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
+    float* __restrict__ part, int slots, int neg_slot) {
+  select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                             usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
+                             vsum, scale_log2, part, slots, neg_slot, blockIdx.x);
 }
 
 // ----------------------------------------------------------------------------
@@ -836,7 +864,10 @@ struct SelView {
   int ids_only;        // 1: a slice (ids and scores to ids_ptr / z_out); 2: the head's list and count,
                        // nothing after them (the retrieval kernel derives the rest)
   int32_t* ids_ptr;
-  float* z_out;        // ids_only: the scores of the listed ids, -inf padded like the ids
+  float* z_out;        // the scores of the listed ids (ids_only: -inf padded like the ids)
+  int32_t* s_ids = nullptr;  // LDS copy of the first stage_cap selected ids (saves reading them back)
+  int no_neg = 0;      // 1: the caller's retrieval launch takes the selected clusters' estimation
+                       // terms out again; no partial is written for them here
 };
 
 template <typename T, int D, int NT, int VPT, bool LDSK>
@@ -874,6 +905,9 @@ __device__ __forceinline__ int select_core(
   __shared__ float sh_f[2];
   static_assert(SEL_BINS * sizeof(int) <= CAND_CAP * sizeof(double), "the histogram borrows cand_z");
   int* hist = reinterpret_cast<int*>(cand_z);  // free until the candidates are re-scored
+  uint32_t* trace = bitmap + (size_t)bh * mwords;
+  (void)trace;
+  WAVE_STAMP(trace, 10);
 
   // ---- this thread's scores as order-preserving integer keys -------------------
   // Error bound inputs first, so that their loads overlap with the key loads:
@@ -991,6 +1025,7 @@ __device__ __forceinline__ int select_core(
   const float zmax = key_to_float(kmax);
   const float guard = sh_f[0];
   const int r_eff = min(r, nvalid);
+  WAVE_STAMP(trace, 11);
 
   // mode 0: nothing selected; 1: every valid cluster; 2: threshold + exact band; 3: fp32 rule
   int mode;
@@ -1148,6 +1183,7 @@ __device__ __forceinline__ int select_core(
       cnt_hi = sh_i[1];
     }
       ktau = klo;
+    WAVE_STAMP(trace, 12);
     const float tau = key_to_float(ktau);
     need_eq = r_eff - cnt_hi;  // count(key > tau) = count(key >= khi) = cnt_hi
     hi = tau + guard;
@@ -1217,6 +1253,7 @@ __device__ __forceinline__ int select_core(
   }
 
   // ---- which of this thread's clusters are selected ------------------------------
+  WAVE_STAMP(trace, 13);
   // bit k of `sel`; mode 3 needs the rank among equal scores in id order.
   uint64_t sel = 0;
   if (mode == 1) {
@@ -1274,6 +1311,7 @@ __device__ __forceinline__ int select_core(
       ids[pos] = c;
       if (usel) usel[pos] = c;
       if (LDSK && view.z_out) view.z_out[pos] = key_to_float(ky);  // the key is the score, bit for bit
+      if (view.s_ids && pos < stage_cap) view.s_ids[pos] = c;
     }
   });
   nsel = min(nsel, rcap);
@@ -1291,6 +1329,7 @@ __device__ __forceinline__ int select_core(
     return nsel;
   }
   __syncthreads();  // ids[] written by other waves are read below
+  WAVE_STAMP(trace, 14);
 
   // ---- first row and running token count of every selected cluster -------------------
   int carry = 0;
@@ -1298,7 +1337,9 @@ __device__ __forceinline__ int select_core(
     const int t = base + tid;
     int r0 = 0, size = 0;
     if (t < nsel) {
-      const int c = ids[t];
+      int c;
+      if (view.s_ids && nsel <= stage_cap) c = view.s_ids[t];
+      else c = ids[t];
       r0 = off[c];
       size = off[c + 1] - r0;
       srow[t] = r0;
@@ -1321,8 +1362,11 @@ __device__ __forceinline__ int select_core(
     nsel_out[bh] = nsel;
   }
   __syncthreads();
-  negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
-                             scale_log2, part + ((size_t)bh * slots + neg_slot) * (D + 2));
+  WAVE_STAMP(trace, 15);
+  if (!view.no_neg)
+    negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
+                               scale_log2, part + ((size_t)bh * slots + neg_slot) * (D + 2));
+  WAVE_STAMP(trace, 16);
   *ntok_out = carry;
   return nsel;
 }
@@ -1526,7 +1570,11 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
 // ============================================================================
 // All NT threads of the workgroup must call this (it contains barriers).  Thread
 // t owns output dimension t % D and every (NT / D)-th partial result.
-// p: the head's `slots` partial results (max, sum, acc[D]).
+// p: the head's `slots` partial results (max, sum, acc[D]).  A partial without any
+// term carries max = kNegBig (weight 0 below); a partial's sum may be zero or
+// negative (the selected clusters' estimation terms are taken out with a minus
+// sign, and may cancel a range's exact terms to the last bit), so the sum says
+// nothing about whether a partial counts.
 // WIDE (the stand-alone merge launch, many slots): (max, sum) pairs as single
 // unconditional loads kept in registers, eight accumulation loads in flight.
 template <int D, int NT, bool WIDE = false>
@@ -1535,23 +1583,22 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
   constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
   static_assert(NT % D == 0 && NT >= D, "whole slot groups");
   const int tid = threadIdx.x, e = tid % D, sg = tid / D;
-  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M), 0 for empty slots
+  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M)
   __shared__ float red[NWV];
   __shared__ float accs[NSG * D];
-  // global maximum over the non-empty slots; (max, sum) of a slot arrive as one
-  // unconditional 8-byte load (a load under a lane condition would be waited for
-  // on its own), and the first NT slots' pairs stay in registers for the weights
+  // global maximum over the slots; (max, sum) of a slot arrive as one unconditional
+  // 8-byte load (a load under a lane condition would be waited for on its own), and
+  // the first NT slots' pairs stay in registers for the weights
   float mloc = kNegBig;
   float2 first = make_float2(kNegBig, 0.f);
   if constexpr (WIDE) {
     for (int s = tid; s < slots; s += NT) {
       const float2 ml = *reinterpret_cast<const float2*>(p + (size_t)s * STR);
       if (s == tid) first = ml;
-      if (ml.y != 0.f) mloc = fmaxf(mloc, ml.x);
+      mloc = fmaxf(mloc, ml.x);
     }
   } else {
-    for (int s = tid; s < slots; s += NT)
-      if (p[(size_t)s * STR + 1] != 0.f) mloc = fmaxf(mloc, p[(size_t)s * STR]);
+    for (int s = tid; s < slots; s += NT) mloc = fmaxf(mloc, p[(size_t)s * STR]);
   }
   mloc = wave_max(mloc);
   if ((tid & 63) == 0) red[tid >> 6] = mloc;
@@ -1568,10 +1615,10 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
       if constexpr (WIDE) {
         ml = base + s == tid ? first : *reinterpret_cast<const float2*>(p + (size_t)(base + s) * STR);
       } else {
+        ml.x = p[(size_t)(base + s) * STR];
         ml.y = p[(size_t)(base + s) * STR + 1];
-        ml.x = ml.y != 0.f ? p[(size_t)(base + s) * STR] : M;
       }
-      const float w = ml.y != 0.f ? exp2f(ml.x - M) : 0.f;
+      const float w = ml.x > 0.5f * kNegBig ? exp2f(ml.x - M) : 0.f;  // (M may itself be kNegBig)
       wgt[s] = w;
       zloc = fmaf(ml.y, w, zloc);
     }
@@ -1621,8 +1668,13 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
     for (int w = 0; w < NWV; ++w) Z += red[w];
 #pragma unroll
     for (int g = 0; g < NSG; ++g) A += accs[g * D + e];
-    out_head[e] = Z > 0.f ? A / Z : 0.f;
-    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
+    // Z > 0 for every index whose stored centroids are the means of their stored rows (the
+    // estimation bound: a selected cluster's term never exceeds its rows' exact terms).  An
+    // index that breaks this can cancel the normaliser away: that is reported as NaN, not
+    // as a silent zero.
+    const float bad = __uint_as_float(0x7fc00000u);
+    out_head[e] = Z > 0.f ? A / Z : bad;
+    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : bad;
   }
 }
 
@@ -2373,6 +2425,458 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
                          slots, reinterpret_cast<char*>(dyn_keys));
 }
 
+// ----------------------------------------------------------------------------
+// Few heads over many clusters (16384 < m <= FILT_NT * FILT_MAX_SWEEPS) in three
+// launches and a merge:
+//   1. scores of all clusters (with the largest score of every run of SCORE_TILE
+//      clusters) and, as extra workgroups, the steady zone;
+//   2. one workgroup per head selects; beside them, workgroups that do not depend
+//      on the selection stream the value sums of ALL clusters (estimation terms),
+//      so the memory system is busy while the selection's chain of short
+//      dependent steps runs;
+//   3. the selected clusters' tokens, cut into equal token ranges per workgroup.
+// Selection of a head, one workgroup: the table of tile maxima gives a lower
+// bound T of the head's r-th largest score (at least r maxima reach T, so r
+// different clusters score at least T): one histogram sweep over m / 16 values
+// and a scan.  With the fp32 error bound `guard`, every cluster the exact ranking
+// could select scores at least T - guard.  One sweep over the head's scores
+// counts those clusters per (sweep, wave), a second lists them in ascending
+// order in LDS (about 1.1 r on clustered data), and the exact ranking
+// (select_core: fp64 re-scoring inside the guard band, ties to the lower id) runs
+// on that list.  The workgroup then leaves everything the retrieval launch
+// needs: ids, first rows, running token counts, the first cluster of every token
+// range, and the selected clusters' estimation terms with a minus sign.  When no
+// bound exists (fewer than r tiles) or more than FILT_CAP clusters pass (many
+// equal scores), the head is ranked by the streaming selection instead.
+// ----------------------------------------------------------------------------
+constexpr int FILT_NT = 512;
+constexpr int FILT_CAP = 2048;         // clusters that pass the filter, kept in LDS
+constexpr int FILT_VPT = FILT_CAP / FILT_NT;
+constexpr int FILT_MAX_SWEEPS = 256;   // of FILT_NT scores each
+// LDS of the selecting role: ids and scores of the clusters that pass, the bitmap of all
+// clusters (whose space the histogram uses before it and the exact ranking's keys after it),
+// then the selected ids
+constexpr size_t FILT_LDS = sizeof(int) * (3 * (size_t)FILT_CAP + (size_t)FILT_MAX_SWEEPS * FILT_NT / 32);
+// largest r the filtered selection is used for: about 1.1 r clusters pass on clustered data
+inline int filtered_max_r() { return (FILT_CAP - 64) * 4 / 5; }
+
+template <typename T, int D, int NT>
+__device__ __forceinline__ void select_filtered(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
+    float scale_log2, float* __restrict__ part, int slots, int neg_slot, int bh,
+    const float* __restrict__ tile_max, int32_t* __restrict__ chunk_first, int gather_chunks,
+    char* dyn) {
+  constexpr int NW = NT / 64;
+  static_assert(NT == FILT_NT, "LDS layout");
+  static_assert(SEL_BINS * sizeof(int) <= FILT_CAP * sizeof(int), "the histogram borrows the key region");
+  static_assert(FILT_MAX_SWEEPS * NT / 32 >= FILT_CAP, "the exact ranking's keys use the bitmap's space");
+  constexpr uint32_t kKeyNegInf = 0x007fffffu;  // order_key(-inf)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = bh / Hq, hq = bh - b * Hq;
+  const int unit = b * Hkv + hq / (Hq / Hkv);
+  const float* zz = z + (size_t)bh * m;
+  const int ntile = (m + SCORE_TILE - 1) / SCORE_TILE;
+  const float* tm = tile_max + (size_t)bh * ntile;
+  int* cand_id = reinterpret_cast<int*>(dyn);
+  float* cand_z = reinterpret_cast<float*>(dyn) + FILT_CAP;
+  uint32_t* skeys = reinterpret_cast<uint32_t*>(dyn) + 2 * FILT_CAP;
+  int* f_hist = reinterpret_cast<int*>(skeys);            // free until the exact ranking loads its keys
+  uint32_t* fbits = reinterpret_cast<uint32_t*>(dyn) + 2 * FILT_CAP;  // bitmap of the clusters that pass
+  int32_t* s_ids = reinterpret_cast<int32_t*>(dyn) + 2 * FILT_CAP + FILT_MAX_SWEEPS * NT / 32;
+  __shared__ int f_scan[NW];
+  __shared__ int f_sh[4];
+  __shared__ float f_shf[2];
+  uint32_t* trace = bitmap + (size_t)bh * mwords;
+  (void)trace;
+  WAVE_STAMP(trace, 0);
+
+  // |q|^2 and max |C|^2 (error bound; bound of every score): loads first, reduced later
+  static_assert(D <= 128, "two query elements per lane");
+  float gq[2] = {0.f, 0.f}, gc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (wave == NW - 1) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = to_f32(q[(size_t)bh * D + min(lane + 64 * j, D - 1)]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) gc[j] = cn2part[(size_t)unit * cn2_chunks + min(lane + 64 * j, cn2_chunks - 1)];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) gq[j] = lane + 64 * j < D ? gq[j] : 0.f;
+  }
+  // the head's tile maxima stay in registers: first for the histogram, then to pick the tiles
+  // that can hold a cluster at or above the bound
+  constexpr int TMV = FILT_MAX_SWEEPS * NT / SCORE_TILE / NT;  // tile maxima per thread at the largest m
+  float tmv[TMV];
+#pragma unroll
+  for (int u = 0; u < TMV; ++u) tmv[u] = tm[min(u * NT + tid, ntile - 1)];
+  if (wave == NW - 1) {
+    float qn2 = gq[0] * gq[0] + gq[1] * gq[1];
+    float c2 = fmaxf(fmaxf(gc[0], gc[1]), fmaxf(gc[2], gc[3]));
+    for (int i = lane + 256; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
+    qn2 = wave_sum_f(qn2);
+    c2 = wave_max(c2);
+    const float qc = sqrtf(qn2) * sqrtf(c2);
+    if (lane == 0) {
+      f_shf[0] = 2.0f * 48.f * 5.9604645e-8f * qc;  // as in the exact ranking
+      f_shf[1] = qc * 1.001f;
+    }
+  }
+  for (int i = tid; i < SEL_BINS; i += NT) f_hist[i] = 0;
+  if (tid == 0) f_sh[1] = 0;
+  __syncthreads();
+  const float guard = f_shf[0];
+  const uint32_t top16 = order_key(f_shf[1] + 0.0f) >> 16;
+  const uint32_t lo16 = top16 >= (uint32_t)(SEL_BINS - 1) ? top16 - (SEL_BINS - 1) : 0u;
+  uint32_t tkey[TMV];
+#pragma unroll
+  for (int u = 0; u < TMV; ++u) {
+    tkey[u] = order_key((u * NT + tid < ntile ? tmv[u] : -INFINITY) + 0.0f);
+    if (tkey[u] > kKeyNegInf) {
+      uint32_t b16 = tkey[u] >> 16;
+      b16 = b16 > top16 ? top16 : b16;  // cannot happen for finite inputs; keeps the index in range
+      atomicAdd(&f_hist[b16 > lo16 ? b16 - lo16 : 0u], 1);
+    }
+  }
+  __syncthreads();
+  constexpr int PER = SEL_BINS / NT;
+  static_assert(PER >= 1 && PER * NT == SEL_BINS, "bins per thread");
+  int hmine[PER], hsum = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    hmine[j] = f_hist[SEL_BINS - 1 - (tid * PER + j)];  // thread 0 holds the top bins
+    hsum += hmine[j];
+  }
+  if (tid == 0) f_sh[0] = -1;
+  int htot;
+  int above = block_excl_scan<NT>(hsum, f_scan, htot);  // its barriers order the store to f_sh[0] first
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    if (above < r && above + hmine[j] >= r) f_sh[0] = SEL_BINS - 1 - (tid * PER + j);  // at most one (thread, j)
+    above += hmine[j];
+  }
+  __syncthreads();
+  const int bsel = f_sh[0];
+  WAVE_STAMP(trace, 1);
+  uint32_t kt = kKeyNegInf + 1u;  // no bound: every non-empty cluster passes
+  if (bsel > 0) {
+    const float t_edge = key_to_float((lo16 + (uint32_t)bsel) << 16);
+    kt = order_key((t_edge - guard) + 0.0f);
+    kt = kt > kKeyNegInf + 3u ? kt - 2u : kKeyNegInf + 1u;  // two ulps for the rounding of the subtraction
+  }
+
+  // Tiles whose maximum reaches the bound (only they hold clusters at or above it), as an
+  // unordered list in LDS; their scores then set bits in a bitmap of all clusters, which
+  // yields the passing clusters in ascending order.  More than FILT_CAP tiles pass only if
+  // more than FILT_CAP clusters do.
+  constexpr int BM_WORDS = FILT_MAX_SWEEPS * NT / 32, BM_PER = BM_WORDS / NT;
+  int* tile_list = cand_id;  // free until the passing clusters are listed
+  for (int i = tid; i < BM_WORDS; i += NT) fbits[i] = 0u;  // (the histogram, in the same space, is dead)
+#pragma unroll
+  for (int u = 0; u < TMV; ++u)
+    if (tkey[u] >= kt) {
+      const int slot = atomicAdd(&f_sh[1], 1);
+      if (slot < FILT_CAP) tile_list[slot] = u * NT + tid;
+    }
+  __syncthreads();
+  const int ntl = f_sh[1];
+  const bool aligned = (m & 3) == 0;  // then every head's scores start at a 16-byte boundary
+  if (ntl <= FILT_CAP) {
+    constexpr int TB = 2;  // tiles in flight per thread
+    for (int e0 = 0; e0 < ntl; e0 += TB * NT) {
+      float sc[TB][SCORE_TILE];
+      int t16[TB];
+#pragma unroll
+      for (int u = 0; u < TB; ++u) {
+        t16[u] = SCORE_TILE * tile_list[min(e0 + u * NT + tid, ntl - 1)];
+        if (aligned) {
+#pragma unroll
+          for (int j4 = 0; j4 < SCORE_TILE / 4; ++j4) {
+            // (the last tile of a head may be short: m is a multiple of 4, so whole float4s)
+            const float4 v = *reinterpret_cast<const float4*>(zz + min(t16[u] + 4 * j4, m - 4));
+            sc[u][4 * j4] = v.x; sc[u][4 * j4 + 1] = v.y; sc[u][4 * j4 + 2] = v.z; sc[u][4 * j4 + 3] = v.w;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < SCORE_TILE; ++j) sc[u][j] = zz[min(t16[u] + j, m - 1)];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < TB; ++u)
+        if (e0 + u * NT + tid < ntl) {
+#pragma unroll
+          for (int j = 0; j < SCORE_TILE; ++j) {
+            const int i = t16[u] + j;
+            if (i < m && order_key(sc[u][j] + 0.0f) >= kt) atomicOr(&fbits[i >> 5], 1u << (i & 31));
+          }
+        }
+    }
+  }
+  __syncthreads();
+  uint32_t words[BM_PER];
+  int tsum = 0;
+#pragma unroll
+  for (int j = 0; j < BM_PER; ++j) {
+    words[j] = fbits[BM_PER * tid + j];
+    tsum += __popc(words[j]);
+  }
+  int cnt;
+  int tbase = block_excl_scan<NT>(tsum, f_scan, cnt);
+  if (ntl > FILT_CAP) cnt = FILT_CAP + 1;  // too many tiles pass: ranked by the streaming selection
+  WAVE_STAMP(trace, 2);
+
+  int nsel, ntok;
+  int* s_pref = reinterpret_cast<int*>(cand_z);  // both lists are dead once the ids are out
+  int* s_row = reinterpret_cast<int*>(skeys);
+  if (cnt <= FILT_CAP) {
+#pragma unroll
+    for (int j = 0; j < BM_PER; ++j) {
+      uint32_t w = words[j];
+      while (w) {
+        const int bit = __ffs(w) - 1;
+        w &= w - 1;
+        cand_id[tbase++] = 32 * (BM_PER * tid + j) + bit;
+      }
+    }
+    __syncthreads();  // (also: every thread has read its bitmap words; the key region is free)
+    {
+      float v[FILT_VPT];
+#pragma unroll
+      for (int u = 0; u < FILT_VPT; ++u) v[u] = zz[cnt > 0 ? cand_id[min(u * NT + tid, cnt - 1)] : 0];
+#pragma unroll
+      for (int u = 0; u < FILT_VPT; ++u)
+        if (u * NT + tid < cnt) cand_z[u * NT + tid] = v[u] + 0.0f;
+    }
+    __syncthreads();
+    WAVE_STAMP(trace, 3);
+    nsel = select_core<T, D, NT, FILT_VPT, true>(
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
+        sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys,
+        s_pref, s_row, FILT_CAP - 1, &ntok,
+        SelView{cnt, 0, cand_id, cand_z, 0, nullptr, nullptr, s_ids, 1});
+    __syncthreads();
+    WAVE_STAMP(trace, 4);
+  } else {
+    select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                               usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
+                               vsum, scale_log2, part, slots, neg_slot, bh, 0);
+    __syncthreads();
+    const int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
+    nsel = nsel_out[bh];
+    for (int i = tid; i <= nsel && i < FILT_CAP; i += NT) s_pref[i] = pref[i];
+    ntok = pref[nsel];
+    __syncthreads();
+  }
+  // token ranges of the retrieval launch: range c starts at token c * ceil(ntok / chunks),
+  // which lies in cluster chunk_first[c] of the head's list (the last entry holds ntok)
+  int32_t* cf = chunk_first + (size_t)bh * (gather_chunks + 2);
+  const int ct = (ntok + gather_chunks - 1) / gather_chunks;
+  for (int c = tid; c <= gather_chunks; c += NT) {
+    const long long t = (long long)c * ct;
+    int a = 0, e = nsel;  // largest a in [0, nsel) with s_pref[a] <= t
+    while (e - a > 1) {
+      const int mid = (a + e) >> 1;
+      if (s_pref[mid] <= t) a = mid; else e = mid;
+    }
+    cf[c] = a;
+  }
+  if (tid == 0) cf[gather_chunks + 1] = ntok;
+  WAVE_STAMP(trace, 5);
+}
+
+template <typename T, int D, int G, int NT>
+__global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void select_estimate_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
+    float scale_log2, float* __restrict__ part, int slots, int neg_slot,
+    const float* __restrict__ tile_max, int32_t* __restrict__ chunk_first, int gather_chunks,
+    int n_select_wgs, const SideWork sw) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];
+  if ((int)blockIdx.x < n_select_wgs) {
+    select_filtered<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                              usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
+                              vsum, scale_log2, part, slots, neg_slot, blockIdx.x, tile_max, chunk_first,
+                              gather_chunks, reinterpret_cast<char*>(dyn_keys));
+    return;
+  }
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+                         slots, reinterpret_cast<char*>(dyn_keys));
+}
+
+// The scores with the steady-zone pieces as extra workgroups.
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void score_steady_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ sizes,
+    float* __restrict__ z, float* __restrict__ cn2part, int Hkv, int m, int chunks,
+    float* __restrict__ tile_max, int n_score_wgs, const T* __restrict__ k_steady,
+    const T* __restrict__ v_steady, int p, int p_stride, int steady_chunks, int steady_rows, int slots,
+    int steady_slot0, float scale_log2, float* __restrict__ part) {
+  using Lds = DenseLds<T, D, G, 256>;
+  constexpr size_t kSteadyBytes = sizeof(float) * 4 * G * (D + 2);
+  __shared__ __attribute__((aligned(16))) char
+      lds_raw[Lds::score_bytes > kSteadyBytes ? Lds::score_bytes : kSteadyBytes];
+  const int Hq = Hkv * G;
+  if ((int)blockIdx.x < n_score_wgs) {
+    const Lds lds(lds_raw);
+    const int wg = xcd_logical_block(blockIdx.x, n_score_wgs);
+    const int unit = wg / chunks, chunk = wg - unit * chunks;
+    const int b = unit / Hkv, h = unit - b * Hkv;
+    const int bh0 = b * Hq + h * G;
+    const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
+    dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
+                                     sizeof(T) == 2 ? tile_max : nullptr);
+    __syncthreads();
+    if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
+    if (sizeof(T) != 2) {  // (the bf16 pass writes the tile maxima tile by tile)
+      constexpr int TPC = DENSE_ROWS / SCORE_TILE, ZG = Lds::ZG;
+      static_assert(TPC * G <= 256, "one thread per (tile, head)");
+      const int t = threadIdx.x % TPC, g = threadIdx.x / TPC;
+      if (g < G && SCORE_TILE * t < nrows) {
+        float mx = -INFINITY;
+        for (int j = SCORE_TILE * t; j < min(SCORE_TILE * (t + 1), nrows); ++j) mx = fmaxf(mx, lds.zw[j * ZG + g]);
+        const int ntile = (m + SCORE_TILE - 1) / SCORE_TILE;
+        tile_max[(size_t)(bh0 + g) * ntile + chunk * TPC + t] = mx;
+      }
+    }
+    return;
+  }
+  const int wg = (int)blockIdx.x - n_score_wgs;
+  const int unit = wg / steady_chunks, chunk = wg - unit * steady_chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv;
+  const int bh0 = b * Hq + h * G;
+  const int r0 = chunk * steady_rows, r1 = min(p, r0 + steady_rows);
+  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p_stride, r0, r1, scale_log2,
+                                    reinterpret_cast<float*>(lds_raw),
+                                    part + ((size_t)bh0 * slots + steady_slot0 + chunk) * (D + 2),
+                                    (size_t)slots * (D + 2));
+}
+
+// Retrieval zone from the lists the selecting workgroup left: workgroup `chunk`
+// of a head attends tokens [chunk * ct, (chunk + 1) * ct) of the head's selected
+// tokens (ct = ceil(ntok / chunks)), which lie in clusters chunk_first[chunk] ..
+// chunk_first[chunk + 1] of the head's list.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_rows_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
+    const int32_t* __restrict__ sel_pref, const int32_t* __restrict__ sel_row,
+    const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ chunk_first,
+    const float* __restrict__ z, const T* __restrict__ vsum, int Hq, int Hkv,
+    int N_idx /* rows per unit */, int m, int rcap, int chunks, int slots, float scale_log2,
+    float* __restrict__ part) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int bh = wg / chunks, chunk = wg - bh * chunks;
+  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+  const int unit = b * Hkv + hq / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  __shared__ int rowidx[GATHER_TILE];
+  __shared__ int cl_pref[GATHER_TILE + 1];
+  __shared__ int cl_row[GATHER_TILE];
+  __shared__ int cl_id[GATHER_TILE];
+  __shared__ float smem[4 * (D + 2)];
+
+  const int32_t* cf = chunk_first + (size_t)bh * (chunks + 2);
+  const int a0 = cf[chunk], a1 = cf[chunk + 1], ntok = cf[chunks + 1];
+  const int ct = (ntok + chunks - 1) / chunks;
+  const long long t0l = (long long)chunk * ct;
+  const int t0 = t0l < ntok ? (int)t0l : ntok, t1 = min(t0 + ct, ntok);
+  const int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
+  const int32_t* srow = sel_row + (size_t)bh * rcap;
+  const int32_t* ids = sel_ids + (size_t)bh * rcap;
+  const float* zz = z + (size_t)bh * m;
+
+  AttnState<T, D, 1> st;
+  st.init(q + (size_t)bh * D, sub, scale_log2);
+  const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
+  const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
+  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+  const int nc_all = t0 < t1 ? a1 - a0 + 1 : 0;
+  for (int cb = 0; cb < nc_all; cb += GATHER_TILE) {
+    const int nc = min(GATHER_TILE, nc_all - cb);
+    __syncthreads();  // the previous pass is done with the tables
+    {
+      const int i = min((int)threadIdx.x, nc);  // entry nc is the end of the pass's last cluster
+      const int pv = pref[a0 + cb + i];
+      const int rv = srow[a0 + cb + min((int)threadIdx.x, nc - 1)];
+      const int iv = ids[a0 + cb + min((int)threadIdx.x, nc - 1)];
+      if ((int)threadIdx.x <= nc) cl_pref[i] = pv;
+      if ((int)threadIdx.x < nc) {
+        cl_row[threadIdx.x] = rv;
+        cl_id[threadIdx.x] = iv;
+      }
+    }
+    __syncthreads();
+    // The estimation pass added a term for every cluster; the selected ones are attended
+    // exactly, so the clusters that START in this token range have theirs taken out again
+    // (every selected cluster starts in exactly one range).  The first GROUPS * U clusters'
+    // value sums are requested here, before the rows stream, and used after it.
+    uint4 nraw[U];
+    float nsc[1][U], nmult[U];
+    auto neg_load = [&](int i0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int ii = i0 + u * GROUPS;
+        const int j = ii < nc ? ii : nc - 1;
+        const int id = cl_id[j];
+        const int ps = cl_pref[j];
+        nraw[u] = load16(VSu + (size_t)id * D);
+        nsc[0][u] = zz[id];
+        nmult[u] = (float)(cl_pref[j + 1] - ps);
+        if (!(ii < nc && ps >= t0 && ps < t1)) nmult[u] = -1.f;  // not this range's: marked, masked below
+      }
+    };
+    auto neg_apply = [&]() {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        nsc[0][u] = nmult[u] >= 0.f ? nsc[0][u] * scale_log2 : -INFINITY;
+        nmult[u] = fmaxf(nmult[u], 0.f);
+      }
+      st.template rows_given<U, true>(nsc, nmult, nraw);
+    };
+    neg_load(grp);
+    const int lo = max(t0, cl_pref[0]), hi = min(t1, cl_pref[nc]);
+    for (int base = lo; base < hi; base += GATHER_TILE) {
+      const int n = min(GATHER_TILE, hi - base);
+      __syncthreads();
+      if ((int)threadIdx.x < n) {
+        const int t = base + threadIdx.x;
+        int a = 0, e = nc;  // largest a with cl_pref[a] <= t
+        while (e - a > 1) {
+          const int mid = (a + e) >> 1;
+          if (cl_pref[mid] <= t) a = mid; else e = mid;
+        }
+        rowidx[threadIdx.x] = cl_row[a] + (t - cl_pref[a]);
+      }
+      __syncthreads();
+      for (int i = grp; i < n; i += GROUPS * U) {
+        uint4 kraw[U], vraw[U];
+        bool valid[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int ii = i + u * GROUPS;
+          valid[u] = ii < n;
+          const int row = rowidx[valid[u] ? ii : i];
+          kraw[u] = load16_stream(Ku + (size_t)row * D);
+          vraw[u] = load16_stream(Vu + (size_t)row * D);
+        }
+        st.template rows<U, LPR>(kraw, vraw, valid);
+      }
+    }
+    neg_apply();
+    for (int i = grp + GROUPS * U; i < nc; i += GROUPS * U) {
+      neg_load(i);
+      neg_apply();
+    }
+  }
+  __syncthreads();
+  merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
+}
+
 __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -2410,8 +2914,29 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.nslices = (m + g.slice_len - 1) / g.slice_len;
   g.sliced = (!g.fused && r > 0 && m > 16384 && g.nslices <= 64 &&
               (long long)g.nslices * r <= 16384) ? 1 : 0;
+  // Few heads over many clusters and a moderate r: one workgroup per head filters and ranks
+  // beside the estimation ranges (see select_filtered).
+  g.filtered = (!g.fused && r > 0 && m > 16384 && m <= FILT_NT * FILT_MAX_SWEEPS &&
+                r <= filtered_max_r()) ? 1 : 0;
+  if (g.filtered) g.sliced = 0;
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and (see below) the selected clusters' estimation terms with a minus sign
+  if (g.filtered) {
+    // Estimation ranges sized so that their 512-thread workgroups and the selecting ones are
+    // all resident at once (2 per CU up to 4 heads per KV head, else 1, by their registers): a
+    // second round of long-lived workgroups would double the launch.  The staged scores and
+    // sizes of a range, (G + 1) * rows floats, share the selecting role's LDS budget.
+    const int G = Hq / ix.Hkv;
+    int chunks = (256 * (G <= 4 ? 2 : 1) - heads) / units;
+    if (chunks < 1) chunks = 1;
+    int rows = (m + chunks - 1) / chunks;
+    rows = (rows + 63) / 64 * 64;
+    const int rows_max = (int)(FILT_LDS / sizeof(float)) / (G + 1) / 64 * 64;
+    if (rows > rows_max) rows = rows_max;
+    if (rows < 512) rows = 512;
+    g.est_rows = rows;
+    g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
+  }
   if (g.sliced) {
     // The estimation terms come from 512-thread workgroups in the launch that ranks the
     // union of the slices' lists.  A range is sized so that those workgroups and the
@@ -2433,7 +2958,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   // Who takes the selected clusters' estimation terms out again: the retrieval
   // kernel itself (no partial of their own), except after the fused kernel and
   // after the streaming selection, which write them as one more partial.
-  g.neg_in_gather = (m > 0 && !g.fused && (g.sliced || m <= 1024 * 64)) ? 1 : 0;
+  g.neg_in_gather = (m > 0 && !g.fused && (g.filtered || g.sliced || m <= 1024 * 64)) ? 1 : 0;
   g.neg_slots = (m > 0 && !g.neg_in_gather) ? 1 : 0;
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots;
   if (g.slots < 1) g.slots = 1;
@@ -2451,6 +2976,10 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
     g.off_slice_ids = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * g.nslices * r);
     g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * r);
     g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
+  }
+  if (g.filtered) {
+    g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
+    g.off_chunk_first = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * (g.gather_chunks + 2));
   }
   g.total = o;
   return g;
@@ -2477,7 +3006,15 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (m > 0) {
     const int est_slot0 = g.gather_chunks + g.steady_chunks;
     const int neg_slot = est_slot0 + g.est_chunks;  // exists when g.neg_slots is 1
-    if (g.sliced)
+    if (g.filtered)
+      WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>),
+                  units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
+                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
+                  reinterpret_cast<float*>(w + g.off_tile_max), units * g.score_chunks,
+                  static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.p,
+                  steady_stride(ix), g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2,
+                  part);
+    else if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
                   reinterpret_cast<float*>(w + g.off_tile_max));
@@ -2503,6 +3040,20 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   key_lds, st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
                   static_cast<const T*>(ix.v_perm), row_stride(ix), static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 2, out, lse);
+    } else if (g.filtered) {
+      size_t lds = FILT_LDS;
+      const size_t lds_merge = sizeof(float) * (FILT_NT / 64) * G * (D + 2);  // the estimation role's last step
+      if (lds < lds_merge) lds = lds_merge;
+      int32_t* cf = reinterpret_cast<int32_t*>(w + g.off_chunk_first);
+      SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, units * g.est_chunks, ix.k_steady,
+                  ix.v_steady, ix.p, steady_stride(ix), 0, g.steady_rows, g.gather_chunks};
+      WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, FILT_NT>),
+                  heads + units * g.est_chunks, FILT_NT, lds, st, WAVE_SELECT_ARGS,
+                  reinterpret_cast<const float*>(w + g.off_tile_max), cf, g.gather_chunks, heads, sw);
+      WAVE_LAUNCH("gather", (gather_rows_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
+                  static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, cf,
+                  z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
+                  g.gather_chunks, g.slots, scale_log2, part);
     } else {
       if (g.sliced) {
         int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
