@@ -282,15 +282,17 @@ def decode_phase(run: DecodeRun, steps: int, warmup: int, profile_steps: int):
     }
     step_bytes = meta + steady_b + gather_b
     kern = {k: v[0] / max(v[1], 1) for k, v in dec_prof.items()}      # ms per launch
-    dominant = max(kern, key=kern.get)
-    dom_gbs = bytes_k.get(dominant, 0) / (kern[dominant] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
-                "traffic": recorded_traffic(wl.name, dominant),
-                "traffic_source": "recorded rocprofv3 --pmc runs (profiles/traffic.json), quoted only "
-                                  "when taken on the kernel sources present",
-                "bytes_per_launch": int(bytes_k.get(dominant, 0)),
-                "ms_per_launch": round(kern[dominant], 5)}
+    roofline = None
+    if kern:   # (no per-kernel profile was asked for: --profile-steps 0)
+        dominant = max(kern, key=kern.get)
+        dom_gbs = bytes_k.get(dominant, 0) / (kern[dominant] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+                    "traffic": recorded_traffic(wl.name, dominant),
+                    "traffic_source": "recorded rocprofv3 --pmc runs (profiles/traffic.json), quoted "
+                                      "only when taken on the kernel sources present",
+                    "bytes_per_launch": int(bytes_k.get(dominant, 0)),
+                    "ms_per_launch": round(kern[dominant], 5)}
     info = {
         "ms_per_step": round(ms_per_step, 5),
         "steps_per_s": round(1e3 / ms_per_step, 2),

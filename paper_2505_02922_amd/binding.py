@@ -13,7 +13,8 @@ from typing import Dict, List, Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libwave.so")
+# WAVE_LIB names another build of the library (tuning variants); the default is the in-tree one
+LIB_PATH = os.environ.get("WAVE_LIB") or os.path.join(_HERE, "libwave.so")
 
 WAVE_F32, WAVE_BF16 = 0, 1
 WAVE_INDEX_BUFFERS = 9

@@ -469,6 +469,24 @@ __device__ __forceinline__ int block_excl_scan(int v, int* scratch, int& total) 
   return base + inc - v;
 }
 
+// Room for `n` entries per lane in a list whose length is the LDS counter *counter: one
+// atomic per wave (same-address LDS atomics run one after the other), then a prefix over
+// the lanes.  Returns the lane's first position.  All 64 lanes call this.
+__device__ __forceinline__ int wave_excl_scan_alloc(int n, int* counter) {
+  const int lane = threadIdx.x & 63;
+  int inc = n;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(inc, off);
+    if (lane >= off) inc += t;
+  }
+  const int total = __shfl(inc, 63);
+  int base = 0;
+  if (lane == 0 && total > 0) base = atomicAdd(counter, total);
+  base = __shfl(base, 0);
+  return base + inc - n;
+}
+
 template <int NT>
 __device__ __forceinline__ int block_sum_i(int v, int* scratch) {
   int t;
@@ -868,6 +886,7 @@ struct SelView {
   int32_t* s_ids = nullptr;  // LDS copy of the first stage_cap selected ids (saves reading them back)
   int no_neg = 0;      // 1: the caller's retrieval launch takes the selected clusters' estimation
                        // terms out again; no partial is written for them here
+  float guard = -1.f;  // >= 0: the fp32 error bound of a score, already known to the caller
 };
 
 template <typename T, int D, int NT, int VPT, bool LDSK>
@@ -916,7 +935,7 @@ __device__ __forceinline__ int select_core(
   // last wave does not reach the first barrier a memory round trip late)
   static_assert(D <= 128, "two query elements per lane");
   float gq[2] = {0.f, 0.f}, gc[4] = {0.f, 0.f, 0.f, 0.f};
-  if (wave == NW - 1) {
+  if (wave == NW - 1 && view.guard < 0.f) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) gq[j] = to_f32(q[(size_t)bh * D + min(lane + 64 * j, D - 1)]);
 #pragma unroll
@@ -967,8 +986,8 @@ __device__ __forceinline__ int select_core(
         else skeys16[(k0 + u) * NT + tid] = (uint16_t)(ky >> 16);
       }
   }
-  float guard_in = 0.f;
-  if (wave == NW - 1) {
+  float guard_in = view.guard;
+  if (wave == NW - 1 && view.guard < 0.f) {
     float qn2 = gq[0] * gq[0] + gq[1] * gq[1];
     float c2 = fmaxf(fmaxf(gc[0], gc[1]), fmaxf(gc[2], gc[3]));
     for (int i = lane + 256; i < cn2_chunks; i += 64) c2 = fmaxf(c2, cn2part[(size_t)unit * cn2_chunks + i]);
@@ -1569,112 +1588,68 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
 // 4. Merge: one normalisation over the partial results of the three zones.
 // ============================================================================
 // All NT threads of the workgroup must call this (it contains barriers).  Thread
-// t owns output dimension t % D and every (NT / D)-th partial result.
+// t owns output dimension t % D and every (NT / D)-th partial result, which it
+// folds into a running (max, sum, acc) of its own, UB partials per trip to memory
+// (three loads each, all unconditional and in flight together); the NT / D
+// running results then meet in LDS.
 // p: the head's `slots` partial results (max, sum, acc[D]).  A partial without any
-// term carries max = kNegBig (weight 0 below); a partial's sum may be zero or
+// term carries max = kNegBig and is skipped; a partial's sum may be zero or
 // negative (the selected clusters' estimation terms are taken out with a minus
 // sign, and may cancel a range's exact terms to the last bit), so the sum says
 // nothing about whether a partial counts.
-// WIDE (the stand-alone merge launch, many slots): (max, sum) pairs as single
-// unconditional loads kept in registers, eight accumulation loads in flight.
-template <int D, int NT, bool WIDE = false>
+template <int D, int NT, int UB = 4>
 __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
                                            float* __restrict__ out_head, float* __restrict__ lse_head) {
-  constexpr int STR = D + 2, TILE = 256, NSG = NT / D, NWV = NT / 64;
+  constexpr int STR = D + 2, NSG = NT / D;
   static_assert(NT % D == 0 && NT >= D, "whole slot groups");
   const int tid = threadIdx.x, e = tid % D, sg = tid / D;
-  __shared__ float wgt[TILE];  // per slot of the current tile: exp2(m_s - M)
-  __shared__ float red[NWV];
-  __shared__ float accs[NSG * D];
-  // global maximum over the slots; (max, sum) of a slot arrive as one unconditional
-  // 8-byte load (a load under a lane condition would be waited for on its own), and
-  // the first NT slots' pairs stay in registers for the weights
-  float mloc = kNegBig;
-  float2 first = make_float2(kNegBig, 0.f);
-  if constexpr (WIDE) {
-    for (int s = tid; s < slots; s += NT) {
-      const float2 ml = *reinterpret_cast<const float2*>(p + (size_t)s * STR);
-      if (s == tid) first = ml;
-      mloc = fmaxf(mloc, ml.x);
-    }
-  } else {
-    for (int s = tid; s < slots; s += NT) mloc = fmaxf(mloc, p[(size_t)s * STR]);
-  }
-  mloc = wave_max(mloc);
-  if ((tid & 63) == 0) red[tid >> 6] = mloc;
-  __syncthreads();
-  float M = red[0];
+  __shared__ float s_m[NSG], s_z[NSG];
+  __shared__ float s_a[NSG * D];
+  float M = kNegBig, Z = 0.f, A = 0.f;
+  for (int s0 = sg; s0 < slots; s0 += NSG * UB) {
+    float mm[UB], ll[UB], aa[UB];
 #pragma unroll
-  for (int w = 1; w < NWV; ++w) M = fmaxf(M, red[w]);
-  float zloc = 0.f, A0 = 0.f, A1 = 0.f, A2 = 0.f, A3 = 0.f;
-  for (int base = 0; base < slots; base += TILE) {
-    const int n = min(TILE, slots - base);
-    __syncthreads();
-    for (int s = tid; s < n; s += NT) {  // TILE <= NT: at most one slot per thread
-      float2 ml;
-      if constexpr (WIDE) {
-        ml = base + s == tid ? first : *reinterpret_cast<const float2*>(p + (size_t)(base + s) * STR);
-      } else {
-        ml.x = p[(size_t)(base + s) * STR];
-        ml.y = p[(size_t)(base + s) * STR + 1];
+    for (int u = 0; u < UB; ++u) {
+      const float* ps = p + (size_t)min(s0 + u * NSG, slots - 1) * STR;
+      mm[u] = ps[0];
+      ll[u] = ps[1];
+      aa[u] = ps[2 + e];
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      if (s0 + u * NSG < slots && mm[u] > 0.5f * kNegBig) {
+        const float mn = fmaxf(M, mm[u]);
+        const float a = exp2f(M - mn), b = exp2f(mm[u] - mn);  // (M = kNegBig at first: a = 0)
+        Z = fmaf(Z, a, ll[u] * b);
+        A = fmaf(A, a, aa[u] * b);
+        M = mn;
       }
-      const float w = ml.x > 0.5f * kNegBig ? exp2f(ml.x - M) : 0.f;  // (M may itself be kNegBig)
-      wgt[s] = w;
-      zloc = fmaf(ml.y, w, zloc);
-    }
-    __syncthreads();
-    const float* pe = p + (size_t)base * STR + 2 + e;
-    int s = sg;
-    if constexpr (!WIDE) {
-      for (; s + 3 * NSG < n; s += 4 * NSG) {
-        A0 = fmaf(pe[(size_t)(s + 0 * NSG) * STR], wgt[s + 0 * NSG], A0);
-        A1 = fmaf(pe[(size_t)(s + 1 * NSG) * STR], wgt[s + 1 * NSG], A1);
-        A2 = fmaf(pe[(size_t)(s + 2 * NSG) * STR], wgt[s + 2 * NSG], A2);
-        A3 = fmaf(pe[(size_t)(s + 3 * NSG) * STR], wgt[s + 3 * NSG], A3);
-      }
-      for (; s < n; s += NSG) A0 = fmaf(pe[(size_t)s * STR], wgt[s], A0);
-      continue;
-    }
-    for (; s + 7 * NSG < n; s += 8 * NSG) {  // eight independent loads in flight
-      float v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = pe[(size_t)(s + u * NSG) * STR];
-      A0 = fmaf(v[0], wgt[s + 0 * NSG], A0);
-      A1 = fmaf(v[1], wgt[s + 1 * NSG], A1);
-      A2 = fmaf(v[2], wgt[s + 2 * NSG], A2);
-      A3 = fmaf(v[3], wgt[s + 3 * NSG], A3);
-      A0 = fmaf(v[4], wgt[s + 4 * NSG], A0);
-      A1 = fmaf(v[5], wgt[s + 5 * NSG], A1);
-      A2 = fmaf(v[6], wgt[s + 6 * NSG], A2);
-      A3 = fmaf(v[7], wgt[s + 7 * NSG], A3);
-    }
-    {  // the remaining slots, up to seven per thread, again with unconditional loads
-      float v[7];
-#pragma unroll
-      for (int u = 0; u < 7; ++u) v[u] = pe[(size_t)min(s + u * NSG, n - 1) * STR];
-#pragma unroll
-      for (int u = 0; u < 7; ++u)
-        if (s + u * NSG < n) A0 = fmaf(v[u], wgt[s + u * NSG], A0);
     }
   }
-  zloc = wave_sum_f(zloc);
-  __syncthreads();
-  if ((tid & 63) == 0) red[tid >> 6] = zloc;
-  accs[sg * D + e] = (A0 + A1) + (A2 + A3);
+  if (e == 0) {
+    s_m[sg] = M;
+    s_z[sg] = Z;
+  }
+  s_a[sg * D + e] = A;
   __syncthreads();
   if (sg == 0) {
-    float Z = 0.f, A = 0.f;
+    float Mx = s_m[0];
 #pragma unroll
-    for (int w = 0; w < NWV; ++w) Z += red[w];
+    for (int g = 1; g < NSG; ++g) Mx = fmaxf(Mx, s_m[g]);
+    float Zt = 0.f, At = 0.f;
 #pragma unroll
-    for (int g = 0; g < NSG; ++g) A += accs[g * D + e];
-    // Z > 0 for every index whose stored centroids are the means of their stored rows (the
+    for (int g = 0; g < NSG; ++g) {
+      const float w = s_m[g] > 0.5f * kNegBig ? exp2f(s_m[g] - Mx) : 0.f;
+      Zt = fmaf(s_z[g], w, Zt);
+      At = fmaf(s_a[g * D + e], w, At);
+    }
+    // Zt > 0 for every index whose stored centroids are the means of their stored rows (the
     // estimation bound: a selected cluster's term never exceeds its rows' exact terms).  An
     // index that breaks this can cancel the normaliser away: that is reported as NaN, not
     // as a silent zero.
     const float bad = __uint_as_float(0x7fc00000u);
-    out_head[e] = Z > 0.f ? A / Z : bad;
-    if (e == 0) *lse_head = Z > 0.f ? (M + log2f(Z)) * kLn2 : bad;
+    out_head[e] = Zt > 0.f ? At / Zt : bad;
+    if (e == 0) *lse_head = Zt > 0.f ? (Mx + log2f(Zt)) * kLn2 : bad;
   }
 }
 
@@ -1862,8 +1837,8 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(const float* __res
                                                               int slot_stride, float* __restrict__ out,
                                                               float* __restrict__ lse) {
   const int bh = blockIdx.x;  // a head's partials are slot_stride slots apart; the first `slots` count
-  merge_head<D, MERGE_THREADS, true>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
-                               lse + bh);
+  merge_head<D, MERGE_THREADS, 16>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
+                                   lse + bh);
 }
 
 // ----------------------------------------------------------------------------
@@ -1984,7 +1959,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   // this kernel; the exact and the negative partials were just written by this
   // workgroup): normalise here instead of in a separate launch.
   __syncthreads();
-  merge_head<D, NT>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
+  merge_head<D, NT, 8>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
 }
 
 // ============================================================================
@@ -2174,6 +2149,150 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
                                    scale_log2, reinterpret_cast<float*>(lds_raw),
                                    part + ((size_t)bh0 * slots + sw.steady_slot0 + chunk) * (D + 2),
                                    (size_t)slots * (D + 2));
+}
+
+// Estimation terms of one range of sw.est_rows clusters of a unit for its G heads, from
+// the scores an earlier launch left in z: the range's scores and sizes are staged in LDS
+// with coalesced loads, turned into weights relative to the range's largest score (and
+// the sum of size x weight), and the value sums then stream through with the weights read
+// from LDS, the next pass's rows already in flight.  One partial per head.
+template <typename T, int D, int G, int NT>
+__device__ __forceinline__ void estimate_range(int wg, const SideWork& sw, const float* __restrict__ z,
+                                               const T* __restrict__ vsum, int Hq, int Hkv, int m,
+                                               float scale_log2, float* __restrict__ part, int slots,
+                                               char* lds_raw) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
+  constexpr int GROUPS = NWV * RPW, U = 4, ZG = (G + 3) / 4 * 4, STR = D + 2;
+  wg = xcd_logical_block(wg, sw.n_est_wgs) + sw.est_first;
+  const int unit = wg / sw.est_chunks, chunk = wg - unit * sw.est_chunks;
+  const int b = unit / Hkv, h = unit - b * Hkv;
+  const int bh0 = b * Hq + h * G;
+  const int c0 = chunk * sw.est_rows, nrows = min(sw.est_rows, m - c0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
+  float* zw = reinterpret_cast<float*>(lds_raw);   // [est_rows][ZG]: scores in base-2 units, then weights
+  float* ms = zw + (size_t)sw.est_rows * ZG;        // [est_rows]: the size as a float
+  float* smem = zw;                                 // the last step reuses the space
+  __shared__ float red[NWV][2 * G];
+  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+  auto load_rows = [&](int i, uint4 (&dst)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) dst[u] = load16_stream(Vu + (size_t)min(i + u * GROUPS, nrows - 1) * D);
+  };
+  uint4 vnext[U];
+  load_rows(grp, vnext);  // (grp may lie beyond a short range: the clamped rows get weight 0)
+  float mx[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) mx[g] = -INFINITY;
+  for (int i = tid; i < nrows; i += NT) {
+    float zv[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) zv[g] = z[(size_t)(bh0 + g) * m + c0 + i];
+    const int sz = sw.sizes[(size_t)unit * m + c0 + i];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float v = zv[g] * scale_log2;  // -inf for an empty cluster
+      zw[i * ZG + g] = v;
+      mx[g] = fmaxf(mx[g], v);
+    }
+    ms[i] = (float)sz;
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mx[g] = wave_max(mx[g]);
+    if (lane == 0) red[wave][g] = mx[g];
+  }
+  __syncthreads();
+  float ref[G], ls[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float v = red[0][g];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) v = fmaxf(v, red[w][g]);
+    mx[g] = v;
+    ref[g] = v > -INFINITY ? v : 0.f;  // a range of empty clusters only: every weight is 0
+    ls[g] = 0.f;
+  }
+  for (int i = tid; i < nrows; i += NT) {  // the entries this thread wrote itself
+    const float sz = ms[i];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float w = exp2f(zw[i * ZG + g] - ref[g]);  // exp2(-inf) = 0
+      zw[i * ZG + g] = w;
+      ls[g] = fmaf(sz, w, ls[g]);
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    ls[g] = wave_sum_f(ls[g]);
+    if (lane == 0) red[wave][G + g] = ls[g];
+  }
+  __syncthreads();
+  float acc[G][EPC];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[g][e] = 0.f;
+  for (int i = grp; i < nrows; i += GROUPS * U) {
+    uint4 vraw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) vraw[u] = vnext[u];
+    if (i + GROUPS * U < nrows) load_rows(i + GROUPS * U, vnext);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ii = i + u * GROUPS;
+      const int row = min(ii, nrows - 1);
+      float w[ZG], vf[EPC];
+#pragma unroll
+      for (int g4 = 0; g4 < ZG; g4 += 4) {
+        const float4 t = *reinterpret_cast<const float4*>(&zw[row * ZG + g4]);
+        w[g4] = t.x; w[g4 + 1] = t.y; w[g4 + 2] = t.z; w[g4 + 3] = t.w;
+      }
+      unpack<T>(vraw[u], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float wg_ = ii < nrows ? w[g] : 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(wg_, vf[e], acc[g][e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[g][e] += __shfl_xor(acc[g][e], off);
+    }
+  }
+  __syncthreads();  // the weights are read no more: their space takes the waves' sums
+  if (lane < LPR) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float* dst = smem + (size_t)(wave * G + g) * STR;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) dst[2 + sub * EPC + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  float* part_head0 = part + ((size_t)bh0 * slots + sw.est_slot0 + chunk) * STR;
+  for (int idx = tid; idx < G * STR; idx += NT) {
+    const int g = idx / STR, e = idx - g * STR;
+    float v = 0.f;
+    if (e == 0) {
+      float mxg = red[0][g];
+#pragma unroll
+      for (int w = 1; w < NWV; ++w) mxg = fmaxf(mxg, red[w][g]);
+      v = mxg > -INFINITY ? mxg : kNegBig;  // no cluster: an empty partial
+    } else if (e == 1) {
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) v += red[w][G + g];
+    } else {
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) v += smem[(size_t)(w * G + g) * STR + e];
+    }
+    part_head0[(size_t)g * slots * STR + e] = v;
+  }
 }
 
 // ----------------------------------------------------------------------------
@@ -2455,8 +2574,9 @@ constexpr int FILT_VPT = FILT_CAP / FILT_NT;
 constexpr int FILT_MAX_SWEEPS = 256;   // of FILT_NT scores each
 // LDS of the selecting role: ids and scores of the clusters that pass, the bitmap of all
 // clusters (whose space the histogram uses before it and the exact ranking's keys after it),
-// then the selected ids
-constexpr size_t FILT_LDS = sizeof(int) * (3 * (size_t)FILT_CAP + (size_t)FILT_MAX_SWEEPS * FILT_NT / 32);
+// the selected ids (before them: the passing clusters in the order they were found), and
+// the scores that go with that unordered list
+constexpr size_t FILT_LDS = sizeof(int) * (4 * (size_t)FILT_CAP + (size_t)FILT_MAX_SWEEPS * FILT_NT / 32);
 // largest r the filtered selection is used for: about 1.1 r clusters pass on clustered data
 inline int filtered_max_r() { return (FILT_CAP - 64) * 4 / 5; }
 
@@ -2487,6 +2607,8 @@ __device__ __forceinline__ void select_filtered(
   int* f_hist = reinterpret_cast<int*>(skeys);            // free until the exact ranking loads its keys
   uint32_t* fbits = reinterpret_cast<uint32_t*>(dyn) + 2 * FILT_CAP;  // bitmap of the clusters that pass
   int32_t* s_ids = reinterpret_cast<int32_t*>(dyn) + 2 * FILT_CAP + FILT_MAX_SWEEPS * NT / 32;
+  int32_t* uid = s_ids;                                  // passing clusters as found (unordered) ...
+  float* uz = reinterpret_cast<float*>(s_ids + FILT_CAP);  // ... and their scores
   __shared__ int f_scan[NW];
   __shared__ int f_sh[4];
   __shared__ float f_shf[2];
@@ -2524,7 +2646,7 @@ __device__ __forceinline__ void select_filtered(
     }
   }
   for (int i = tid; i < SEL_BINS; i += NT) f_hist[i] = 0;
-  if (tid == 0) f_sh[1] = 0;
+  if (tid == 0) f_sh[1] = f_sh[2] = 0;
   __syncthreads();
   const float guard = f_shf[0];
   const uint32_t top16 = order_key(f_shf[1] + 0.0f) >> 16;
@@ -2573,13 +2695,21 @@ __device__ __forceinline__ void select_filtered(
   constexpr int BM_WORDS = FILT_MAX_SWEEPS * NT / 32, BM_PER = BM_WORDS / NT;
   int* tile_list = cand_id;  // free until the passing clusters are listed
   for (int i = tid; i < BM_WORDS; i += NT) fbits[i] = 0u;  // (the histogram, in the same space, is dead)
+  {
+    // (one LDS atomic per wave: hundreds of atomics on one address would run one after the other)
+    int nmine = 0;
 #pragma unroll
-  for (int u = 0; u < TMV; ++u)
-    if (tkey[u] >= kt) {
-      const int slot = atomicAdd(&f_sh[1], 1);
-      if (slot < FILT_CAP) tile_list[slot] = u * NT + tid;
-    }
+    for (int u = 0; u < TMV; ++u) nmine += tkey[u] >= kt ? 1 : 0;
+    int base = wave_excl_scan_alloc(nmine, &f_sh[1]);
+#pragma unroll
+    for (int u = 0; u < TMV; ++u)
+      if (tkey[u] >= kt) {
+        if (base < FILT_CAP) tile_list[base] = u * NT + tid;
+        ++base;
+      }
+  }
   __syncthreads();
+  WAVE_STAMP(trace, 6);
   const int ntl = f_sh[1];
   const bool aligned = (m & 3) == 0;  // then every head's scores start at a 16-byte boundary
   if (ntl <= FILT_CAP) {
@@ -2602,18 +2732,36 @@ __device__ __forceinline__ void select_filtered(
           for (int j = 0; j < SCORE_TILE; ++j) sc[u][j] = zz[min(t16[u] + j, m - 1)];
         }
       }
+      uint32_t pm[TB];  // bit j: score j of tile u passes
+      int nmine = 0;
 #pragma unroll
-      for (int u = 0; u < TB; ++u)
+      for (int u = 0; u < TB; ++u) {
+        pm[u] = 0u;
         if (e0 + u * NT + tid < ntl) {
 #pragma unroll
-          for (int j = 0; j < SCORE_TILE; ++j) {
-            const int i = t16[u] + j;
-            if (i < m && order_key(sc[u][j] + 0.0f) >= kt) atomicOr(&fbits[i >> 5], 1u << (i & 31));
-          }
+          for (int j = 0; j < SCORE_TILE; ++j)
+            if (t16[u] + j < m && order_key(sc[u][j] + 0.0f) >= kt) pm[u] |= 1u << j;
         }
+        nmine += __popc(pm[u]);
+      }
+      int slot = wave_excl_scan_alloc(nmine, &f_sh[2]);
+#pragma unroll
+      for (int u = 0; u < TB; ++u)
+#pragma unroll
+        for (int j = 0; j < SCORE_TILE; ++j)
+          if ((pm[u] >> j) & 1u) {
+            const int i = t16[u] + j;
+            atomicOr(&fbits[i >> 5], 1u << (i & 31));
+            if (slot < FILT_CAP) {
+              uid[slot] = i;
+              uz[slot] = sc[u][j] + 0.0f;
+            }
+            ++slot;
+          }
     }
   }
   __syncthreads();
+  WAVE_STAMP(trace, 7);
   uint32_t words[BM_PER];
   int tsum = 0;
 #pragma unroll
@@ -2640,13 +2788,15 @@ __device__ __forceinline__ void select_filtered(
       }
     }
     __syncthreads();  // (also: every thread has read its bitmap words; the key region is free)
-    {
-      float v[FILT_VPT];
-#pragma unroll
-      for (int u = 0; u < FILT_VPT; ++u) v[u] = zz[cnt > 0 ? cand_id[min(u * NT + tid, cnt - 1)] : 0];
-#pragma unroll
-      for (int u = 0; u < FILT_VPT; ++u)
-        if (u * NT + tid < cnt) cand_z[u * NT + tid] = v[u] + 0.0f;
+    // the scores were seen when the bits were set: each finds its place in the ordered list
+    for (int u = tid; u < cnt; u += NT) {
+      const int id = uid[u];
+      int a = 0, e = cnt;  // the position of id in cand_id[0, cnt)
+      while (e - a > 1) {
+        const int mid = (a + e) >> 1;
+        if (cand_id[mid] <= id) a = mid; else e = mid;
+      }
+      cand_z[a] = uz[u];
     }
     __syncthreads();
     WAVE_STAMP(trace, 3);
@@ -2654,7 +2804,7 @@ __device__ __forceinline__ void select_filtered(
         q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
         sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys,
         s_pref, s_row, FILT_CAP - 1, &ntok,
-        SelView{cnt, 0, cand_id, cand_z, 0, nullptr, nullptr, s_ids, 1});
+        SelView{cnt, 0, cand_id, cand_z, 0, nullptr, nullptr, s_ids, 1, guard});
     __syncthreads();
     WAVE_STAMP(trace, 4);
   } else {
@@ -2703,13 +2853,21 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void select_estimate_kernel(
                               gather_chunks, reinterpret_cast<char*>(dyn_keys));
     return;
   }
-  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
-                         slots, reinterpret_cast<char*>(dyn_keys));
+#ifdef WAVE_TRACE
+  const int te = (int)blockIdx.x - n_select_wgs;
+  uint32_t* tbuf = bitmap + (size_t)(te % n_select_wgs) * mwords;
+  WAVE_STAMP(tbuf, 32 + 2 * (te / n_select_wgs));
+#endif
+  estimate_range<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, z, vsum, Hq, Hkv, m, scale_log2, part,
+                              slots, reinterpret_cast<char*>(dyn_keys));
+#ifdef WAVE_TRACE
+  WAVE_STAMP(tbuf, 33 + 2 * (te / n_select_wgs));
+#endif
 }
 
 // The scores with the steady-zone pieces as extra workgroups.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void score_steady_kernel(
+__global__ __launch_bounds__(256, G <= 4 ? 4 : 2) void score_steady_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ sizes,
     float* __restrict__ z, float* __restrict__ cn2part, int Hkv, int m, int chunks,
     float* __restrict__ tile_max, int n_score_wgs, const T* __restrict__ k_steady,
@@ -2918,7 +3076,12 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   // beside the estimation ranges (see select_filtered).
   g.filtered = (!g.fused && r > 0 && m > 16384 && m <= FILT_NT * FILT_MAX_SWEEPS &&
                 r <= filtered_max_r()) ? 1 : 0;
-  if (g.filtered) g.sliced = 0;
+  if (g.filtered) {
+    g.sliced = 0;
+    // the retrieval workgroups (4 resident per CU) in one round rather than one and a bit
+    if ((long long)heads * g.gather_chunks > 1024 && (long long)heads * g.gather_chunks < 2048 && heads <= 1024)
+      g.gather_chunks = 1024 / heads;
+  }
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and (see below) the selected clusters' estimation terms with a minus sign
   if (g.filtered) {
@@ -2931,7 +3094,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
     if (chunks < 1) chunks = 1;
     int rows = (m + chunks - 1) / chunks;
     rows = (rows + 63) / 64 * 64;
-    const int rows_max = (int)(FILT_LDS / sizeof(float)) / (G + 1) / 64 * 64;
+    const int rows_max = (int)(FILT_LDS / sizeof(float)) / ((G + 3) / 4 * 4 + 1) / 64 * 64;
     if (rows > rows_max) rows = rows_max;
     if (rows < 512) rows = 512;
     g.est_rows = rows;
@@ -3048,10 +3211,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, units * g.est_chunks, ix.k_steady,
                   ix.v_steady, ix.p, steady_stride(ix), 0, g.steady_rows, g.gather_chunks};
       WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, FILT_NT>),
-                  heads + units * g.est_chunks, FILT_NT, lds, st, WAVE_SELECT_ARGS,
+                  heads + sw.n_est_wgs, FILT_NT, lds, st, WAVE_SELECT_ARGS,
                   reinterpret_cast<const float*>(w + g.off_tile_max), cf, g.gather_chunks, heads, sw);
-      WAVE_LAUNCH("gather", (gather_rows_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
-                  static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, cf,
+      WAVE_LAUNCH("gather", (gather_rows_kernel<T, D>), heads * g.gather_chunks, 256, 0, st,
+                  q, static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, cf,
                   z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
                   g.gather_chunks, g.slots, scale_log2, part);
     } else {
