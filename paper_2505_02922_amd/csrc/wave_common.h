@@ -193,9 +193,12 @@ struct DecodeGeom {
   int neg_in_gather, neg_slots;    // selected clusters' estimation terms: taken out by the retrieval kernel / a partial of their own
   int sliced, nslices, slice_len;  // selection cut into slices ranked by workgroups of their own
   int est_with_slices_pct;         // sliced path: share of the estimation work in the slices' launch
-  int filtered;                    // one workgroup per head filters by the tile maxima, then ranks
+  int listed, list_filtered;       // selection launch + retrieval from one work list of token ranges;
+                                   // with more clusters than fit in LDS: filtered by the tile maxima
+  int chunk_tokens, wmain, wtotal, gather_wgs, stage;  // work list: tokens per range, entries, launch size
   size_t off_z, off_cn2, off_sel, off_pref, off_srow, off_bitmap, off_nsel, off_part,
-      off_slice_ids, off_slice_z, off_tile_max, off_chunk_first, total;
+      off_slice_ids, off_slice_z, off_tile_max, off_chunk_first, off_head_info, off_work,
+      off_work_count, off_part_g, total;
 };
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 

@@ -1597,10 +1597,13 @@ __device__ __forceinline__ void merge_groups_and_store(AttnState<T, D, NG>& st, 
 // negative (the selected clusters' estimation terms are taken out with a minus
 // sign, and may cancel a range's exact terms to the last bit), so the sum says
 // nothing about whether a partial counts.
+// p2, n2: a second run of partials that counts after the first (slots n1 .. n1 + n2 - 1).
 template <int D, int NT, int UB = 4>
-__device__ __forceinline__ void merge_head(const float* __restrict__ p, int slots,
-                                           float* __restrict__ out_head, float* __restrict__ lse_head) {
+__device__ __forceinline__ void merge_head(const float* __restrict__ p, int n1,
+                                           float* __restrict__ out_head, float* __restrict__ lse_head,
+                                           const float* __restrict__ p2 = nullptr, int n2 = 0) {
   constexpr int STR = D + 2, NSG = NT / D;
+  const int slots = n1 + n2;
   static_assert(NT % D == 0 && NT >= D, "whole slot groups");
   const int tid = threadIdx.x, e = tid % D, sg = tid / D;
   __shared__ float s_m[NSG], s_z[NSG];
@@ -1610,7 +1613,8 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p, int slot
     float mm[UB], ll[UB], aa[UB];
 #pragma unroll
     for (int u = 0; u < UB; ++u) {
-      const float* ps = p + (size_t)min(s0 + u * NSG, slots - 1) * STR;
+      const int sl = min(s0 + u * NSG, slots - 1);
+      const float* ps = sl < n1 ? p + (size_t)sl * STR : p2 + (size_t)(sl - n1) * STR;
       mm[u] = ps[0];
       ll[u] = ps[1];
       aa[u] = ps[2 + e];
@@ -1876,6 +1880,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
 
+  WAVE_STAMP(bitmap + (size_t)bh * mwords, 20);
   AttnState<T, D, 1> st;
   st.init(q + (size_t)bh * D, sub, scale_log2);
 
@@ -1960,6 +1965,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   // workgroup): normalise here instead of in a separate launch.
   __syncthreads();
   merge_head<D, NT, 8>(part + (size_t)bh * slots * (D + 2), slots, out + (size_t)bh * D, lse + bh);
+  WAVE_STAMP(bitmap + (size_t)bh * mwords, 21);
 }
 
 // ============================================================================
@@ -2156,13 +2162,13 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
 // with coalesced loads, turned into weights relative to the range's largest score (and
 // the sum of size x weight), and the value sums then stream through with the weights read
 // from LDS, the next pass's rows already in flight.  One partial per head.
-template <typename T, int D, int G, int NT>
+template <typename T, int D, int G, int NT, int U = 4>
 __device__ __forceinline__ void estimate_range(int wg, const SideWork& sw, const float* __restrict__ z,
                                                const T* __restrict__ vsum, int Hq, int Hkv, int m,
                                                float scale_log2, float* __restrict__ part, int slots,
                                                char* lds_raw) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
-  constexpr int GROUPS = NWV * RPW, U = 4, ZG = (G + 3) / 4 * 4, STR = D + 2;
+  constexpr int GROUPS = NWV * RPW, ZG = (G + 3) / 4 * 4, STR = D + 2;
   wg = xcd_logical_block(wg, sw.n_est_wgs) + sw.est_first;
   const int unit = wg / sw.est_chunks, chunk = wg - unit * sw.est_chunks;
   const int b = unit / Hkv, h = unit - b * Hkv;
@@ -2545,6 +2551,67 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
 }
 
 // ----------------------------------------------------------------------------
+// What a selecting workgroup leaves for the retrieval launch.  A head's selected
+// tokens (ntok of them, in the order of its ascending cluster list) are cut into
+// nch = ceil(ntok / chunk_tokens) equal token ranges; range c starts at token
+// c * ct (ct = ceil(ntok / nch)), which lies in cluster chunk_first[c] of the
+// head's list.  The ranges of all heads go onto ONE work list (a head's ranges
+// are consecutive entries, claimed with one atomic), so the retrieval launch has
+// as many equal pieces as there are tokens, however unevenly the heads share
+// them (heavy-tailed cluster sizes: one head can hold ten times the mean).
+// The list holds wmain entries plus one spare entry per head: a head that finds
+// the list full takes its spare entry and retrieves as ONE range.  Entries not
+// claimed stay -1 (an earlier launch of the step fills the list and zeroes the
+// counter).  An entry is head * 256 + range.
+// ----------------------------------------------------------------------------
+constexpr int LIST_MAX_CHUNKS = 255;  // ranges per head
+struct ListOut {
+  int32_t* chunk_first;  // [heads][LIST_MAX_CHUNKS + 1]
+  int4* head_info;       // [heads]: first list entry, ranges, tokens per range, tokens
+  int32_t* work;         // [wmain + heads]
+  int32_t* work_count;   // entries claimed so far (may run past wmain)
+  int wmain, chunk_tokens;
+};
+
+// pref: the head's running token counts, nsel + 1 entries (LDS or global).  All
+// NT threads call this.
+template <int NT>
+__device__ __forceinline__ void publish_token_ranges(int bh, int nsel, int ntok, const int* pref,
+                                                     const ListOut& lo) {
+  __shared__ int s_pub[3];
+  if (threadIdx.x == 0) {
+    int nch = ntok > 0 ? min((ntok + lo.chunk_tokens - 1) / lo.chunk_tokens, LIST_MAX_CHUNKS) : 0;
+    int base = 0;
+    if (nch > 0) {
+      base = atomicAdd(lo.work_count, nch);
+      if (base + nch > lo.wmain) {  // the list is full: the head's spare entry, one range
+        base = lo.wmain + bh;
+        nch = 1;
+      }
+    }
+    const int ct = nch > 0 ? (ntok + nch - 1) / nch : 0;
+    s_pub[0] = base;
+    s_pub[1] = nch;
+    s_pub[2] = ct;
+    lo.head_info[bh] = make_int4(base, nch, ct, ntok);
+  }
+  __syncthreads();
+  const int base = s_pub[0], nch = s_pub[1], ct = s_pub[2];
+  int32_t* cf = lo.chunk_first + (size_t)bh * (LIST_MAX_CHUNKS + 1);
+  if (nch == 0) return;
+  for (int c = threadIdx.x; c <= nch; c += NT) {
+    const long long t = (long long)c * ct;
+    int a = 0, e = nsel;  // largest a in [0, nsel) with pref[a] <= t
+    while (e - a > 1) {
+      const int mid = (a + e) >> 1;
+      if (pref[mid] <= t) a = mid; else e = mid;
+    }
+    cf[c] = a;
+    if (c < nch) lo.work[base + c] = bh * 256 + c;
+  }
+}
+
+// ----------------------------------------------------------------------------
 // Few heads over many clusters (16384 < m <= FILT_NT * FILT_MAX_SWEEPS) in three
 // launches and a merge:
 //   1. scores of all clusters (with the largest score of every run of SCORE_TILE
@@ -2588,8 +2655,7 @@ __device__ __forceinline__ void select_filtered(
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
     float scale_log2, float* __restrict__ part, int slots, int neg_slot, int bh,
-    const float* __restrict__ tile_max, int32_t* __restrict__ chunk_first, int gather_chunks,
-    char* dyn) {
+    const float* __restrict__ tile_max, const ListOut lo, char* dyn) {
   constexpr int NW = NT / 64;
   static_assert(NT == FILT_NT, "LDS layout");
   static_assert(SEL_BINS * sizeof(int) <= FILT_CAP * sizeof(int), "the histogram borrows the key region");
@@ -2818,48 +2884,85 @@ __device__ __forceinline__ void select_filtered(
     ntok = pref[nsel];
     __syncthreads();
   }
-  // token ranges of the retrieval launch: range c starts at token c * ceil(ntok / chunks),
-  // which lies in cluster chunk_first[c] of the head's list (the last entry holds ntok)
-  int32_t* cf = chunk_first + (size_t)bh * (gather_chunks + 2);
-  const int ct = (ntok + gather_chunks - 1) / gather_chunks;
-  for (int c = tid; c <= gather_chunks; c += NT) {
-    const long long t = (long long)c * ct;
-    int a = 0, e = nsel;  // largest a in [0, nsel) with s_pref[a] <= t
-    while (e - a > 1) {
-      const int mid = (a + e) >> 1;
-      if (s_pref[mid] <= t) a = mid; else e = mid;
-    }
-    cf[c] = a;
-  }
-  if (tid == 0) cf[gather_chunks + 1] = ntok;
+  publish_token_ranges<NT>(bh, nsel, ntok, s_pref, lo);
   WAVE_STAMP(trace, 5);
 }
 
-template <typename T, int D, int G, int NT>
-__global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void select_estimate_kernel(
+// Selection of a head when its clusters' keys fit in LDS (m <= 16384): the exact ranking on
+// all of them, then the lists for the retrieval launch.  dyn: keys, then the staged running
+// token counts, first rows and ids of up to `stage` selected clusters.
+template <typename T, int D, int NT>
+__device__ __forceinline__ void select_direct(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
+    int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
+    float scale_log2, float* __restrict__ part, int slots, int neg_slot, int bh, int stage,
+    const ListOut lo, char* dyn) {
+  uint32_t* skeys = reinterpret_cast<uint32_t*>(dyn);
+  int* s_pref = reinterpret_cast<int*>(skeys + (size_t)NT * ((m + NT - 1) / NT));
+  int* s_row = s_pref + stage + 1;
+  int32_t* s_ids = s_row + stage;
+  int ntok;
+  const int nsel = select_core<T, D, NT, 16384 / NT, true>(
+      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
+      sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys, s_pref,
+      s_row, stage, &ntok, SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr, s_ids, 1});
+  __syncthreads();
+  // (more selected clusters than are staged: the running token counts are read from memory)
+  const int* pref = nsel < stage ? s_pref : sel_pref + (size_t)bh * (rcap + 1);
+  publish_token_ranges<NT>(bh, nsel, ntok, pref, lo);
+}
+
+constexpr int DIRECT_NT = 256;  // threads of a selecting workgroup when the keys fit in LDS (many heads:
+                                // small workgroups, so that more heads' chains of short steps are in flight)
+inline size_t select_direct_lds(int m, int stage) {
+  return sizeof(uint32_t) * DIRECT_NT * (size_t)((m + DIRECT_NT - 1) / DIRECT_NT) + sizeof(int) * (3 * (size_t)stage + 1);
+}
+
+// One workgroup per head selects (FILTERED: through the tile maxima, for more clusters than
+// fit in LDS); beside them, workgroups that do not depend on the selection take the
+// estimation ranges of all clusters.
+template <typename T, int D, int G, int NT, bool FILTERED>
+__global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_estimate_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
     int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
     float scale_log2, float* __restrict__ part, int slots, int neg_slot,
-    const float* __restrict__ tile_max, int32_t* __restrict__ chunk_first, int gather_chunks,
-    int n_select_wgs, const SideWork sw) {
+    const float* __restrict__ tile_max, const ListOut lo, int stage, int n_select_wgs,
+    const SideWork sw) {
   extern __shared__ __attribute__((aligned(16))) uint32_t dyn_keys[];
-  if ((int)blockIdx.x < n_select_wgs) {
-    select_filtered<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+  // FILTERED (few heads, all workgroups resident at once): the selecting workgroups come
+  // first.  Otherwise the two kinds alternate in proportion, so that at any time some
+  // workgroups stream value sums while others run their selection's short dependent steps.
+  const int total = gridDim.x, b = blockIdx.x;
+  const int sel_before = FILTERED ? min(b, n_select_wgs) : (int)((long long)b * n_select_wgs / total);
+  const bool is_select = FILTERED ? b < n_select_wgs
+                                  : (int)((long long)(b + 1) * n_select_wgs / total) > sel_before;
+  if (is_select) {
+    if constexpr (FILTERED)
+      select_filtered<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+                                usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
+                                vsum, scale_log2, part, slots, neg_slot, sel_before, tile_max, lo,
+                                reinterpret_cast<char*>(dyn_keys));
+    else
+      select_direct<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
                               usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
-                              vsum, scale_log2, part, slots, neg_slot, blockIdx.x, tile_max, chunk_first,
-                              gather_chunks, reinterpret_cast<char*>(dyn_keys));
+                              vsum, scale_log2, part, slots, neg_slot, sel_before, stage, lo,
+                              reinterpret_cast<char*>(dyn_keys));
     return;
   }
 #ifdef WAVE_TRACE
-  const int te = (int)blockIdx.x - n_select_wgs;
+  const int te = b - sel_before;
   uint32_t* tbuf = bitmap + (size_t)(te % n_select_wgs) * mwords;
   WAVE_STAMP(tbuf, 32 + 2 * (te / n_select_wgs));
 #endif
-  estimate_range<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, z, vsum, Hq, Hkv, m, scale_log2, part,
-                              slots, reinterpret_cast<char*>(dyn_keys));
+  // (small workgroups: twice the rows in flight per lane group)
+  estimate_range<T, D, G, NT, (NT <= 256 && G <= 4 ? 8 : 4)>(b - sel_before, sw, z, vsum, Hq, Hkv, m, scale_log2,
+                                                             part, slots, reinterpret_cast<char*>(dyn_keys));
 #ifdef WAVE_TRACE
   WAVE_STAMP(tbuf, 33 + 2 * (te / n_select_wgs));
 #endif
@@ -2867,17 +2970,21 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void select_estimate_kernel(
 
 // The scores with the steady-zone pieces as extra workgroups.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256, G <= 4 ? 4 : 2) void score_steady_kernel(
+__global__ __launch_bounds__(256, 4) void score_steady_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ sizes,
     float* __restrict__ z, float* __restrict__ cn2part, int Hkv, int m, int chunks,
     float* __restrict__ tile_max, int n_score_wgs, const T* __restrict__ k_steady,
     const T* __restrict__ v_steady, int p, int p_stride, int steady_chunks, int steady_rows, int slots,
-    int steady_slot0, float scale_log2, float* __restrict__ part) {
+    int steady_slot0, float scale_log2, float* __restrict__ part, int32_t* __restrict__ work,
+    int32_t* __restrict__ work_count, int wtotal) {
   using Lds = DenseLds<T, D, G, 256>;
   constexpr size_t kSteadyBytes = sizeof(float) * 4 * G * (D + 2);
   __shared__ __attribute__((aligned(16))) char
       lds_raw[Lds::score_bytes > kSteadyBytes ? Lds::score_bytes : kSteadyBytes];
   const int Hq = Hkv * G;
+  // the retrieval work list of this step starts empty (the next launch fills it)
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < wtotal; i += gridDim.x * 256) work[i] = -1;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *work_count = 0;
   if ((int)blockIdx.x < n_score_wgs) {
     const Lds lds(lds_raw);
     const int wg = xcd_logical_block(blockIdx.x, n_score_wgs);
@@ -2889,7 +2996,7 @@ __global__ __launch_bounds__(256, G <= 4 ? 4 : 2) void score_steady_kernel(
                                      sizeof(T) == 2 ? tile_max : nullptr);
     __syncthreads();
     if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
-    if (sizeof(T) != 2) {  // (the bf16 pass writes the tile maxima tile by tile)
+    if (sizeof(T) != 2 && tile_max) {  // (the bf16 pass writes the tile maxima tile by tile)
       constexpr int TPC = DENSE_ROWS / SCORE_TILE, ZG = Lds::ZG;
       static_assert(TPC * G <= 256, "one thread per (tile, head)");
       const int t = threadIdx.x % TPC, g = threadIdx.x / TPC;
@@ -2907,29 +3014,34 @@ __global__ __launch_bounds__(256, G <= 4 ? 4 : 2) void score_steady_kernel(
   const int b = unit / Hkv, h = unit - b * Hkv;
   const int bh0 = b * Hq + h * G;
   const int r0 = chunk * steady_rows, r1 = min(p, r0 + steady_rows);
-  steady_rows_partial<T, D, G, 256>(q, k_steady, v_steady, unit, bh0, p_stride, r0, r1, scale_log2,
-                                    reinterpret_cast<float*>(lds_raw),
-                                    part + ((size_t)bh0 * slots + steady_slot0 + chunk) * (D + 2),
-                                    (size_t)slots * (D + 2));
+  // (more than 4 heads at once would take the registers of the scoring role's occupancy:
+  // the rows are read a second time, from cache, for the heads beyond the fourth)
+  constexpr int G1 = G <= 4 ? G : 4;
+  steady_rows_partial<T, D, G1, 256>(q, k_steady, v_steady, unit, bh0, p_stride, r0, r1, scale_log2,
+                                     reinterpret_cast<float*>(lds_raw),
+                                     part + ((size_t)bh0 * slots + steady_slot0 + chunk) * (D + 2),
+                                     (size_t)slots * (D + 2));
+  if constexpr (G > 4) {
+    __syncthreads();
+    steady_rows_partial<T, D, G - 4, 256>(q, k_steady, v_steady, unit, bh0 + 4, p_stride, r0, r1, scale_log2,
+                                          reinterpret_cast<float*>(lds_raw),
+                                          part + ((size_t)(bh0 + 4) * slots + steady_slot0 + chunk) * (D + 2),
+                                          (size_t)slots * (D + 2));
+  }
 }
 
-// Retrieval zone from the lists the selecting workgroup left: workgroup `chunk`
-// of a head attends tokens [chunk * ct, (chunk + 1) * ct) of the head's selected
-// tokens (ct = ceil(ntok / chunks)), which lie in clusters chunk_first[chunk] ..
-// chunk_first[chunk + 1] of the head's list.
+// Retrieval zone from the work list the selecting workgroups left: a workgroup takes list
+// entry blockIdx.x (and every gridDim.x-th after it): range `c` of head `bh`, tokens
+// [c * ct, (c + 1) * ct) of the head's selected tokens, which lie in clusters
+// chunk_first[c] .. chunk_first[c + 1] of the head's list.  One partial per entry.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_rows_kernel(
+__global__ __launch_bounds__(256) void gather_list_kernel(
     const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
     const int32_t* __restrict__ sel_pref, const int32_t* __restrict__ sel_row,
-    const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ chunk_first,
-    const float* __restrict__ z, const T* __restrict__ vsum, int Hq, int Hkv,
-    int N_idx /* rows per unit */, int m, int rcap, int chunks, int slots, float scale_log2,
-    float* __restrict__ part) {
+    const int32_t* __restrict__ sel_ids, const ListOut lo, int wtotal, const float* __restrict__ z,
+    const T* __restrict__ vsum, int Hq, int Hkv, int N_idx /* rows per unit */, int m, int rcap,
+    float scale_log2, float* __restrict__ part_g) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int bh = wg / chunks, chunk = wg - bh * chunks;
-  const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
-  const int unit = b * Hkv + hq / G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
   __shared__ int rowidx[GATHER_TILE];
@@ -2937,102 +3049,126 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
   __shared__ int cl_row[GATHER_TILE];
   __shared__ int cl_id[GATHER_TILE];
   __shared__ float smem[4 * (D + 2)];
+  const int claimed = *lo.work_count;
+  const int cnt = min(claimed, lo.wmain);
+  // entries [0, cnt), then (only if some head found the list full) the heads' spare entries
+  const int items = cnt + (claimed > lo.wmain ? wtotal - lo.wmain : 0);
+  for (int w = blockIdx.x; w < items; w += gridDim.x) {
+    const int idx = w < cnt ? w : lo.wmain + (w - cnt);
+    const int item = lo.work[idx];
+    if (item < 0) continue;  // (the same for every thread of the workgroup)
+    const int bh = item >> 8, chunk = item & 255;
+    const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
+    const int unit = b * Hkv + hq / G;
+    const int4 info = lo.head_info[bh];
+    const int32_t* cf = lo.chunk_first + (size_t)bh * (LIST_MAX_CHUNKS + 1);
+    const int a0 = cf[chunk], a1 = cf[chunk + 1], ct = info.z, ntok = info.w;
+    const long long t0l = (long long)chunk * ct;
+    const int t0 = t0l < ntok ? (int)t0l : ntok, t1 = min(t0 + ct, ntok);
+    const int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
+    const int32_t* srow = sel_row + (size_t)bh * rcap;
+    const int32_t* ids = sel_ids + (size_t)bh * rcap;
+    const float* zz = z + (size_t)bh * m;
 
-  const int32_t* cf = chunk_first + (size_t)bh * (chunks + 2);
-  const int a0 = cf[chunk], a1 = cf[chunk + 1], ntok = cf[chunks + 1];
-  const int ct = (ntok + chunks - 1) / chunks;
-  const long long t0l = (long long)chunk * ct;
-  const int t0 = t0l < ntok ? (int)t0l : ntok, t1 = min(t0 + ct, ntok);
-  const int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
-  const int32_t* srow = sel_row + (size_t)bh * rcap;
-  const int32_t* ids = sel_ids + (size_t)bh * rcap;
-  const float* zz = z + (size_t)bh * m;
-
-  AttnState<T, D, 1> st;
-  st.init(q + (size_t)bh * D, sub, scale_log2);
-  const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
-  const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
-  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
-  const int nc_all = t0 < t1 ? a1 - a0 + 1 : 0;
-  for (int cb = 0; cb < nc_all; cb += GATHER_TILE) {
-    const int nc = min(GATHER_TILE, nc_all - cb);
-    __syncthreads();  // the previous pass is done with the tables
-    {
-      const int i = min((int)threadIdx.x, nc);  // entry nc is the end of the pass's last cluster
-      const int pv = pref[a0 + cb + i];
-      const int rv = srow[a0 + cb + min((int)threadIdx.x, nc - 1)];
-      const int iv = ids[a0 + cb + min((int)threadIdx.x, nc - 1)];
-      if ((int)threadIdx.x <= nc) cl_pref[i] = pv;
-      if ((int)threadIdx.x < nc) {
-        cl_row[threadIdx.x] = rv;
-        cl_id[threadIdx.x] = iv;
+    AttnState<T, D, 1> st;
+    st.init(q + (size_t)bh * D, sub, scale_log2);
+    const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
+    const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
+    const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+    const int nc_all = t0 < t1 ? a1 - a0 + 1 : 0;
+    for (int cb = 0; cb < nc_all; cb += GATHER_TILE) {
+      const int nc = min(GATHER_TILE, nc_all - cb);
+      __syncthreads();  // the previous pass is done with the tables
+      {
+        const int i = min((int)threadIdx.x, nc);  // entry nc is the end of the pass's last cluster
+        const int pv = pref[a0 + cb + i];
+        const int rv = srow[a0 + cb + min((int)threadIdx.x, nc - 1)];
+        const int iv = ids[a0 + cb + min((int)threadIdx.x, nc - 1)];
+        if ((int)threadIdx.x <= nc) cl_pref[i] = pv;
+        if ((int)threadIdx.x < nc) {
+          cl_row[threadIdx.x] = rv;
+          cl_id[threadIdx.x] = iv;
+        }
+      }
+      __syncthreads();
+      // The estimation pass added a term for every cluster; the selected ones are attended
+      // exactly, so the clusters that START in this token range have theirs taken out again
+      // (every selected cluster starts in exactly one range).  The first GROUPS * U clusters'
+      // value sums are requested here, before the rows stream, and used after it.
+      uint4 nraw[U];
+      float nsc[1][U], nmult[U];
+      auto neg_load = [&](int i0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int ii = i0 + u * GROUPS;
+          const int j = ii < nc ? ii : nc - 1;
+          const int id = cl_id[j];
+          const int ps = cl_pref[j];
+          nraw[u] = load16(VSu + (size_t)id * D);
+          nsc[0][u] = zz[id];
+          nmult[u] = (float)(cl_pref[j + 1] - ps);
+          if (!(ii < nc && ps >= t0 && ps < t1)) nmult[u] = -1.f;  // not this range's: marked, masked below
+        }
+      };
+      auto neg_apply = [&]() {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          nsc[0][u] = nmult[u] >= 0.f ? nsc[0][u] * scale_log2 : -INFINITY;
+          nmult[u] = fmaxf(nmult[u], 0.f);
+        }
+        st.template rows_given<U, true>(nsc, nmult, nraw);
+      };
+      neg_load(grp);
+      const int lo_t = max(t0, cl_pref[0]), hi_t = min(t1, cl_pref[nc]);
+      for (int base = lo_t; base < hi_t; base += GATHER_TILE) {
+        const int n = min(GATHER_TILE, hi_t - base);
+        __syncthreads();
+        if ((int)threadIdx.x < n) {
+          const int t = base + threadIdx.x;
+          int a = 0, e = nc;  // largest a with cl_pref[a] <= t
+          while (e - a > 1) {
+            const int mid = (a + e) >> 1;
+            if (cl_pref[mid] <= t) a = mid; else e = mid;
+          }
+          rowidx[threadIdx.x] = cl_row[a] + (t - cl_pref[a]);
+        }
+        __syncthreads();
+        for (int i = grp; i < n; i += GROUPS * U) {
+          uint4 kraw[U], vraw[U];
+          bool valid[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int ii = i + u * GROUPS;
+            valid[u] = ii < n;
+            const int row = rowidx[valid[u] ? ii : i];
+            kraw[u] = load16_stream(Ku + (size_t)row * D);
+            vraw[u] = load16_stream(Vu + (size_t)row * D);
+          }
+          st.template rows<U, LPR>(kraw, vraw, valid);
+        }
+      }
+      neg_apply();
+      for (int i = grp + GROUPS * U; i < nc; i += GROUPS * U) {
+        neg_load(i);
+        neg_apply();
       }
     }
     __syncthreads();
-    // The estimation pass added a term for every cluster; the selected ones are attended
-    // exactly, so the clusters that START in this token range have theirs taken out again
-    // (every selected cluster starts in exactly one range).  The first GROUPS * U clusters'
-    // value sums are requested here, before the rows stream, and used after it.
-    uint4 nraw[U];
-    float nsc[1][U], nmult[U];
-    auto neg_load = [&](int i0) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int ii = i0 + u * GROUPS;
-        const int j = ii < nc ? ii : nc - 1;
-        const int id = cl_id[j];
-        const int ps = cl_pref[j];
-        nraw[u] = load16(VSu + (size_t)id * D);
-        nsc[0][u] = zz[id];
-        nmult[u] = (float)(cl_pref[j + 1] - ps);
-        if (!(ii < nc && ps >= t0 && ps < t1)) nmult[u] = -1.f;  // not this range's: marked, masked below
-      }
-    };
-    auto neg_apply = [&]() {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        nsc[0][u] = nmult[u] >= 0.f ? nsc[0][u] * scale_log2 : -INFINITY;
-        nmult[u] = fmaxf(nmult[u], 0.f);
-      }
-      st.template rows_given<U, true>(nsc, nmult, nraw);
-    };
-    neg_load(grp);
-    const int lo = max(t0, cl_pref[0]), hi = min(t1, cl_pref[nc]);
-    for (int base = lo; base < hi; base += GATHER_TILE) {
-      const int n = min(GATHER_TILE, hi - base);
-      __syncthreads();
-      if ((int)threadIdx.x < n) {
-        const int t = base + threadIdx.x;
-        int a = 0, e = nc;  // largest a with cl_pref[a] <= t
-        while (e - a > 1) {
-          const int mid = (a + e) >> 1;
-          if (cl_pref[mid] <= t) a = mid; else e = mid;
-        }
-        rowidx[threadIdx.x] = cl_row[a] + (t - cl_pref[a]);
-      }
-      __syncthreads();
-      for (int i = grp; i < n; i += GROUPS * U) {
-        uint4 kraw[U], vraw[U];
-        bool valid[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int ii = i + u * GROUPS;
-          valid[u] = ii < n;
-          const int row = rowidx[valid[u] ? ii : i];
-          kraw[u] = load16_stream(Ku + (size_t)row * D);
-          vraw[u] = load16_stream(Vu + (size_t)row * D);
-        }
-        st.template rows<U, LPR>(kraw, vraw, valid);
-      }
-    }
-    neg_apply();
-    for (int i = grp + GROUPS * U; i < nc; i += GROUPS * U) {
-      neg_load(i);
-      neg_apply();
-    }
+    merge_groups_and_store<T, D, 1>(st, smem, part_g + (size_t)idx * (D + 2), 0);
+    __syncthreads();  // smem and the tables are free for the next entry
   }
-  __syncthreads();
-  merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
+}
+
+// The merge for heads whose retrieval partials sit on the work list: the head's partials of
+// the other zones, then its list entries' partials.
+template <int D, int NT>
+__global__ __launch_bounds__(NT) void merge_list_kernel(
+    const float* __restrict__ part, int slots, int slot_stride, const float* __restrict__ part_g,
+    const int4* __restrict__ head_info, float* __restrict__ out, float* __restrict__ lse) {
+  const int bh = blockIdx.x;
+  const int4 info = head_info[bh];
+  merge_head<D, NT, 16>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D, lse + bh,
+                        part_g + (size_t)info.x * (D + 2), info.y);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
@@ -3072,34 +3208,53 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.nslices = (m + g.slice_len - 1) / g.slice_len;
   g.sliced = (!g.fused && r > 0 && m > 16384 && g.nslices <= 64 &&
               (long long)g.nslices * r <= 16384) ? 1 : 0;
-  // Few heads over many clusters and a moderate r: one workgroup per head filters and ranks
-  // beside the estimation ranges (see select_filtered).
-  g.filtered = (!g.fused && r > 0 && m > 16384 && m <= FILT_NT * FILT_MAX_SWEEPS &&
-                r <= filtered_max_r()) ? 1 : 0;
-  if (g.filtered) {
+  // Selection in one launch (one workgroup per head, beside the estimation ranges of all
+  // clusters), retrieval in the next from ONE work list of equal token ranges over all heads:
+  // with many heads whose clusters' keys fit in LDS, or with few heads over many clusters and
+  // a moderate r (filtered through the tile maxima, see select_filtered).
+  g.list_filtered = (r > 0 && m > 16384 && m <= FILT_NT * FILT_MAX_SWEEPS && r <= filtered_max_r()) ? 1 : 0;
+  // (up to about three heads per CU the fused kernel below, one workgroup per head with all
+  // of them resident at once, is faster; beyond that, or with uneven heads, its tail is long)
+  g.listed = (g.list_filtered || (m > 0 && r > 0 && heads > 768 && m <= 512 * 32)) ? 1 : 0;
+  if (g.listed) {
+    g.fused = 0;
     g.sliced = 0;
-    // the retrieval workgroups (4 resident per CU) in one round rather than one and a bit
-    if ((long long)heads * g.gather_chunks > 1024 && (long long)heads * g.gather_chunks < 2048 && heads <= 1024)
-      g.gather_chunks = 1024 / heads;
+    g.gather_chunks = 0;  // the retrieval partials are the work list's, not per-head slots
+    g.steady_chunks = ix.p > 0 ? (ix.p + g.steady_rows - 1) / g.steady_rows : 0;
+    const int G = Hq / ix.Hkv;
+    if (g.list_filtered) {
+      // Estimation ranges sized so that their 512-thread workgroups and the selecting ones are
+      // all resident at once (2 per CU up to 4 heads per KV head, else 1, by their registers): a
+      // second round of long-lived workgroups would double the launch.  The staged scores and
+      // sizes of a range, (ZG + 1) * rows floats, share the selecting role's LDS budget.
+      int chunks = (256 * (G <= 4 ? 2 : 1) - heads) / units;
+      if (chunks < 1) chunks = 1;
+      int rows = (m + chunks - 1) / chunks;
+      rows = (rows + 63) / 64 * 64;
+      const int rows_max = (int)(FILT_LDS / sizeof(float)) / ((G + 3) / 4 * 4 + 1) / 64 * 64;
+      if (rows > rows_max) rows = rows_max;
+      if (rows < 512) rows = 512;
+      g.est_rows = rows;
+    } else {
+      g.est_rows = G <= 4 ? 1024 : 512;  // many heads: several rounds of workgroups anyway
+    }
+    g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
+    // tokens per range: about one resident round of retrieval workgroups (4 per CU) when
+    // there are few tokens, never more than 512 (several rounds of equal pieces then)
+    const double tokens = expect * heads;
+    int ctok = (int)((tokens + 1023) / 1024);
+    g.chunk_tokens = ctok < 256 ? 256 : (ctok > 512 ? 512 : ctok);
+    const long long ranges = (long long)(tokens / g.chunk_tokens) + 1;
+    // heavy-tailed cluster sizes select large clusters: room for three times the expected
+    // ranges (a head that finds the list full still retrieves, as one range)
+    g.wmain = (int)(3 * ranges + heads);
+    g.wtotal = g.wmain + heads;
+    const long long grid = 2 * ranges + heads;
+    g.gather_wgs = (int)(grid < g.wtotal ? grid : g.wtotal);
+    g.stage = (r < FUSED_STAGE ? r : FUSED_STAGE) + 1;  // (+ 1: the end of the last staged cluster)
   }
   // partial results per head: retrieval, steady, estimation of all clusters per
   // range, and (see below) the selected clusters' estimation terms with a minus sign
-  if (g.filtered) {
-    // Estimation ranges sized so that their 512-thread workgroups and the selecting ones are
-    // all resident at once (2 per CU up to 4 heads per KV head, else 1, by their registers): a
-    // second round of long-lived workgroups would double the launch.  The staged scores and
-    // sizes of a range, (G + 1) * rows floats, share the selecting role's LDS budget.
-    const int G = Hq / ix.Hkv;
-    int chunks = (256 * (G <= 4 ? 2 : 1) - heads) / units;
-    if (chunks < 1) chunks = 1;
-    int rows = (m + chunks - 1) / chunks;
-    rows = (rows + 63) / 64 * 64;
-    const int rows_max = (int)(FILT_LDS / sizeof(float)) / ((G + 3) / 4 * 4 + 1) / 64 * 64;
-    if (rows > rows_max) rows = rows_max;
-    if (rows < 512) rows = 512;
-    g.est_rows = rows;
-    g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
-  }
   if (g.sliced) {
     // The estimation terms come from 512-thread workgroups in the launch that ranks the
     // union of the slices' lists.  A range is sized so that those workgroups and the
@@ -3121,7 +3276,7 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   // Who takes the selected clusters' estimation terms out again: the retrieval
   // kernel itself (no partial of their own), except after the fused kernel and
   // after the streaming selection, which write them as one more partial.
-  g.neg_in_gather = (m > 0 && !g.fused && (g.filtered || g.sliced || m <= 1024 * 64)) ? 1 : 0;
+  g.neg_in_gather = (m > 0 && !g.fused && (g.listed || g.sliced || m <= 1024 * 64)) ? 1 : 0;
   g.neg_slots = (m > 0 && !g.neg_in_gather) ? 1 : 0;
   g.slots = g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots;
   if (g.slots < 1) g.slots = 1;
@@ -3140,9 +3295,15 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
     g.off_slice_z = o;   o = align_up(o + sizeof(float) * (size_t)heads * g.nslices * r);
     g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
   }
-  if (g.filtered) {
-    g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
-    g.off_chunk_first = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * (g.gather_chunks + 2));
+  if (g.listed) {
+    if (g.list_filtered) {
+      g.off_tile_max = o;  o = align_up(o + sizeof(float) * (size_t)heads * ((m + SCORE_TILE - 1) / SCORE_TILE));
+    }
+    g.off_chunk_first = o; o = align_up(o + sizeof(int32_t) * (size_t)heads * (LIST_MAX_CHUNKS + 1));
+    g.off_head_info = o;   o = align_up(o + sizeof(int4) * (size_t)heads);
+    g.off_work = o;        o = align_up(o + sizeof(int32_t) * (size_t)g.wtotal);
+    g.off_work_count = o;  o = align_up(o + sizeof(int32_t));
+    g.off_part_g = o;      o = align_up(o + sizeof(float) * (size_t)g.wtotal * (D + 2));
   }
   g.total = o;
   return g;
@@ -3169,15 +3330,19 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (m > 0) {
     const int est_slot0 = g.gather_chunks + g.steady_chunks;
     const int neg_slot = est_slot0 + g.est_chunks;  // exists when g.neg_slots is 1
-    if (g.filtered)
+    ListOut lo{};
+    if (g.listed) {
+      lo = ListOut{reinterpret_cast<int32_t*>(w + g.off_chunk_first), reinterpret_cast<int4*>(w + g.off_head_info),
+                   reinterpret_cast<int32_t*>(w + g.off_work), reinterpret_cast<int32_t*>(w + g.off_work_count),
+                   g.wmain, g.chunk_tokens};
       WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>),
                   units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
-                  reinterpret_cast<float*>(w + g.off_tile_max), units * g.score_chunks,
-                  static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.p,
-                  steady_stride(ix), g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2,
-                  part);
-    else if (g.sliced)
+                  g.list_filtered ? reinterpret_cast<float*>(w + g.off_tile_max) : nullptr,
+                  units * g.score_chunks, static_cast<const T*>(ix.k_steady),
+                  static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows,
+                  g.slots, 0, scale_log2, part, lo.work, lo.work_count, g.wtotal);
+    } else if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
                   reinterpret_cast<float*>(w + g.off_tile_max));
@@ -3203,20 +3368,36 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   key_lds, st, WAVE_SELECT_ARGS, static_cast<const T*>(ix.k_perm),
                   static_cast<const T*>(ix.v_perm), row_stride(ix), static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 2, out, lse);
-    } else if (g.filtered) {
-      size_t lds = FILT_LDS;
-      const size_t lds_merge = sizeof(float) * (FILT_NT / 64) * G * (D + 2);  // the estimation role's last step
+    } else if (g.listed) {
+      const size_t lds_est = sizeof(float) * ((G + 3) / 4 * 4 + 1) * (size_t)g.est_rows;
+      const int nt = g.list_filtered ? FILT_NT : DIRECT_NT;
+      const size_t lds_merge = sizeof(float) * (nt / 64) * G * (D + 2);  // the estimation role's last step
+      size_t lds = g.list_filtered ? FILT_LDS : select_direct_lds(m, g.stage);
+      if (lds < lds_est) lds = lds_est;
       if (lds < lds_merge) lds = lds_merge;
-      int32_t* cf = reinterpret_cast<int32_t*>(w + g.off_chunk_first);
-      SideWork sw{ix.sizes, g.est_rows, g.est_chunks, est_slot0, 0, units * g.est_chunks, ix.k_steady,
-                  ix.v_steady, ix.p, steady_stride(ix), 0, g.steady_rows, g.gather_chunks};
-      WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, FILT_NT>),
-                  heads + sw.n_est_wgs, FILT_NT, lds, st, WAVE_SELECT_ARGS,
-                  reinterpret_cast<const float*>(w + g.off_tile_max), cf, g.gather_chunks, heads, sw);
-      WAVE_LAUNCH("gather", (gather_rows_kernel<T, D>), heads * g.gather_chunks, 256, 0, st,
-                  q, static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, cf,
-                  z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
-                  g.gather_chunks, g.slots, scale_log2, part);
+      SideWork sw{ix.sizes, g.est_rows, g.est_chunks, g.steady_chunks, 0, units * g.est_chunks, ix.k_steady,
+                  ix.v_steady, ix.p, steady_stride(ix), 0, g.steady_rows, 0};
+      if (g.list_filtered)
+        WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, FILT_NT, true>),
+                    heads + sw.n_est_wgs, FILT_NT, lds, st, WAVE_SELECT_ARGS,
+                    reinterpret_cast<const float*>(w + g.off_tile_max), lo, g.stage, heads, sw);
+      else
+        WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, DIRECT_NT, false>),
+                    heads + sw.n_est_wgs, DIRECT_NT, lds, st, WAVE_SELECT_ARGS,
+                    static_cast<const float*>(nullptr), lo, g.stage, heads, sw);
+      WAVE_LAUNCH("gather", (gather_list_kernel<T, D>), g.gather_wgs, 256, 0, st, q,
+                  static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, lo,
+                  g.wtotal, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
+                  scale_log2, reinterpret_cast<float*>(w + g.off_part_g));
+      // (few heads: many threads per head, every partial in one trip; many heads: small workgroups)
+      if (heads <= 256)
+        WAVE_LAUNCH("merge", (merge_list_kernel<D, MERGE_THREADS>), heads, MERGE_THREADS, 0, st, part,
+                    g.steady_chunks + g.est_chunks, g.slots, reinterpret_cast<const float*>(w + g.off_part_g),
+                    lo.head_info, out, lse);
+      else
+        WAVE_LAUNCH("merge", (merge_list_kernel<D, 256>), heads, 256, 0, st, part,
+                    g.steady_chunks + g.est_chunks, g.slots, reinterpret_cast<const float*>(w + g.off_part_g),
+                    lo.head_info, out, lse);
     } else {
       if (g.sliced) {
         int32_t* slice_ids = reinterpret_cast<int32_t*>(w + g.off_slice_ids);
@@ -3271,7 +3452,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                 static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady), ix.Hkv, ix.p,
                 steady_stride(ix),
                 g.steady_chunks, g.steady_rows, g.slots, g.gather_chunks, scale_log2, part);
-  if (!g.fused)  // the fused kernel normalises each head itself
+  if (!g.fused && !g.listed)  // (the fused kernel normalises each head itself; the listed path has its own merge)
     WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part,
                 g.gather_chunks + g.steady_chunks + g.est_chunks + g.neg_slots, g.slots, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;

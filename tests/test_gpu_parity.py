@@ -43,6 +43,17 @@ CASES = {
     "bf16_many_heads_g7": _small("qwen7b_64k_b64", name="bf16_many_heads_g7", B=28, N=900, Hq=14,
                                  Hkv=2, segment_len=400, clusters_per_segment=24, n_local=300,
                                  n_components=64, iters=2, retrieve_frac=0.1),
+    # 800 query heads: selection in a launch of its own beside the estimation ranges, retrieval
+    # from one work list of token ranges over all heads (uneven heads: outlier tokens make
+    # large clusters)
+    "bf16_listed_heads": _small("llama8b_32k", name="bf16_listed_heads", B=100, N=1100, Hq=8, Hkv=2,
+                                segment_len=512, clusters_per_segment=32, n_local=40, n_components=48,
+                                iters=2, retrieve_frac=0.1, outlier_token_frac=0.05,
+                                outlier_token_scale=3.0),
+    # the same path at 7 query heads per KV head (840 heads)
+    "bf16_listed_heads_g7": _small("qwen7b_64k_b64", name="bf16_listed_heads_g7", B=60, N=700, Hq=14,
+                                   Hkv=2, segment_len=300, clusters_per_segment=20, n_local=200,
+                                   n_components=40, iters=2, retrieve_frac=0.15),
     # 600 clusters per segment: more centroid rows than fit in LDS at once, so the assign step
     # stages them tile by tile instead of keeping them resident
     "bf16_big_k": _small("llama8b_32k", name="bf16_big_k", N=2900, Hq=4, Hkv=1, segment_len=1400,
