@@ -28,7 +28,9 @@
  *    clusters, C centroids, s sizes, VS value sums, L segment length, k
  *    clusters per segment, T k-means iterations, G = Hq / Hkv.
  *  - Supported shapes: d in {64, 128}; 1 <= G <= 8; dtype f32 or bf16;
- *    clusters_per_segment <= 4096; N < 2^31.
+ *    clusters_per_segment <= WAVE_MAX_CLUSTERS_PER_SEGMENT (8192: one segment
+ *    over a 128K-token sequence at 16 tokens per cluster, the "global k-means"
+ *    of the segment-size study); N < 2^31.
  */
 #ifndef WAVE_H
 #define WAVE_H
@@ -51,6 +53,8 @@ typedef enum {
 } wave_status;
 
 typedef enum { WAVE_F32 = 0, WAVE_BF16 = 1 } wave_dtype;
+
+enum { WAVE_MAX_CLUSTERS_PER_SEGMENT = 8192 };
 
 /* Index of B x Hkv independent (sequence, KV head) units: the meta index
  * (centroid, value sum, size per cluster: "Index Organization" and the value-sum
@@ -182,7 +186,23 @@ wave_status wave_index_build(const void *K, const void *V, wave_index *ix, int i
  *   result is then exact attention); 0 leaves steady + estimation only.
  * Scores accumulate in fp32; a cluster whose fp32 score lies within the
  * accumulation error bound of the selection threshold is re-scored in fp64, so
- * the selected set is the fp64 ranking's. */
+ * the selected set is the fp64 ranking's.
+ *
+ * Precondition on the index (it holds for every index this library builds or
+ * grows; a caller that fills the arrays itself must keep it): each stored
+ * centroid is the mean of the cluster's stored key rows and each stored value
+ * sum the sum of its value rows, up to one rounding to dtype.  The estimation
+ * terms are computed for ALL clusters in one pass over the meta index and the
+ * selected clusters' terms are taken out again; by the estimation bound
+ * (s_i exp(q.C_i / sqrt(d)) <= sum over the cluster's rows of exp(q.K_j /
+ * sqrt(d)) when C_i is the mean) a term that is taken out never exceeds what
+ * the cluster's exact rows put in, so the cancellation costs about one fp32
+ * ulp of the result.  A centroid whose logit lies delta above that bound costs
+ * about exp(delta) ulps (storage rounding of a bf16 centroid: delta <=
+ * 2^-8 |q| |C_i| / sqrt(d), harmless); an index that breaks the bound grossly
+ * loses the retrieved part of the result to cancellation.  If the normaliser
+ * itself cancels to zero or below, out and lse of that head are NaN: never a
+ * silent zero. */
 wave_status wave_attention_decode(const void *q, const wave_index *ix, int Hq, int topk_clusters,
                                   int n_sink, int n_local, float *out, float *lse,
                                   int32_t *selected, void *workspace, size_t workspace_bytes,

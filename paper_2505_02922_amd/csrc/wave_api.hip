@@ -105,11 +105,11 @@ static wave_status check_dims(const wave_index* ix) {
   if (ix->B < 1 || ix->Hkv < 1 || ix->N < 1 || ix->n_sink < 0 || ix->n_local < 0) return WAVE_ERR_ARG;
   if (ix->segment_len < 1 || ix->clusters_per_segment < 1) return WAVE_ERR_ARG;
   if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
-  if (ix->clusters_per_segment > 4096) return WAVE_ERR_SHAPE;
+  if (ix->clusters_per_segment > WAVE_MAX_CLUSTERS_PER_SEGMENT) return WAVE_ERR_SHAPE;
   if (ix->appended_segments < 0 || ix->row_capacity < 0 || ix->steady_capacity < 0) return WAVE_ERR_ARG;
   if (ix->appended_segments > 0) {
     if (ix->update_segment_len < 1 || ix->update_clusters < 1) return WAVE_ERR_ARG;
-    if (ix->update_clusters > 4096) return WAVE_ERR_SHAPE;
+    if (ix->update_clusters > WAVE_MAX_CLUSTERS_PER_SEGMENT) return WAVE_ERR_SHAPE;
   }
   return WAVE_OK;
 }
@@ -270,7 +270,7 @@ static wave_status plan_append(const wave_index* old_ix, int n_new, int n_local_
   wave_status st = check_dims(old_ix);
   if (st != WAVE_OK) return st;
   if (!out || n_new < 0 || n_local_min < 0 || U < 1 || k_u < 1) return WAVE_ERR_ARG;
-  if (k_u > 4096) return WAVE_ERR_SHAPE;
+  if (k_u > WAVE_MAX_CLUSTERS_PER_SEGMENT) return WAVE_ERR_SHAPE;
   if (!planned_fields_match(*old_ix)) return WAVE_ERR_SHAPE;
   if (old_ix->N < old_ix->n_sink) return WAVE_ERR_SHAPE;  // the sink zone itself is still filling
   if (old_ix->appended_segments > 0 &&
@@ -519,7 +519,7 @@ wave_status wave_kmeans_assign_step(const void* xhat, const void* chat, int dtyp
   if (!xhat || !chat || !assign) return WAVE_ERR_ARG;
   if (dtype != WAVE_F32 && dtype != WAVE_BF16) return WAVE_ERR_DTYPE;
   if (d != 64 && d != 128) return WAVE_ERR_SHAPE;
-  if (L_s < 1 || k_s < 1 || k_s > 4096 || k_s > L_s) return WAVE_ERR_SHAPE;
+  if (L_s < 1 || k_s < 1 || k_s > WAVE_MAX_CLUSTERS_PER_SEGMENT || k_s > L_s) return WAVE_ERR_SHAPE;
   if (!aligned16(xhat) || !aligned16(chat)) return WAVE_ERR_ARG;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
       workspace_bytes < (size_t)4 * L_s + 1024)

@@ -125,7 +125,6 @@ __global__ __launch_bounds__(256) void normalise_kernel(const T* __restrict__ K,
 // t < b is the latest such step, it is the value position t held before step t.
 // Every thread follows that chain for its own i (chains are short: k << L).
 // ============================================================================
-constexpr int KMAX = 4096;
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
@@ -134,7 +133,9 @@ __global__ __launch_bounds__(256) void init_kernel(const T* __restrict__ xhat, T
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
-  __shared__ int target[KMAX], chosen[KMAX];
+  extern __shared__ int init_lds[];  // 2 * kk ints
+  int* target = init_lds;
+  int* chosen = init_lds + kk;
   // (seg_id_base: the segments of an index update continue the numbering of the build)
   const uint64_t st0 = init_stream_state(seed, si.unit / Hkv, si.unit % Hkv, si.s + seg_id_base);
   for (int i = threadIdx.x; i < si.k_s; i += 256) {
@@ -908,8 +909,8 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     WAVE_LAUNCH("normalise", (normalise_kernel<T, D>), grid, 256, 0, st, K, mean, xhat, S, L, ix.N,
                 N_idx, ns, (int)rows);
   }
-  WAVE_LAUNCH("init", (init_kernel<T, D>), g.segs, 256, 0, st, xhat, chat, S, L, kk, N_idx, ix.Hkv,
-              seed, seg_id_base);
+  WAVE_LAUNCH("init", (init_kernel<T, D>), g.segs, 256, 2 * sizeof(int) * (size_t)kk, st, xhat, chat, S, L,
+              kk, N_idx, ix.Hkv, seed, seg_id_base);
 
   int W = SORT_HIST_INTS / kk;
   if (W > 16) W = 16;

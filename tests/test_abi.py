@@ -141,7 +141,7 @@ def _plan_struct(**kw):
 
 
 def test_plan_rejects_bad_shapes():
-    for kw, code in [(dict(d=96), 2), (dict(clusters_per_segment=5000), 2), (dict(B=0), 1),
+    for kw, code in [(dict(d=96), 2), (dict(clusters_per_segment=8193), 2), (dict(B=0), 1),
                      (dict(segment_len=0), 1), (dict(n_sink=-1), 1)]:
         with pytest.raises(wb.WaveError) as e:
             _plan_struct(**kw)
@@ -293,7 +293,7 @@ def test_append_refuses_bad_arguments_on_the_host():
                                                           sizes, ctypes.byref(wsb))
     assert plan(-1, 64, 256, 16) == 1 and plan(10, -1, 256, 16) == 1
     assert plan(10, 64, 0, 16) == 1 and plan(10, 64, 256, 0) == 1
-    assert plan(10, 64, 256, 5000) == 2
+    assert plan(10, 64, 256, 8193) == 2
     assert plan(300, 64, 256, 16) == 0 and cn.appended_segments == 1 and wsb.value > 0
     fake = ctypes.c_void_p(0x1000)
     for name in wb.BUFFER_NAMES:

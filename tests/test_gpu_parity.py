@@ -59,11 +59,16 @@ CASES = {
     "bf16_big_k": _small("llama8b_32k", name="bf16_big_k", N=2900, Hq=4, Hkv=1, segment_len=1400,
                          clusters_per_segment=600, n_local=60, n_components=512, iters=3,
                          retrieve_frac=0.05),
-    # the largest cluster count per segment the library takes (4096), at 4 tokens per cluster,
+    # 4096 clusters per segment at 4 tokens per cluster,
     # with a ragged tail segment: the staged assign step and the two-wave counting sort
     "bf16_max_k": _small("llama8b_32k", name="bf16_max_k", N=19500, Hq=2, Hkv=1, segment_len=16384,
                          clusters_per_segment=4096, n_local=60, n_components=2048, iters=2,
                          retrieve_frac=0.02),
+    # 8192 clusters in one segment (the library's limit; the segment-size study's global k-means
+    # baseline clusters a whole 128K-token sequence this way), d = 64, a ragged second segment
+    "bf16_k8192": _small("llama8b_32k", name="bf16_k8192", d=64, N=13000, Hq=2, Hkv=1, segment_len=12288,
+                         clusters_per_segment=8192, n_local=40, n_components=4096, iters=2,
+                         retrieve_frac=0.01),
     # d = 128 in f32 (32 lanes per row)
     "f32_d128": _small("tiny_f32", name="f32_d128", d=128, N=1500, Hq=2, Hkv=1, segment_len=512,
                        clusters_per_segment=32, n_local=30, iters=3, retrieve_abs=9),
@@ -316,6 +321,73 @@ def test_decode_many_clusters_hand_index(m, dup, Hq, dtype, d):
             pu.check_outputs(out[0, hq].cpu().numpy(), lse[0, hq:hq + 1].cpu().numpy(), o, np.array([l]),
                              dtype, tag)
             pu.check_selected(sel[0, hq].cpu().numpy(), s_ref, parts["z"], tag)
+
+
+def _decode_hand(arrs, n, m, d, dtype, q, r, Hq=2):
+    """Decode on a hand-filled index of m clusters (one KV head) and the oracle on the same arrays."""
+    p, Hkv = 8, 1
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    c, _, _, _ = wb.wave_index_plan(tdt, 1, Hkv, d, 4 * m + p, 4, p - 4, 4, 1)
+    pad = c.N_idx - n
+    arrs = dict(arrs)
+    arrs["k_perm"] = np.concatenate([arrs["k_perm"], np.zeros((pad, d))])
+    arrs["v_perm"] = np.concatenate([arrs["v_perm"], np.zeros((pad, d))])
+    arrs["perm"] = np.arange(c.N_idx)
+    tens = {k: torch.from_numpy(np.asarray(v)[None, None].astype(
+        np.int32 if k in ("sizes", "offsets", "perm") else np.float32)) for k, v in arrs.items()}
+    ix = wb.index_from_arrays(tdt, 1, Hkv, d, 4 * m + p, 4, p - 4, 4, 1, tens)
+    plan = wo.make_plan(4 * m + p, 4, p - 4, 4, 1)
+    ref = wo.UnitIndex(plan, dtype, arrs["centroids"], arrs["vsum"], arrs["sizes"], arrs["offsets"],
+                       arrs["perm"], arrs["k_perm"], arrs["v_perm"], arrs["k_steady"],
+                       arrs["v_steady"], np.zeros(0, dtype=np.int64))
+    out, lse, sel = wb.wave_attention_decode(q.cuda(), ix, r, want_selected=True)
+    torch.cuda.synchronize()
+    qn = q.double().numpy()
+    res = []
+    for hq in range(Hq):
+        parts = {}
+        o, l, s_ref = wo.decode_unit(qn[0, hq], ref, r, parts)
+        res.append((out[0, hq].cpu().numpy(), float(lse[0, hq]), sel[0, hq].cpu().numpy(), o, l, s_ref,
+                    parts["z"]))
+    return res
+
+
+@pytest.mark.parametrize("m", [3000, 40000])
+def test_decode_on_an_index_whose_centroids_are_not_the_member_means(m):
+    """The decode step takes the selected clusters' estimation terms out of a sum over ALL
+    clusters, which is exact only up to cancellation; the header states what the index must
+    satisfy.  (a) Centroids a little off the mean (5 % noise: far more than storage rounding)
+    still match the oracle, which never subtracts, on the same arrays.  (b) A centroid grossly
+    off the mean, selected and dominating everything, is outside that contract; it must still
+    not come back as a silent zero."""
+    d, dtype = 128, "bf16"
+    arrs, n = _hand_index(m, d, dtype, 8, seed=m + 1)
+    g = np.random.default_rng(11)
+    q = torch.from_numpy(wo.quant(g.standard_normal((1, 2, d)) * 1.5, dtype).astype(np.float32)
+                         ).to(torch.bfloat16)
+    off = g.random(m) < 0.3
+    C = np.array(arrs["centroids"], dtype=np.float64)
+    C[off] += 0.05 * g.standard_normal((int(off.sum()), d)) * np.abs(C[off]).mean()
+    mild = dict(arrs, centroids=wo.quant(C, dtype))
+    for r in (50, 300):
+        for hq, (o_g, l_g, s_g, o, l, s_ref, z) in enumerate(_decode_hand(mild, n, m, d, dtype, q, r)):
+            tag = f"mild m={m} r={r} hq={hq}"
+            pu.check_outputs(o_g, np.array([l_g]), o, np.array([l]), dtype, tag)
+            pu.check_selected(s_g, s_ref, z, tag)
+    # (b) one non-empty cluster whose centroid points along q with a huge norm: its estimation
+    # term is ~e^40 times everything else, it is selected, and its rows do not back it
+    C2 = np.array(arrs["centroids"], dtype=np.float64)
+    big = int(np.nonzero(arrs["sizes"])[0][5])
+    C2[big] = q[0, 0].double().numpy() * 4.0
+    gross = dict(arrs, centroids=wo.quant(C2, dtype))
+    o_g, l_g, s_g, o, l, s_ref, z = _decode_hand(gross, n, m, d, dtype, q, 50)[0]
+    assert big in set(int(x) for x in s_g)
+    # outside the contract the header states: what is left after the cancellation is rounding
+    # residue of the dominating term, positive or negative.  The one promise left is that a
+    # normaliser that cancels to zero or below is reported as NaN, never as an output of zeros
+    # with lse = -inf.
+    assert not np.all(o_g == 0.0) and l_g != float("-inf")
+    assert (np.isnan(o_g).all() and np.isnan(l_g)) or (np.isfinite(o_g).all() and np.isfinite(l_g))
 
 
 @pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),

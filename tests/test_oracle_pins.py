@@ -542,3 +542,31 @@ def test_gqa_mapping_and_workload_tiny():
     for hq in range(4):
         of, lf = wo.full_attention(qn[0, hq], Kn[0, hq // 2], Vn[0, hq // 2])
         assert np.allclose(out[0, hq], of, atol=1e-12) and abs(lse[0, hq] - lf) < 1e-12
+
+
+def test_storage_rounding_of_a_centroid_stays_within_the_stated_logit_bound():
+    """The GPU path subtracts a selected cluster's estimation term from a sum over all clusters,
+    which is harmless while the term does not exceed the cluster's exact terms (the estimation
+    bound, which needs the centroid to be the mean).  A stored centroid is the mean rounded to
+    bf16: its logit moves by at most 2^-8 |q| |C| / sqrt(d), so the bound is broken by at most
+    that much.  Checked on an oracle-built index."""
+    from paper_2505_02922_amd import synth
+    wl = synth.scaled(synth.WORKLOADS["llama8b_32k"], N=3000, Hq=4, Hkv=1, segment_len=1024,
+                      clusters_per_segment=64, n_local=100, n_components=64, iters=3)
+    K, V = synth.make_kv(wl)
+    q = synth.make_queries(wl).double().numpy()[0]
+    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+    ix = wo.build_unit(K[0, 0].double().numpy(), V[0, 0].double().numpy(), plan, wl.iters, 0, 0, 0, "bf16")
+    C = np.asarray(ix.centroids, dtype=np.float64)
+    Kp = np.asarray(ix.k_perm, dtype=np.float64)
+    off = np.asarray(ix.offsets)
+    worst = 0.0
+    for hq in range(wl.Hq):
+        for c in np.nonzero(np.asarray(ix.sizes))[0]:
+            rows = Kp[off[c]:off[c + 1]] @ q[hq] / math.sqrt(wl.d)
+            lme = rows.max() + math.log(np.exp(rows - rows.max()).mean())     # log of the mean exponential
+            lc = C[c] @ q[hq] / math.sqrt(wl.d)
+            bound = 2.0 ** -8 * np.linalg.norm(q[hq]) * np.linalg.norm(C[c]) / math.sqrt(wl.d)
+            assert lc <= lme + bound
+            worst = max(worst, lc - lme)
+    assert worst < 0.1     # e^0.1: a tenth of a bit of the fp32 result
