@@ -1670,14 +1670,15 @@ constexpr int GATHER_TILE = 256;  // tokens (and clusters) per pass of a workgro
 // set, takes the same clusters' estimation terms (which the estimation pass
 // added for every cluster) out again, in the same online-softmax state.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_kernel(
-    const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
-    const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ nsel_arr,
-    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int N_idx /* rows per unit in k_perm / v_perm */, int m, int rcap, int chunks,
-    int slots, float scale_log2, int own_neg, float* __restrict__ part) {
+__device__ __forceinline__ void gather_role(
+    int block, int nblocks, const T* __restrict__ q, const T* __restrict__ k_perm,
+    const T* __restrict__ v_perm, const int32_t* __restrict__ sel_ids,
+    const int32_t* __restrict__ nsel_arr, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const T* __restrict__ vsum, int Hq, int Hkv,
+    int N_idx /* rows per unit in k_perm / v_perm */, int m, int rcap, int chunks, int slots,
+    float scale_log2, int own_neg, float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int wg = xcd_logical_block(block, nblocks);
   const int bh = wg / chunks, chunk = wg - bh * chunks;
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
   const int unit = b * Hkv + hq / G;
@@ -1772,6 +1773,17 @@ __global__ __launch_bounds__(256) void gather_kernel(
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + chunk) * (D + 2), 0);
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
+    const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ nsel_arr,
+    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
+    int Hq, int Hkv, int N_idx, int m, int rcap, int chunks, int slots, float scale_log2, int own_neg,
+    float* __restrict__ part) {
+  gather_role<T, D>(blockIdx.x, gridDim.x, q, k_perm, v_perm, sel_ids, nsel_arr, offsets, z, vsum, Hq, Hkv,
+                    N_idx, m, rcap, chunks, slots, scale_log2, own_neg, part);
+}
+
 // Estimation zone with a budget: the clusters of the (ascending) list ids2 that
 // are not in the (ascending) list ids1 enter with their centroid's score as the
 // logit, their size as the multiplicity and their value sum as the value.
@@ -1779,14 +1791,14 @@ __global__ __launch_bounds__(256) void gather_kernel(
 constexpr int EST_STAGE = 4096;  // retrieved ids kept in LDS for the membership test
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void est_gather_kernel(
-    const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
+__device__ __forceinline__ void est_gather_role(
+    int block, const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
     const int32_t* __restrict__ ids1_all, const int32_t* __restrict__ nsel1_arr,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
     int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
     float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
-  const int bh = blockIdx.x / chunks, chunk = blockIdx.x - bh * chunks;
+  const int bh = block / chunks, chunk = block - bh * chunks;
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
   const int unit = b * Hkv + hq / G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1807,17 +1819,19 @@ __global__ __launch_bounds__(256) void est_gather_kernel(
   const int c_lo = (int)((long long)chunk * nsel2 / chunks), c_hi = (int)((long long)(chunk + 1) * nsel2 / chunks);
   AttnState<T, D, 1> st;
   st.reset();
-  for (int i = c_lo + grp; i < c_hi; i += GROUPS * U) {
-    uint4 vraw[U];
-    float sc[1][U], mult[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int ii = i + u * GROUPS;
-      const bool on = ii < c_hi;
-      const int id = ids2[on ? ii : i];
-      // member of the retrieved list?  (largest a with ids1[a] <= id)
+  // Passes of 256 list positions: one thread per position reads the id, looks it up in the
+  // retrieved list, and reads the cluster's score and size (three dependent trips to memory
+  // for 256 clusters at once); the value-sum rows then stream, eight per lane group in flight.
+  __shared__ int t_id[256];
+  __shared__ float t_logit[256], t_mult[256];
+  constexpr int UE = 8;
+  for (int p0 = c_lo; p0 < c_hi; p0 += 256) {
+    const int n = min(256, c_hi - p0);
+    __syncthreads();  // the previous pass is done with the tables
+    {
+      const int id = ids2[min(p0 + (int)threadIdx.x, c_hi - 1)];
       bool retrieved = false;
-      if (nsel1 > 0) {
+      if (nsel1 > 0) {  // largest a with ids1[a] <= id
         int a = 0, e = nsel1;
         while (e - a > 1) {
           const int mid = (a + e) >> 1;
@@ -1825,24 +1839,69 @@ __global__ __launch_bounds__(256) void est_gather_kernel(
         }
         retrieved = ids1[a] == id;
       }
-      vraw[u] = load16(VSu + (size_t)id * D);
-      sc[0][u] = (on && !retrieved) ? zz[id] * scale_log2 : -INFINITY;
-      mult[u] = (float)(off[id + 1] - off[id]);
+      const float zc = zz[id];
+      const int o0 = off[id], o1 = off[id + 1];
+      t_id[threadIdx.x] = id;
+      t_logit[threadIdx.x] = ((int)threadIdx.x < n && !retrieved) ? zc * scale_log2 : -INFINITY;
+      t_mult[threadIdx.x] = (float)(o1 - o0);
     }
-    st.template rows_given<U>(sc, mult, vraw);
+    __syncthreads();
+    for (int i = grp; i < n; i += GROUPS * UE) {
+      uint4 vraw[UE];
+      float sc[1][UE], mult[UE];
+#pragma unroll
+      for (int u = 0; u < UE; ++u) {
+        const int j = min(i + u * GROUPS, 255);  // entries at or beyond n carry -inf
+        vraw[u] = load16(VSu + (size_t)t_id[j] * D);
+        sc[0][u] = i + u * GROUPS < n ? t_logit[j] : -INFINITY;
+        mult[u] = t_mult[j];
+      }
+      st.template rows_given<UE>(sc, mult, vraw);
+    }
   }
+  __syncthreads();
   merge_groups_and_store<T, D, 1>(st, smem, part + ((size_t)bh * slots + slot0 + chunk) * (D + 2), 0);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void est_gather_kernel(
+    const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
+    const int32_t* __restrict__ ids1_all, const int32_t* __restrict__ nsel1_arr,
+    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
+    int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
+    float* __restrict__ part) {
+  est_gather_role<T, D>(blockIdx.x, ids2_all, nsel2_arr, ids1_all, nsel1_arr, offsets, z, vsum, Hq, Hkv, m,
+                        rcap2, rcap1, chunks, slots, slot0, scale_log2, part);
+}
+
+// The retrieval zone and the budgeted estimation zone in one launch: both only need the two
+// id lists, neither needs the other.  The estimation workgroups come first: they have the
+// scattered value-sum rows, the retrieval workgroups the long contiguous ranges.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_est_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
+    const int32_t* __restrict__ ids1, const int32_t* __restrict__ nsel1,
+    const int32_t* __restrict__ ids2, const int32_t* __restrict__ nsel2,
+    const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
+    int Hq, int Hkv, int N_idx, int m, int rcap1, int rcap2, int gather_chunks, int est_chunks, int slots,
+    int gather_slot0, int est_slot0, int n_est_wgs, float scale_log2, float* __restrict__ part) {
+  if ((int)blockIdx.x < n_est_wgs) {
+    est_gather_role<T, D>(blockIdx.x, ids2, nsel2, ids1, nsel1, offsets, z, vsum, Hq, Hkv, m, rcap2, rcap1,
+                          est_chunks, slots, est_slot0, scale_log2, part);
+    return;
+  }
+  gather_role<T, D>((int)blockIdx.x - n_est_wgs, (int)gridDim.x - n_est_wgs, q, k_perm, v_perm, ids1, nsel1,
+                    offsets, z, vsum, Hq, Hkv, N_idx, m, rcap1, gather_chunks, slots, scale_log2, 0,
+                    part + (size_t)gather_slot0 * (D + 2));
 }
 
 constexpr int MERGE_THREADS = 1024;
 
-template <int D>
-__global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(const float* __restrict__ part, int slots,
-                                                              int slot_stride, float* __restrict__ out,
-                                                              float* __restrict__ lse) {
+template <int D, int NT = MERGE_THREADS>
+__global__ __launch_bounds__(NT) void merge_kernel(const float* __restrict__ part, int slots, int slot_stride,
+                                                   float* __restrict__ out, float* __restrict__ lse) {
   const int bh = blockIdx.x;  // a head's partials are slot_stride slots apart; the first `slots` count
-  merge_head<D, MERGE_THREADS, 16>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D,
-                                   lse + bh);
+  merge_head<D, NT, 16>(part + (size_t)bh * slot_stride * (D + 2), slots, out + (size_t)bh * D, lse + bh);
 }
 
 // ----------------------------------------------------------------------------
@@ -2002,6 +2061,28 @@ __device__ __forceinline__ void steady_rows_partial(const T* __restrict__ q,
     st.template rows<U, LPR>(kraw, vraw, valid);
   }
   merge_groups_and_store<T, D, G, NWV>(st, smem, part_head0, head_stride);
+}
+
+// Two selections of every head in one launch (the r best and the r + e best clusters of the
+// budgeted estimation zone): even workgroups take the first, odd ones the second.  Each
+// leaves its ascending id list and count.
+template <typename T, int D, int NT, int VPT>
+__global__ __launch_bounds__(NT) void select_two_kernel(
+    const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
+    const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
+    int m, int mwords, uint32_t* __restrict__ bitmap, int r1, int rcap1, int32_t* __restrict__ ids1,
+    int32_t* __restrict__ nsel1, int32_t* __restrict__ user_selected, int r2, int rcap2,
+    int32_t* __restrict__ ids2, int32_t* __restrict__ nsel2, const T* __restrict__ vsum, float scale_log2) {
+  extern __shared__ uint32_t dyn_keys[];
+  const int bh = blockIdx.x >> 1;
+  const bool second = blockIdx.x & 1;
+  int ntok;
+  select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, second ? r2 : r1,
+                                   second ? rcap2 : rcap1, mwords, second ? r2 : r1, second ? ids2 : ids1,
+                                   nullptr, nullptr, bitmap, second ? nsel2 : nsel1,
+                                   second ? nullptr : user_selected, vsum, scale_log2, nullptr, 0, 0, bh,
+                                   dyn_keys, nullptr, nullptr, 0, &ntok,
+                                   SelView{m, 0, nullptr, nullptr, 2, nullptr, nullptr});
 }
 
 template <typename T, int D, int G>
@@ -2984,7 +3065,7 @@ __global__ __launch_bounds__(256, 4) void score_steady_kernel(
   const int Hq = Hkv * G;
   // the retrieval work list of this step starts empty (the next launch fills it)
   for (int i = blockIdx.x * 256 + threadIdx.x; i < wtotal; i += gridDim.x * 256) work[i] = -1;
-  if (blockIdx.x == 0 && threadIdx.x == 0) *work_count = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && work_count) *work_count = 0;
   if ((int)blockIdx.x < n_score_wgs) {
     const Lds lds(lds_raw);
     const int wg = xcd_logical_block(blockIdx.x, n_score_wgs);
@@ -3551,6 +3632,32 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const int slots = g.slots + 1, spare_slot = g.slots;
 
+  // Keys of a head fit in LDS: four launches.  The scores with the steady zone as extra
+  // workgroups; both selections at once (two workgroups per head); retrieval and estimation in
+  // one launch (neither needs the other); the merge.
+  if (m <= 512 * 32 && est_clusters > 0) {
+    WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>), units * (g.score_chunks + g.steady_chunks),
+                256, 0, st, q, C, ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks, static_cast<float*>(nullptr),
+                units * g.score_chunks, static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady),
+                ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows, slots, 0, scale_log2, part,
+                static_cast<int32_t*>(nullptr), static_cast<int32_t*>(nullptr), 0);
+    WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32>), 2 * heads, 512,
+                sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, q, C, ix.offsets, z, cn2,
+                g.score_chunks, Hq, ix.Hkv, m, g.mwords, bitmap, g.r, g.rcap1, ids1, nsel1, selected, g.k2,
+                g.rcap2, ids2, nsel2, VS, scale_log2);
+    const int n_est = heads * g.est_chunks;
+    WAVE_LAUNCH("gather+estimate", (gather_est_kernel<T, D>), n_est + heads * g.gather_chunks, 256, 0, st, q,
+                static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1, ids2, nsel2,
+                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, g.rcap1, g.rcap2, g.gather_chunks,
+                g.est_chunks, slots, g.steady_chunks, g.steady_chunks + g.gather_chunks, n_est, scale_log2,
+                part);
+    if (heads <= 256)
+      WAVE_LAUNCH("merge", (merge_kernel<D, MERGE_THREADS>), heads, MERGE_THREADS, 0, st, part, g.slots, slots,
+                  out, lse);
+    else
+      WAVE_LAUNCH("merge", (merge_kernel<D, 256>), heads, 256, 0, st, part, g.slots, slots, out, lse);
+    return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+  }
   WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q, C, ix.sizes, z,
               cn2, ix.Hkv, m, g.score_chunks, static_cast<float*>(nullptr));
   // the k best clusters of every head as an ascending id list (ids, nsel)
