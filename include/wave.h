@@ -186,7 +186,12 @@ wave_status wave_index_build(const void *K, const void *V, wave_index *ix, int i
  *   result is then exact attention); 0 leaves steady + estimation only.
  * Scores accumulate in fp32; a cluster whose fp32 score lies within the
  * accumulation error bound of the selection threshold is re-scored in fp64, so
- * the selected set is the fp64 ranking's.
+ * the selected set is the fp64 ranking's (also when thousands of scores lie
+ * inside that bound: they are then ranked in fp64 without being kept, slowly).
+ * One exception: a head ranked by the streaming selection (more than 131072
+ * clusters per KV head, or more than 2048 clusters passing the first-stage
+ * filter of the many-cluster path) AND with more than 1024 scores inside the
+ * bound keeps the fp32 ranking, ties to the lower id.
  *
  * Precondition on the index (it holds for every index this library builds or
  * grows; a caller that fills the arrays itself must keep it): each stored

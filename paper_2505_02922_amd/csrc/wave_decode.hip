@@ -1012,6 +1012,21 @@ __device__ __forceinline__ int select_core(
       }
     }
   };
+  // fp64 score of position i as an order-preserving 64-bit integer (for the rare ranking of a
+  // band too large for the candidate list); a thread caches its first four band positions
+  uint64_t zc64[4] = {0, 0, 0, 0}, t64 = 0;
+  int need_eq64 = 0;
+  auto key64_of = [&](int i) -> uint64_t {
+    const T* rowp = C + ((size_t)unit * m + cid(i)) * D;
+    double acc = 0.0;
+    for (int e = 0; e < D; ++e) acc = fma(to_f64(q[(size_t)bh * D + e]), to_f64(rowp[e]), acc);
+    const uint64_t u = (uint64_t)__double_as_longlong(acc + 0.0);
+    return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+  };
+  auto band_key = [&](int j, int i) -> uint64_t {
+    if (j < 4) return j == 0 ? zc64[0] : (j == 1 ? zc64[1] : (j == 2 ? zc64[2] : zc64[3]));
+    return key64_of(i);
+  };
   // ---- valid count, maximum, |q|^2, max |C|^2 ----------------------------------
   int nv = 0;
   uint32_t kmax = kKeyNegInf, kmin = 0xffffffffu;  // over the valid scores
@@ -1046,11 +1061,12 @@ __device__ __forceinline__ int select_core(
   const int r_eff = min(r, nvalid);
   WAVE_STAMP(trace, 11);
 
-  // mode 0: nothing selected; 1: every valid cluster; 2: threshold + exact band; 3: fp32 rule
+  // mode 0: nothing selected; 1: every valid cluster; 2: threshold + exact band (fp64 scores
+  // kept in LDS); 3: the same band ranked in fp64 without keeping its scores
   int mode;
   uint32_t ktau = 0, klo_band = 0, khi_band = 0;
   float hi = 0.f;
-  int need_eq = 0, n_cand = 0, need = 0;
+  int n_cand = 0, need = 0;
   if (r_eff == 0) {
     mode = 0;
   } else if (r_eff == nvalid) {
@@ -1204,7 +1220,6 @@ __device__ __forceinline__ int select_core(
       ktau = klo;
     WAVE_STAMP(trace, 12);
     const float tau = key_to_float(ktau);
-    need_eq = r_eff - cnt_hi;  // count(key > tau) = count(key >= khi) = cnt_hi
     hi = tau + guard;
     klo_band = order_key((tau - guard) + 0.0f);
     khi_band = order_key(hi + 0.0f);
@@ -1233,7 +1248,42 @@ __device__ __forceinline__ int select_core(
     n_cand = sh_i[2];
     need = r_eff - n_hi;
     if (n_cand > CAND_CAP) {
-      mode = 3;  // too many near-equal scores: keep the fp32 ranking
+      // More scores inside the band than the candidate list holds: their fp64 scores are not
+      // kept.  The need-th largest is found bit by bit on the order-preserving 64-bit image
+      // of the fp64 score (64 counting steps, each re-scoring what a thread could not cache):
+      // slow, exact, and only ever reached with over a thousand nearly equal centroids.
+      mode = 3;
+      {
+        int j = 0;
+        for_k([&](int k, uint32_t ky) {
+          if (ky >= klo_band && ky <= khi_band) {
+            const uint64_t v = key64_of(k * NT + tid);
+            if (j == 0) zc64[0] = v;
+            if (j == 1) zc64[1] = v;
+            if (j == 2) zc64[2] = v;
+            if (j == 3) zc64[3] = v;
+            ++j;
+          }
+        });
+      }
+      auto count_band = [&](uint64_t bound, bool strict) {
+        int c = 0, j = 0;
+        for_k([&](int k, uint32_t ky) {
+          if (ky >= klo_band && ky <= khi_band) {
+            const uint64_t v = band_key(j, k * NT + tid);
+            c += (strict ? v > bound : v >= bound) ? 1 : 0;
+            ++j;
+          }
+        });
+        return block_sum_i<NT>(c, scan_scratch);
+      };
+      uint64_t t = 0;
+      for (int bit = 63; bit >= 0; --bit) {
+        const uint64_t trial = t | (1ull << bit);
+        if (count_band(trial, false) >= need) t = trial;
+      }
+      t64 = t;  // the need-th largest: count(>= t) >= need > count(>= t + 1)
+      need_eq64 = need - count_band(t, true);
     } else if (n_cand == need) {
       mode = 2;  // the whole band is taken; no ranking needed
     } else {
@@ -1287,24 +1337,38 @@ __device__ __forceinline__ int select_core(
       sel |= (uint64_t)(on ? 1 : 0) << k;
     });
   } else if (mode == 3) {
+    // above the band: in; inside it: fp64 score above the need-th largest, or equal to it and
+    // among the need_eq64 lowest ids of those (positions are in id order)
     if (tid < TBL) tbl_cnt[tid] = 0;  // sweeps beyond nk stay empty
     __syncthreads();
-    for_k([&](int k, uint32_t ky) {
-      const uint64_t eq = __ballot(ky == ktau);
-      if (lane == 0) tbl_cnt[k * NW + wave] = __popcll(eq);
-    });
+    {
+      int j = 0;
+      for_k([&](int k, uint32_t ky) {
+        const bool inb = ky >= klo_band && ky <= khi_band;
+        uint64_t v = 0;
+        if (inb) v = band_key(j++, k * NT + tid);
+        const uint64_t eq = __ballot(inb && v == t64);
+        if (lane == 0) tbl_cnt[k * NW + wave] = __popcll(eq);
+      });
+    }
     __syncthreads();
     int tot;
     const int base = block_excl_scan<NT>(tid < TBL ? tbl_cnt[tid] : 0, scan_scratch, tot);
     __syncthreads();
     if (tid < TBL) tbl_cnt[tid] = base;
     __syncthreads();
-    for_k([&](int k, uint32_t ky) {
-      const uint64_t eq = __ballot(ky == ktau);
-      const int rank = tbl_cnt[k * NW + wave] + __popcll(eq & lt_mask);
-      const bool on = ky > ktau || (ky == ktau && rank < need_eq);
-      sel |= (uint64_t)(on ? 1 : 0) << k;
-    });
+    {
+      int j = 0;
+      for_k([&](int k, uint32_t ky) {
+        const bool inb = ky >= klo_band && ky <= khi_band;
+        uint64_t v = 0;
+        if (inb) v = band_key(j++, k * NT + tid);
+        const uint64_t eq = __ballot(inb && v == t64);
+        const int rank = tbl_cnt[k * NW + wave] + __popcll(eq & lt_mask);
+        const bool on = ky > khi_band || (inb && (v > t64 || (v == t64 && rank < need_eq64)));
+        sel |= (uint64_t)(on ? 1 : 0) << k;
+      });
+    }
     __syncthreads();
   }
 
@@ -1797,7 +1861,7 @@ __device__ __forceinline__ void est_gather_role(
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
     int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
     float* __restrict__ part) {
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW;
   const int bh = block / chunks, chunk = block - bh * chunks;
   const int b = bh / Hq, hq = bh - b * Hq, G = Hq / Hkv;
   const int unit = b * Hkv + hq / G;

@@ -390,6 +390,45 @@ def test_decode_on_an_index_whose_centroids_are_not_the_member_means(m):
     assert (np.isnan(o_g).all() and np.isnan(l_g)) or (np.isfinite(o_g).all() and np.isfinite(l_g))
 
 
+@pytest.mark.parametrize("m,r", [(3000, 700), (3000, 1), (40000, 900)])
+def test_more_near_equal_scores_than_the_candidate_list_holds(m, r):
+    """1500 clusters whose centroids differ from one vector only in the last bf16 bit of three
+    small-weight coordinates: 1500 scores, hundreds of them distinct, inside the fp32 error band around the
+    selection threshold (fp32 accumulation orders them differently from fp64), more than the
+    1024 the exact ranking keeps in LDS.  The selected set must still be the fp64 ranking's,
+    ties to the lower id: here it is compared for equality, not up to a tie band."""
+    d, dtype = 128, "bf16"
+    g = np.random.default_rng(m + r)
+    arrs, n = _hand_index(m, d, dtype, 8, seed=m + 7)
+    # q: weight 1 on the first 64 coordinates, distinct small weights 2^-8 (1 + t / 128) on the others
+    qv = np.ones(d)
+    qv[64:] = 2.0 ** -8 * (1.0 + np.arange(64) / 128.0)
+    c0 = np.ones(d)
+    nb = 1500
+    band_ids = np.sort(g.choice(np.nonzero(arrs["sizes"])[0], nb, replace=False))
+    C = np.array(arrs["centroids"], dtype=np.float64) * 0.05      # every other cluster scores far lower
+    Kp = np.array(arrs["k_perm"], dtype=np.float64)
+    off = arrs["offsets"]
+    for c in band_ids:
+        row = c0.copy()
+        for a in g.choice(64, 3, replace=False) + 64:
+            row[a] += g.integers(-1, 2) * 2.0 ** -7               # one bf16 ulp of 1.0 up or down
+        C[c] = row
+        Kp[off[c]:off[c + 1]] = row                               # the rows are the centroid: still their mean
+    arrs = dict(arrs, centroids=wo.quant(C, dtype), k_perm=wo.quant(Kp, dtype))
+    assert np.array_equal(arrs["centroids"][band_ids], C[band_ids])   # exactly representable
+    q = torch.from_numpy(np.stack([qv, wo.quant(g.standard_normal(d), dtype)])[None].astype(np.float32)
+                         ).to(torch.bfloat16)
+    zb = C[band_ids] @ qv
+    assert np.unique(zb).size > 400                               # many distinct fp64 scores (and exact ties) ...
+    assert zb.max() - zb.min() < 2 * 48 * 2.0 ** -24 * np.linalg.norm(qv) * np.linalg.norm(c0)   # ... inside the band
+    res = _decode_hand(arrs, n, m, d, dtype, q, r)
+    for hq, (o_g, l_g, s_g, o, l, s_ref, z) in enumerate(res):
+        tag = f"band m={m} r={r} hq={hq}"
+        assert np.array_equal(s_g[s_g >= 0], np.asarray(s_ref)), tag
+        pu.check_outputs(o_g, np.array([l_g]), o, np.array([l]), dtype, tag)
+
+
 @pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),
                                         ("llama8b_32k", [(0, 0), (0, 3), (0, 7)]),
                                         ("llama8b_1m", [(0, 5)]),
