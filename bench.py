@@ -277,7 +277,7 @@ def decode_phase(run: DecodeRun, steps: int, warmup: int, profile_steps: int):
         "select_gather_steady": gather_b + steady_b, "select": 0, "merge": 0,
         "scores": cbytes + units * ix.m * 4, "select_slices+side": steady_b, "select+side": cbytes,
         "meta_index+steady": meta + steady_b,
-        "scores+steady": cbytes + units * ix.m * 4 + steady_b, "select+estimate": cbytes,
+        "scores+steady": cbytes + units * ix.m * 4 + steady_b, "select+estimate+steady": cbytes + steady_b,
         "gather+estimate": gather_b + cbytes,
     }
     step_bytes = meta + steady_b + gather_b

@@ -3050,7 +3050,7 @@ __device__ __forceinline__ void select_direct(
   int* s_row = s_pref + stage + 1;
   int32_t* s_ids = s_row + stage;
   int ntok;
-  const int nsel = select_core<T, D, NT, 16384 / NT, true>(
+  const int nsel = select_core<T, D, NT, 64, true>(
       q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
       sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys, s_pref,
       s_row, stage, &ntok, SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr, s_ids, 1});
@@ -3060,10 +3060,13 @@ __device__ __forceinline__ void select_direct(
   publish_token_ranges<NT>(bh, nsel, ntok, pref, lo);
 }
 
-constexpr int DIRECT_NT = 256;  // threads of a selecting workgroup when the keys fit in LDS (many heads:
-                                // small workgroups, so that more heads' chains of short steps are in flight)
+// Threads of a selecting workgroup when the keys fit in LDS (many heads): small workgroups, so
+// that more heads' chains of short dependent steps are in flight per CU; a thread holds at most
+// 64 keys' marks.
+inline int select_direct_threads(int m) { return m <= 64 * 128 ? 128 : 256; }
 inline size_t select_direct_lds(int m, int stage) {
-  return sizeof(uint32_t) * DIRECT_NT * (size_t)((m + DIRECT_NT - 1) / DIRECT_NT) + sizeof(int) * (3 * (size_t)stage + 1);
+  const int nt = select_direct_threads(m);
+  return sizeof(uint32_t) * nt * (size_t)((m + nt - 1) / nt) + sizeof(int) * (3 * (size_t)stage + 1);
 }
 
 // One workgroup per head selects (FILTERED: through the tile maxima, for more clusters than
@@ -3098,6 +3101,31 @@ __global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_esti
                               usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
                               vsum, scale_log2, part, slots, neg_slot, sel_before, stage, lo,
                               reinterpret_cast<char*>(dyn_keys));
+    return;
+  }
+  if (b - sel_before >= sw.n_est_wgs) {
+    // the steady-zone pieces (rows shared by the G heads of a KV head, read once per KV head)
+    const int wg = b - sel_before - sw.n_est_wgs;
+    const int unit = wg / sw.steady_chunks, chunk = wg - unit * sw.steady_chunks;
+    const int bq = unit / Hkv, h = unit - bq * Hkv;
+    const int bh0 = bq * Hq + h * G;
+    const int r0 = chunk * sw.steady_rows, r1 = min(sw.p, r0 + sw.steady_rows);
+    // (more than 4 heads at once would cost the launch its occupancy: the rows are read a
+    // second time, from cache, for the heads beyond the fourth)
+    constexpr int G1 = G <= 4 ? G : 4;
+    float* smem = reinterpret_cast<float*>(dyn_keys);
+    steady_rows_partial<T, D, G1, NT>(q, static_cast<const T*>(sw.k_steady), static_cast<const T*>(sw.v_steady),
+                                      unit, bh0, sw.p_stride, r0, r1, scale_log2, smem,
+                                      part + ((size_t)bh0 * slots + sw.steady_slot0 + chunk) * (D + 2),
+                                      (size_t)slots * (D + 2));
+    if constexpr (G > 4) {
+      __syncthreads();
+      steady_rows_partial<T, D, G - 4, NT>(q, static_cast<const T*>(sw.k_steady),
+                                           static_cast<const T*>(sw.v_steady), unit, bh0 + 4, sw.p_stride, r0, r1,
+                                           scale_log2, smem,
+                                           part + ((size_t)(bh0 + 4) * slots + sw.steady_slot0 + chunk) * (D + 2),
+                                           (size_t)slots * (D + 2));
+    }
     return;
   }
 #ifdef WAVE_TRACE
@@ -3480,12 +3508,12 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       lo = ListOut{reinterpret_cast<int32_t*>(w + g.off_chunk_first), reinterpret_cast<int4*>(w + g.off_head_info),
                    reinterpret_cast<int32_t*>(w + g.off_work), reinterpret_cast<int32_t*>(w + g.off_work_count),
                    g.wmain, g.chunk_tokens};
-      WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>),
-                  units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
+      // (the steady zone rides with the selection launch; this kernel's steady role stays idle)
+      WAVE_LAUNCH("scores", (score_steady_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
                   g.list_filtered ? reinterpret_cast<float*>(w + g.off_tile_max) : nullptr,
                   units * g.score_chunks, static_cast<const T*>(ix.k_steady),
-                  static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows,
+                  static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 0, g.steady_rows,
                   g.slots, 0, scale_log2, part, lo.work, lo.work_count, g.wtotal);
     } else if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
@@ -3515,20 +3543,25 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 2, out, lse);
     } else if (g.listed) {
       const size_t lds_est = sizeof(float) * ((G + 3) / 4 * 4 + 1) * (size_t)g.est_rows;
-      const int nt = g.list_filtered ? FILT_NT : DIRECT_NT;
+      const int nt = g.list_filtered ? FILT_NT : select_direct_threads(m);
       const size_t lds_merge = sizeof(float) * (nt / 64) * G * (D + 2);  // the estimation role's last step
       size_t lds = g.list_filtered ? FILT_LDS : select_direct_lds(m, g.stage);
       if (lds < lds_est) lds = lds_est;
-      if (lds < lds_merge) lds = lds_merge;
+      if (lds < lds_merge) lds = lds_merge;  // (also covers the steady role's, at most 4 heads at a time)
       SideWork sw{ix.sizes, g.est_rows, g.est_chunks, g.steady_chunks, 0, units * g.est_chunks, ix.k_steady,
-                  ix.v_steady, ix.p, steady_stride(ix), 0, g.steady_rows, 0};
+                  ix.v_steady, ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows, 0};
+      const int n_side = sw.n_est_wgs + units * g.steady_chunks;
       if (g.list_filtered)
-        WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, FILT_NT, true>),
-                    heads + sw.n_est_wgs, FILT_NT, lds, st, WAVE_SELECT_ARGS,
+        WAVE_LAUNCH("select+estimate+steady", (select_estimate_kernel<T, D, G, FILT_NT, true>),
+                    heads + n_side, FILT_NT, lds, st, WAVE_SELECT_ARGS,
                     reinterpret_cast<const float*>(w + g.off_tile_max), lo, g.stage, heads, sw);
+      else if (nt == 128)
+        WAVE_LAUNCH("select+estimate+steady", (select_estimate_kernel<T, D, G, 128, false>),
+                    heads + n_side, 128, lds, st, WAVE_SELECT_ARGS,
+                    static_cast<const float*>(nullptr), lo, g.stage, heads, sw);
       else
-        WAVE_LAUNCH("select+estimate", (select_estimate_kernel<T, D, G, DIRECT_NT, false>),
-                    heads + sw.n_est_wgs, DIRECT_NT, lds, st, WAVE_SELECT_ARGS,
+        WAVE_LAUNCH("select+estimate+steady", (select_estimate_kernel<T, D, G, 256, false>),
+                    heads + n_side, 256, lds, st, WAVE_SELECT_ARGS,
                     static_cast<const float*>(nullptr), lo, g.stage, heads, sw);
       WAVE_LAUNCH("gather", (gather_list_kernel<T, D>), g.gather_wgs, 256, 0, st, q,
                   static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, lo,
