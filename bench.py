@@ -449,11 +449,11 @@ def index_update_phase(wb, wl, ix, K, V, ms_per_step, dev):
         assert ix2.m == ix.m + U_UPD // 16 and ix2.n_local == wl.n_local
         del ix2
         torch.cuda.empty_cache()
-    # the same with room for the new rows in the permuted key/value arrays (row_capacity): the
-    # rows are added in place and only the meta index and the steady rows are rewritten
+    # the same with room for the new rows and clusters (row_capacity, cluster_capacity): they are
+    # added in place and only the steady rows are rewritten
     ixc = wb.alloc_index(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
                          wl.segment_len, wl.clusters_per_segment, dev, row_capacity=ix.N_idx + U_UPD,
-                         steady_capacity=ix.p + U_UPD)
+                         steady_capacity=ix.p + U_UPD, cluster_capacity=ix.m + U_UPD // 16)
     bws3 = wb.workspace(ixc.build_ws_bytes, dev)
     wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
                         wl.iters, 0, ws=bws3, index=ixc)
@@ -469,6 +469,7 @@ def index_update_phase(wb, wl, ix, K, V, ms_per_step, dev):
         torch.cuda.synchronize()
         upd_cap_ms.append(e0.elapsed_time(e1))
         assert ix2.k_perm.data_ptr() == ixc.k_perm.data_ptr() and ix2.m == ix.m + U_UPD // 16
+        assert ix2.centroids.data_ptr() == ixc.centroids.data_ptr()
         del ix2
     # one new token per sequence (a decode step's own key and value): with room in the steady
     # buffers its rows go behind the window and nothing else is touched
@@ -492,8 +493,9 @@ def index_update_phase(wb, wl, ix, K, V, ms_per_step, dev):
         "rows_in_place": {
             "ms": round(_median(upd_cap_ms), 3),
             "share_of_the_decode_steps_it_follows": round(_median(upd_cap_ms) / (U_UPD * ms_per_step), 5),
-            "note": "row_capacity leaves room in perm / k_perm / v_perm: new rows go behind the old "
-                    "ones, only the meta index and the steady rows are rewritten"},
+            "note": "row_capacity and cluster_capacity leave room in perm / k_perm / v_perm and in the "
+                    "meta-index arrays: the new rows and clusters go behind the old ones, only the steady "
+                    "rows are rewritten"},
         "one_token_in_place": {
             "ms": round(_median(tok_ms), 4),
             "share_of_a_decode_step": round(_median(tok_ms) / ms_per_step, 4),

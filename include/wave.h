@@ -80,6 +80,8 @@ typedef struct {
   int32_t *sizes;               /* DEVICE [B,Hkv,m]     0 = empty cluster              */
   int32_t *offsets;             /* DEVICE [B,Hkv,m+1]   rows of cluster c in k_perm /  */
                                 /*        v_perm are [offsets[c], offsets[c+1])        */
+                                /*        (with cluster_capacity > 0 these four have   */
+                                /*        cluster_capacity (+ 1) entries per unit)     */
   int32_t *perm;                /* DEVICE [B,Hkv,N_idx] original position of each row  */
   void *k_perm, *v_perm;        /* DEVICE [B,Hkv,N_idx,d] dtype, rows ordered by       */
                                 /*        (segment, cluster, original position); with  */
@@ -96,6 +98,12 @@ typedef struct {
                                 /* 0 means N_idx (dense); a larger value, set by the    */
                                 /* caller before wave_index_plan, leaves room for       */
                                 /* wave_index_append to add rows in place               */
+  int32_t cluster_capacity;     /* clusters allocated per unit in centroids, vsum, sizes */
+                                /* (and + 1 entries in offsets): 0 means m (dense); a    */
+                                /* larger value, set by the caller before                */
+                                /* wave_index_plan, leaves room for wave_index_append to */
+                                /* add clusters in place; the first m (m + 1) entries of */
+                                /* a unit are in use                                     */
 } wave_index;
 
 enum { WAVE_INDEX_BUFFERS = 9 };
@@ -134,12 +142,16 @@ wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
  * -- may name old_ix's own seven arrays of the clustered part, which are then
  * left as they are; and perm, k_perm, v_perm may be old_ix's when both indexes
  * have the same row_capacity >= the new N_idx: the new rows are then written
- * behind the old ones in place and old_ix stays valid; likewise k_steady and
+ * behind the old ones in place and old_ix stays valid; centroids, vsum, sizes
+ * and offsets may be old_ix's when both indexes have the same cluster_capacity
+ * >= the new m: the new clusters are then written behind the old ones in place
+ * (an update of 1K tokens then writes its 64 clusters and 1K rows per unit and
+ * copies nothing that was indexed before); likewise k_steady and
  * v_steady may be old_ix's when no segment is flushed and both indexes have
  * the same steady_capacity >= the new p: only the new tokens' rows are then
  * written, behind the old window); workspace DEVICE, 256-byte aligned.  The
- * plan keeps old_ix's row_capacity and steady_capacity while the grown index
- * fits in them and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
+ * plan keeps old_ix's row_capacity, cluster_capacity and steady_capacity while
+ * the grown index fits in them and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
  * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
 wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,
                                    int update_segment_len, int update_clusters, wave_index *new_ix,

@@ -44,7 +44,8 @@ class wave_index(ctypes.Structure):
                 ("v_perm", ctypes.c_void_p), ("k_steady", ctypes.c_void_p),
                 ("v_steady", ctypes.c_void_p),
                 ("appended_segments", ctypes.c_int32), ("update_segment_len", ctypes.c_int32),
-                ("update_clusters", ctypes.c_int32), ("row_capacity", ctypes.c_int32)]
+                ("update_clusters", ctypes.c_int32), ("row_capacity", ctypes.c_int32),
+                ("cluster_capacity", ctypes.c_int32)]
 
 
 class WaveError(RuntimeError):
@@ -136,7 +137,8 @@ class Index:
     def __getattr__(self, name):
         if name in ("B", "Hkv", "d", "N", "n_sink", "n_local", "segment_len",
                     "clusters_per_segment", "S", "m", "N_idx", "p", "appended_segments",
-                    "update_segment_len", "update_clusters", "row_capacity", "steady_capacity"):
+                    "update_segment_len", "update_clusters", "row_capacity", "steady_capacity",
+                    "cluster_capacity"):
             return getattr(self.c, name)
         if name in BUFFER_NAMES:
             return self.t[name]
@@ -147,21 +149,23 @@ def _shapes(c: wave_index) -> Dict[str, Tuple[int, ...]]:
     u = (c.B, c.Hkv)
     rows = c.row_capacity if c.row_capacity > 0 else c.N_idx   # the first N_idx rows are in use
     prow = c.steady_capacity if c.steady_capacity > 0 else c.p  # the first p rows are in use
-    return {"centroids": u + (c.m, c.d), "vsum": u + (c.m, c.d), "sizes": u + (c.m,),
-            "offsets": u + (c.m + 1,), "perm": u + (rows,), "k_perm": u + (rows, c.d),
+    mc = c.cluster_capacity if c.cluster_capacity > 0 else c.m   # the first m clusters are in use
+    return {"centroids": u + (mc, c.d), "vsum": u + (mc, c.d), "sizes": u + (mc,),
+            "offsets": u + (mc + 1,), "perm": u + (rows,), "k_perm": u + (rows, c.d),
             "v_perm": u + (rows, c.d), "k_steady": u + (prow, c.d), "v_steady": u + (prow, c.d)}
 
 
 def wave_index_plan(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
                     segment_len: int, clusters_per_segment: int, Hq: Optional[int] = None,
-                    topk_clusters: int = 0, row_capacity: int = 0, steady_capacity: int = 0
-                    ) -> Tuple[wave_index, List[int], int, Optional[int]]:
+                    topk_clusters: int = 0, row_capacity: int = 0, steady_capacity: int = 0,
+                    cluster_capacity: int = 0) -> Tuple[wave_index, List[int], int, Optional[int]]:
     """Returns (struct with derived fields, byte sizes of the nine buffers,
     build workspace bytes, decode workspace bytes or None)."""
     c = wave_index()
     c.dtype, c.B, c.Hkv, c.d, c.N = _dtype_code(dtype), B, Hkv, d, N
     c.n_sink, c.n_local, c.segment_len, c.clusters_per_segment = n_sink, n_local, segment_len, clusters_per_segment
     c.row_capacity, c.steady_capacity = row_capacity, steady_capacity
+    c.cluster_capacity = cluster_capacity
     sizes = (ctypes.c_size_t * WAVE_INDEX_BUFFERS)()
     bws, dws = ctypes.c_size_t(0), ctypes.c_size_t(0)
     st = lib().wave_index_plan(ctypes.byref(c), sizes, ctypes.byref(bws), Hq or 0, topk_clusters,
@@ -173,12 +177,13 @@ def wave_index_plan(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink
 
 def alloc_index(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
                 segment_len: int, clusters_per_segment: int, device="cuda",
-                row_capacity: int = 0, steady_capacity: int = 0) -> Index:
+                row_capacity: int = 0, steady_capacity: int = 0, cluster_capacity: int = 0) -> Index:
     """Plans and allocates an empty index on the device (row_capacity > 0: room for that many
-    permuted rows per unit, so that index updates can add rows in place)."""
+    permuted rows per unit, cluster_capacity > 0: for that many clusters per unit, so that
+    index updates can add rows and clusters in place)."""
     c, sizes, bws, _ = wave_index_plan(dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
                                        clusters_per_segment, row_capacity=row_capacity,
-                                       steady_capacity=steady_capacity)
+                                       steady_capacity=steady_capacity, cluster_capacity=cluster_capacity)
     tensors = {}
     for name, nbytes in zip(BUFFER_NAMES, sizes):
         dt = torch.int32 if name in ("sizes", "offsets", "perm") else dtype
@@ -196,7 +201,7 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
 def wave_index_build(K: torch.Tensor, V: torch.Tensor, n_sink: int, n_local: int, segment_len: int,
                      clusters_per_segment: int, iters: int, seed: int,
                      ws: Optional[torch.Tensor] = None, index: Optional[Index] = None,
-                     row_capacity: int = 0, steady_capacity: int = 0) -> Index:
+                     row_capacity: int = 0, steady_capacity: int = 0, cluster_capacity: int = 0) -> Index:
     """K, V: [B, Hkv, N, d] device tensors (f32 or bf16).  Enqueues the build on
     the current stream and returns the index (valid after a stream sync)."""
     assert K.is_cuda and V.is_cuda and K.shape == V.shape and K.dtype == V.dtype
@@ -204,7 +209,7 @@ def wave_index_build(K: torch.Tensor, V: torch.Tensor, n_sink: int, n_local: int
     B, Hkv, N, d = K.shape
     ix = index or alloc_index(K.dtype, B, Hkv, d, N, n_sink, n_local, segment_len,
                               clusters_per_segment, K.device, row_capacity=row_capacity,
-                              steady_capacity=steady_capacity)
+                              steady_capacity=steady_capacity, cluster_capacity=cluster_capacity)
     if ws is None:
         ws = workspace(ix.build_ws_bytes, K.device)
     st = lib().wave_index_build(K.data_ptr(), V.data_ptr(), ctypes.byref(ix.c), iters, seed,
@@ -239,12 +244,14 @@ def wave_index_append(ix: Index, K_new: Optional[torch.Tensor], V_new: Optional[
     tensors = {}
     keep = c.appended_segments == ix.c.appended_segments   # nothing flushed: the clustered part is shared
     in_place = c.row_capacity > 0 and c.row_capacity == ix.c.row_capacity   # rows added behind the old ones
+    meta_in_place = c.cluster_capacity > 0 and c.cluster_capacity == ix.c.cluster_capacity   # clusters likewise
     for name, nbytes in zip(BUFFER_NAMES, sizes):
         dt = torch.int32 if name in ("sizes", "offsets", "perm") else ix.dtype
         steady_in_place = (keep and c.steady_capacity > 0 and c.steady_capacity == ix.c.steady_capacity
                            and name in ("k_steady", "v_steady"))   # the new tokens' rows behind the window
         if ((keep and name not in ("k_steady", "v_steady")) or steady_in_place
-                or (in_place and name in ("perm", "k_perm", "v_perm"))):
+                or (in_place and name in ("perm", "k_perm", "v_perm"))
+                or (meta_in_place and name in ("centroids", "vsum", "sizes", "offsets"))):
             t = ix.t[name]
         else:
             t = torch.empty(_shapes(c)[name], dtype=dt, device=device)

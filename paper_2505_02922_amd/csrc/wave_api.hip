@@ -107,6 +107,7 @@ static wave_status check_dims(const wave_index* ix) {
   if (ix->d != 64 && ix->d != 128) return WAVE_ERR_SHAPE;
   if (ix->clusters_per_segment > WAVE_MAX_CLUSTERS_PER_SEGMENT) return WAVE_ERR_SHAPE;
   if (ix->appended_segments < 0 || ix->row_capacity < 0 || ix->steady_capacity < 0) return WAVE_ERR_ARG;
+  if (ix->cluster_capacity < 0) return WAVE_ERR_ARG;
   if (ix->appended_segments > 0) {
     if (ix->update_segment_len < 1 || ix->update_clusters < 1) return WAVE_ERR_ARG;
     if (ix->update_clusters > WAVE_MAX_CLUSTERS_PER_SEGMENT) return WAVE_ERR_SHAPE;
@@ -143,6 +144,7 @@ static bool planned_fields_match(const wave_index& ix) {
   const Derived d = derive(ix);
   if (ix.row_capacity > 0 && ix.row_capacity < d.N_idx) return false;
   if (ix.steady_capacity > 0 && ix.steady_capacity < d.p) return false;
+  if (ix.cluster_capacity > 0 && ix.cluster_capacity < d.m) return false;
   return ix.S == d.S && ix.m == d.m && ix.N_idx == d.N_idx && ix.p == d.p;
 }
 
@@ -161,8 +163,10 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   if (st != WAVE_OK) return st;
   if (!bytes) return WAVE_ERR_ARG;
   const Derived d = derive(*ix);
-  if ((long long)ix->B * ix->Hkv * ((long long)d.m + 1) >= (1ll << 31)) return WAVE_ERR_SHAPE;
   if (d.m < 0 || (ix->row_capacity > 0 && ix->row_capacity < d.N_idx)) return WAVE_ERR_SHAPE;
+  if (ix->cluster_capacity > 0 && ix->cluster_capacity < d.m) return WAVE_ERR_SHAPE;
+  const size_t mcap = ix->cluster_capacity > 0 ? (size_t)ix->cluster_capacity : (size_t)d.m;
+  if ((long long)ix->B * ix->Hkv * ((long long)mcap + 1) >= (1ll << 31)) return WAVE_ERR_SHAPE;
   if (ix->steady_capacity > 0 && ix->steady_capacity < d.p) return WAVE_ERR_SHAPE;
   ix->S = d.S;
   ix->m = d.m;
@@ -170,10 +174,10 @@ wave_status wave_index_plan(wave_index* ix, size_t bytes[WAVE_INDEX_BUFFERS],
   ix->p = d.p;
   const size_t es = ix->dtype == WAVE_BF16 ? 2 : 4;
   const size_t units = (size_t)ix->B * ix->Hkv;
-  bytes[0] = units * d.m * ix->d * es;
-  bytes[1] = units * d.m * ix->d * es;
-  bytes[2] = units * d.m * sizeof(int32_t);
-  bytes[3] = units * ((size_t)d.m + 1) * sizeof(int32_t);
+  bytes[0] = units * mcap * ix->d * es;
+  bytes[1] = units * mcap * ix->d * es;
+  bytes[2] = units * mcap * sizeof(int32_t);
+  bytes[3] = units * (mcap + 1) * sizeof(int32_t);
   const size_t rows = ix->row_capacity > 0 ? (size_t)ix->row_capacity : (size_t)d.N_idx;
   bytes[4] = units * rows * sizeof(int32_t);
   bytes[5] = units * rows * ix->d * es;
@@ -289,6 +293,7 @@ static wave_status plan_append(const wave_index* old_ix, int n_new, int n_local_
   nw.update_clusters = k_u;
   if ((long long)old_ix->N_idx + (long long)g.F * U > old_ix->row_capacity) nw.row_capacity = 0;
   if (old_ix->n_sink + nw.n_local > old_ix->steady_capacity) nw.steady_capacity = 0;
+  if ((long long)old_ix->m + (long long)g.F * g.ks > old_ix->cluster_capacity) nw.cluster_capacity = 0;
   *out = nw;
   return WAVE_OK;
 }
@@ -338,8 +343,9 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
     const void* b[7] = {new_ix->centroids, new_ix->vsum, new_ix->sizes, new_ix->offsets, new_ix->perm,
                         new_ix->k_perm, new_ix->v_perm};
     const bool in_place = new_ix->row_capacity > 0 && new_ix->row_capacity == old_ix->row_capacity;
+    const bool meta_in_place = new_ix->cluster_capacity > 0 && new_ix->cluster_capacity == old_ix->cluster_capacity;
     for (int i = 0; i < 7; ++i)
-      if (g.F > 0 && a[i] && a[i] == b[i] && !(in_place && i >= 4)) return WAVE_ERR_ARG;
+      if (g.F > 0 && a[i] && a[i] == b[i] && !(i >= 4 ? in_place : meta_in_place)) return WAVE_ERR_ARG;
     const bool steady_in_place = g.F == 0 && new_ix->steady_capacity > 0 &&
                                  new_ix->steady_capacity == old_ix->steady_capacity;
     if (old_ix->k_steady && !steady_in_place &&

@@ -112,15 +112,15 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
   const int ns = o.n_sink;                  // old N >= n_sink was checked
   char* w = static_cast<char*>(ws);
 
-  // (1) the old index at the new strides
-  copy_units<uint4>(nw.centroids, o.centroids, (size_t)o.m * rowc, (size_t)nw.m * rowc, (size_t)o.m * rowc, 0, units, st);
-  copy_units<uint4>(nw.vsum, o.vsum, (size_t)o.m * rowc, (size_t)nw.m * rowc, (size_t)o.m * rowc, 0, units, st);
-  copy_units<int32_t>(nw.sizes, o.sizes, (size_t)o.m, (size_t)nw.m, (size_t)o.m, 0, units, st);
+  // (1) the old index at the new strides (arrays that are the old ones stay as they are)
+  const size_t cs_new = (size_t)cluster_stride(nw), cs_old = (size_t)cluster_stride(o);  // clusters per unit
+  copy_units<uint4>(nw.centroids, o.centroids, (size_t)o.m * rowc, cs_new * rowc, cs_old * rowc, 0, units, st);
+  copy_units<uint4>(nw.vsum, o.vsum, (size_t)o.m * rowc, cs_new * rowc, cs_old * rowc, 0, units, st);
+  copy_units<int32_t>(nw.sizes, o.sizes, (size_t)o.m, cs_new, cs_old, 0, units, st);
   if (o.offsets)
-    copy_units<int32_t>(nw.offsets, o.offsets, (size_t)o.m + 1, (size_t)nw.m + 1, (size_t)o.m + 1, 0, units, st);
+    copy_units<int32_t>(nw.offsets, o.offsets, (size_t)o.m + 1, cs_new + 1, cs_old + 1, 0, units, st);
   else if (nw.offsets)  // no clusters before and no array for them: the first offset of every unit is 0
-    WAVE_LAUNCH("append_copy", set_first_kernel, grid_for(units), 256, 0, st, nw.offsets,
-                (size_t)nw.m + 1, units);
+    WAVE_LAUNCH("append_copy", set_first_kernel, grid_for(units), 256, 0, st, nw.offsets, cs_new + 1, units);
   const size_t rs_new = (size_t)row_stride(nw), rs_old = (size_t)row_stride(o);  // rows per unit
   copy_units<int32_t>(nw.perm, o.perm, (size_t)o.N_idx, rs_new, rs_old, 0, units, st);
   copy_units<uint4>(nw.k_perm, o.k_perm, (size_t)o.N_idx * rowc, rs_new * rowc, rs_old * rowc, 0, units, st);
@@ -161,12 +161,12 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
   if (bs != WAVE_OK) return bs;
 
   // (4) appended behind the old clusters and rows
-  copy_units<uint4>(nw.centroids, mi.centroids, (size_t)mi.m * rowc, (size_t)nw.m * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
-  copy_units<uint4>(nw.vsum, mi.vsum, (size_t)mi.m * rowc, (size_t)nw.m * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
-  copy_units<int32_t>(nw.sizes, mi.sizes, (size_t)mi.m, (size_t)nw.m, (size_t)mi.m, (size_t)o.m, units, st);
+  copy_units<uint4>(nw.centroids, mi.centroids, (size_t)mi.m * rowc, cs_new * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
+  copy_units<uint4>(nw.vsum, mi.vsum, (size_t)mi.m * rowc, cs_new * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
+  copy_units<int32_t>(nw.sizes, mi.sizes, (size_t)mi.m, cs_new, (size_t)mi.m, (size_t)o.m, units, st);
   // offsets[o.m + 1 + i] = old rows + mini offsets[i + 1]
   WAVE_LAUNCH("append_copy", copy_units_add_kernel, grid_for((size_t)mi.m * units), 256, 0, st, nw.offsets,
-              mi.offsets, (size_t)mi.m, (size_t)nw.m + 1, (size_t)mi.m + 1, (size_t)o.m + 1, (size_t)1, units,
+              mi.offsets, (size_t)mi.m, cs_new + 1, (size_t)mi.m + 1, (size_t)o.m + 1, (size_t)1, units,
               o.N_idx);
   // positions: window row w is token (old N - old local count) + w
   WAVE_LAUNCH("append_copy", copy_units_add_kernel, grid_for((size_t)mi.N_idx * units), 256, 0, st, nw.perm,

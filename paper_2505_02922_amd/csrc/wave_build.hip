@@ -13,6 +13,8 @@
 //               sort    (stable counting sort of the segment's points by cluster)
 //               update  (centroid = quant(member sum / |member sum|), fp64)
 //   finalize    sizes, offsets, mean of raw keys, value sums, permuted K/V rows
+#include <stdlib.h>
+
 #include "wave_common.h"
 
 namespace wave {
@@ -326,36 +328,37 @@ __global__ __launch_bounds__(64 * NW) void assign_mfma_kernel(
 // ~136 KiB) and then every wave works through fragments of 32 * NF points on
 // its own: no barrier and no global centroid traffic inside the loop.
 // ============================================================================
-template <int D, int NF, int NW>
-__global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
-    const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
-    int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
-    int pieces_per_seg) {
-  constexpr int KS = D / 16;            // MFMA k-steps per tile
-  constexpr int ROWB = D * 2 + 16;      // LDS row pitch: 16 B pad keeps 16 lanes on 64 distinct banks
-  constexpr int CPR = D / 8;            // 16-byte chunks per centroid row
-  extern __shared__ __attribute__((aligned(16))) char cent[];  // 32 * ceil(k_s / 32) rows
+template <int D>
+struct ResidentTile {
+  static constexpr int KS = D / 16;        // MFMA k-steps per tile
+  static constexpr int ROWB = D * 2 + 16;  // LDS row pitch: 16 B pad keeps 16 lanes on 64 distinct banks
+  static constexpr int CPR = D / 8;        // 16-byte chunks per centroid row
+};
 
-  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int sg = wg / pieces_per_seg, piece = wg - sg * pieces_per_seg;
-  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
-  const int nfrag = (si.L_s + 31) / 32;
-  const int per = ((nfrag + pieces_per_seg - 1) / pieces_per_seg + NF - 1) / NF * NF;
-  const int f_lo = piece * per, f_hi = min(nfrag, f_lo + per);
-  if (f_lo >= f_hi) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int half = lane >> 5, col = lane & 31;
-  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
-  const bf16_t* Cs = chat + (size_t)sg * kk * D;
-  const int ntiles = (si.k_s + 31) / 32;
-
-  for (int id = tid; id < 32 * ntiles * CPR; id += 64 * NW) {
-    const int row = id / CPR, ch = id - row * CPR;
-    store16(cent + row * ROWB + ch * 16, load16(Cs + (size_t)min(row, si.k_s - 1) * D + ch * 8));
+// The segment's k_s centroid rows into the padded LDS tiles (rows beyond k_s repeat the
+// last one; the epilogue ignores them).  All NT threads call this; the caller's barrier follows.
+template <int D, int NT>
+__device__ __forceinline__ void resident_load_centroids(const bf16_t* Cs, int k_s, char* cent) {
+  using RT = ResidentTile<D>;
+  const int ntiles = (k_s + 31) / 32;
+  for (int id = threadIdx.x; id < 32 * ntiles * RT::CPR; id += NT) {
+    const int row = id / RT::CPR, ch = id - row * RT::CPR;
+    store16(cent + row * RT::ROWB + ch * 16, load16(Cs + (size_t)min(row, k_s - 1) * D + ch * 8));
   }
-  __syncthreads();
+}
 
-  const int nfull = si.k_s / 32;  // tiles without rows beyond k_s
+// Wave `wave` of NW takes the fragments f_lo + wave * NF, + NW * NF, ... below f_hi of the
+// segment's points X against the centroids in `cent`; emit(point, cluster, near_tie) is
+// called once per point by the lane that holds it.
+template <int D, int NF, int NW, typename Emit>
+__device__ __forceinline__ void resident_assign_fragments(const bf16_t* X, const char* cent, int L_s, int k_s,
+                                                          int f_lo, int f_hi, Emit&& emit) {
+  using RT = ResidentTile<D>;
+  constexpr int KS = RT::KS, ROWB = RT::ROWB;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int ntiles = (k_s + 31) / 32;
+  const int nfull = k_s / 32;  // tiles without rows beyond k_s
   constexpr float B0 = kAssignBias;
   floatx16 bias = {B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0};
   asm volatile("" : "+v"(bias));  // kept in registers: one accumulator-start operand for every tile
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
     uint4 bfrag[NF][KS];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-      const int row = min(32 * (fb + f) + col, si.L_s - 1);
+      const int row = min(32 * (fb + f) + col, L_s - 1);
 #pragma unroll
       for (int s = 0; s < KS; ++s) bfrag[f][s] = load16(X + (size_t)row * D + (2 * s + half) * 8);
     }
@@ -400,24 +403,24 @@ __global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
       int t = 1;
       for (; t + 1 < nfull; t += 2) {
         mfma_tile(t, accB);
-        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, k_s);
         interleave();
         mfma_tile(t + 1, accA);
-        assign_epilogue<NF, false>(accB, best, second, btile, t, half, si.k_s);
+        assign_epilogue<NF, false>(accB, best, second, btile, t, half, k_s);
         interleave();
       }
       if (t < nfull) {
         mfma_tile(t, accB);
-        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, k_s);
         interleave();
-        assign_epilogue<NF, false>(accB, best, second, btile, t, half, si.k_s);
+        assign_epilogue<NF, false>(accB, best, second, btile, t, half, k_s);
       } else {
-        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, si.k_s);
+        assign_epilogue<NF, false>(accA, best, second, btile, t - 1, half, k_s);
       }
     }
     if (nfull < ntiles) {  // the last tile has rows beyond k_s
       mfma_tile(nfull, accA);
-      assign_epilogue<NF, true>(accA, best, second, btile, nfull, half, si.k_s);
+      assign_epilogue<NF, true>(accA, best, second, btile, nfull, half, k_s);
     }
     // lanes l and l ^ 32 hold the same points over disjoint centroid rows
 #pragma unroll
@@ -432,14 +435,37 @@ __global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
         brow = orow;
       }
       const int point = 32 * (fb + f) + col;
-      if (half == 0 && fb + f < f_hi && point < si.L_s) {
-        const size_t gp = (size_t)si.unit * N_idx + si.seg_start + point;
-        assign[gp] = btile[f] * 32 + brow;
+      if (half == 0 && fb + f < f_hi && point < L_s) {
         const float gap = __int_as_float(best[f]) - (nsec > 0 ? __int_as_float(nsec) : 0.f);
-        if (gap < kAssignGuard) flag_list[atomicAdd(flag_count, 1)] = (int32_t)gp;
+        emit(point, btile[f] * 32 + brow, gap < kAssignGuard);
       }
     }
   }
+}
+
+template <int D, int NF, int NW>
+__global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
+    const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
+    int32_t* __restrict__ flag_list, int32_t* __restrict__ flag_count, int S, int L, int kk, int N_idx,
+    int pieces_per_seg) {
+  extern __shared__ __attribute__((aligned(16))) char cent[];  // 32 * ceil(k_s / 32) rows
+
+  const int wg = xcd_logical_block(blockIdx.x, gridDim.x);
+  const int sg = wg / pieces_per_seg, piece = wg - sg * pieces_per_seg;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int nfrag = (si.L_s + 31) / 32;
+  const int per = ((nfrag + pieces_per_seg - 1) / pieces_per_seg + NF - 1) / NF * NF;
+  const int f_lo = piece * per, f_hi = min(nfrag, f_lo + per);
+  if (f_lo >= f_hi) return;
+  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
+  resident_load_centroids<D, 64 * NW>(chat + (size_t)sg * kk * D, si.k_s, cent);
+  __syncthreads();
+  const size_t gp0 = (size_t)si.unit * N_idx + si.seg_start;
+  resident_assign_fragments<D, NF, NW>(X, cent, si.L_s, si.k_s, f_lo, f_hi,
+                                       [&](int point, int cluster, bool near_tie) {
+                                         assign[gp0 + point] = cluster;
+                                         if (near_tie) flag_list[atomicAdd(flag_count, 1)] = (int32_t)(gp0 + point);
+                                       });
 }
 
 // ============================================================================
@@ -571,25 +597,17 @@ __global__ __launch_bounds__(256) void refine_kernel(const T* __restrict__ xhat,
 // ============================================================================
 constexpr int SORT_HIST_INTS = 11264;  // LDS budget for the per-wave counters
 
-__global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ assign,
-                                                    int32_t* __restrict__ order,
-                                                    int32_t* __restrict__ count,
-                                                    int32_t* __restrict__ start,
-                                                    int32_t* __restrict__ flag_count, int S, int L,
-                                                    int kk, int N_idx, int key_bits) {
-  extern __shared__ int hist[];  // [W][kk], then kk ints of scan space
-  const int sg = blockIdx.x;
-  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+// One segment's points a[0, L_s) sorted into ord[] by the calling workgroup of W waves;
+// per-cluster counts and first positions to cnt[] / first[] (kk entries each).
+__device__ __forceinline__ void sort_segment(const int32_t* a, int32_t* ord, int32_t* cnt, int32_t* first,
+                                             int L_s, int kk, int key_bits, int* hist) {
   const int W = blockDim.x >> 6;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (sg == 0 && tid == 0) *flag_count = 0;  // the refine pass before this one has consumed it
-  const int32_t* a = assign + (size_t)si.unit * N_idx + si.seg_start;
-  int32_t* ord = order + (size_t)si.unit * N_idx + si.seg_start;
   int* tot = hist + W * kk;
   for (int i = tid; i < W * kk; i += blockDim.x) hist[i] = 0;
   __syncthreads();
-  const int stripe = (si.L_s + W - 1) / W;
-  const int s0 = min(si.L_s, wave * stripe), s1 = min(si.L_s, s0 + stripe);
+  const int stripe = (L_s + W - 1) / W;
+  const int s0 = min(L_s, wave * stripe), s1 = min(L_s, s0 + stripe);
   for (int i = s0 + lane; i < s1; i += 64) atomicAdd(&hist[wave * kk + a[i]], 1);
   __syncthreads();
   // per cluster: exclusive scan over the waves, total into tot[]
@@ -616,8 +634,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
         if (lane >= off) inc += t;
       }
       if (c < kk) {
-        count[(size_t)sg * kk + c] = v;
-        start[(size_t)sg * kk + c] = carry + inc - v;
+        cnt[c] = v;
+        first[c] = carry + inc - v;
         tot[c] = carry + inc - v;
       }
       carry += __shfl(inc, 63);
@@ -638,34 +656,42 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
       peers &= ((key >> bit) & 1) ? bal : ~bal;
     }
     const uint64_t below = peers & ((1ull << lane) - 1ull);
-    const int rank = __popcll(below), cnt = __popcll(peers);
+    const int rank = __popcll(below), cnt_l = __popcll(peers);
     if (on) {
       const int base = hist[wave * kk + key];
       ord[base + rank] = i;
       __builtin_amdgcn_wave_barrier();
-      if (rank == cnt - 1) hist[wave * kk + key] = base + cnt;
+      if (rank == cnt_l - 1) hist[wave * kk + key] = base + cnt_l;
     }
     __threadfence_block();
     __builtin_amdgcn_wave_barrier();
   }
 }
 
+__global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ assign,
+                                                    int32_t* __restrict__ order,
+                                                    int32_t* __restrict__ count,
+                                                    int32_t* __restrict__ start,
+                                                    int32_t* __restrict__ flag_count, int S, int L,
+                                                    int kk, int N_idx, int key_bits) {
+  extern __shared__ int hist[];  // [W][kk], then kk ints of scan space
+  const int sg = blockIdx.x;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  if (sg == 0 && threadIdx.x == 0) *flag_count = 0;  // the refine pass before this one has consumed it
+  sort_segment(assign + (size_t)si.unit * N_idx + si.seg_start, order + (size_t)si.unit * N_idx + si.seg_start,
+               count + (size_t)sg * kk, start + (size_t)sg * kk, si.L_s, kk, key_bits, hist);
+}
+
 // ============================================================================
 // Update: one group of LPR lanes per cluster sums its members' xhat in fp64.
 // ============================================================================
+// Cluster gc = sg * kk + c of segment si: the calling group of LPR lanes (lane `sub` of it)
+// sums the members' rows and writes the new centroid.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
-                                                     const int32_t* __restrict__ order,
-                                                     const int32_t* __restrict__ count,
-                                                     const int32_t* __restrict__ start, int S, int L,
-                                                     int kk, int N_idx, int nclusters) {
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
-  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-  const int gc = blockIdx.x * GROUPS + grp;  // sg * kk + c
-  if (gc >= nclusters) return;
-  const int sg = gc / kk, c = gc - sg * kk;
-  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
-  if (c >= si.k_s) return;
+__device__ __forceinline__ void update_cluster(const T* xhat, T* chat, const int32_t* order,
+                                               const int32_t* count, const int32_t* start,
+                                               const SegInfo& si, int gc, int N_idx, int sub) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC;
   const int n = count[gc], st = start[gc];
   if (n == 0) return;  // an empty cluster keeps its centroid
   const int32_t* ord = order + (size_t)si.unit * N_idx + si.seg_start + st;
@@ -705,6 +731,115 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   store16(chat + (size_t)gc * D + sub * EPC, *reinterpret_cast<uint4*>(o));
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
+                                                     const int32_t* __restrict__ order,
+                                                     const int32_t* __restrict__ count,
+                                                     const int32_t* __restrict__ start, int S, int L,
+                                                     int kk, int N_idx, int nclusters) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int gc = blockIdx.x * GROUPS + grp;  // sg * kk + c
+  if (gc >= nclusters) return;
+  const int sg = gc / kk, c = gc - sg * kk;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  if (c >= si.k_s) return;
+  update_cluster<T, D>(xhat, chat, order, count, start, si, gc, N_idx, sub);
+}
+
+// ============================================================================
+// Short segments (an index update's 1K tokens into 64 clusters; small builds): all T
+// iterations of one segment in ONE workgroup of 16 waves.  Per iteration: centroids
+// into LDS, assign (the resident MFMA form), near-ties re-decided with fp64
+// similarities by one wave each, the counting sort, the update; the steps are
+// those of the kernels above, separated by workgroup barriers instead of
+// launches (assignments, order and centroids still pass through global memory,
+// which one workgroup sees coherently).  Launches per build: 5 instead of 4 T + 3.
+// ============================================================================
+constexpr int SMALL_L_MAX = 2048;   // points per segment
+constexpr int SMALL_K_MAX = 128;    // clusters per segment
+constexpr int SMALL_NW = 16;
+
+template <int D>
+inline size_t small_kmeans_lds(int kk) {
+  return (size_t)32 * ((kk + 31) / 32) * ResidentTile<D>::ROWB + sizeof(int) * ((size_t)SMALL_NW * kk + kk) +
+         sizeof(int) * SMALL_L_MAX;
+}
+
+template <int D>
+__global__ __launch_bounds__(64 * SMALL_NW) void kmeans_small_kernel(
+    const bf16_t* __restrict__ xhat, bf16_t* chat, int32_t* assign, int32_t* order, int32_t* count,
+    int32_t* start, int S, int L, int kk, int N_idx, int iters, int key_bits) {
+  using RT = ResidentTile<D>;
+  constexpr int NT = 64 * SMALL_NW, LPR = D / 8, GROUPS = NT / LPR;
+  extern __shared__ __attribute__((aligned(16))) char small_lds[];
+  char* cent = small_lds;
+  int* hist = reinterpret_cast<int*>(small_lds + (size_t)32 * ((kk + 31) / 32) * RT::ROWB);
+  int* flags = hist + SMALL_NW * kk + kk;
+  __shared__ int nflag;
+  const int sg = blockIdx.x;
+  const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
+  bf16_t* Cs = chat + (size_t)sg * kk * D;
+  int32_t* a = assign + (size_t)si.unit * N_idx + si.seg_start;
+  const int nfrag = (si.L_s + 31) / 32;
+  for (int t = 0; t < iters; ++t) {
+    resident_load_centroids<D, NT>(Cs, si.k_s, cent);
+    if (tid == 0) nflag = 0;
+    __syncthreads();
+    resident_assign_fragments<D, 1, SMALL_NW>(X, cent, si.L_s, si.k_s, 0, nfrag,
+                                              [&](int point, int cluster, bool near_tie) {
+                                                a[point] = cluster;
+                                                if (near_tie) flags[atomicAdd(&nflag, 1)] = point;
+                                              });
+    __syncthreads();
+    // near-ties: fp64 similarities in index order against the LDS copy of the centroids,
+    // ties to the lowest centroid (the arithmetic of refine_kernel)
+    const int nf = nflag;
+    for (int it = wave; it < nf; it += SMALL_NW) {
+      const int point = flags[it];
+      const bf16_t* xr = X + (size_t)point * D;
+      double bv = -1.0e300;
+      int bi = 0x7fffffff;
+      for (int c = lane; c < si.k_s; c += 64) {
+        const char* row = cent + (size_t)c * RT::ROWB;
+        double acc = 0.0;
+#pragma unroll 4
+        for (int e0 = 0; e0 < D; e0 += 8) {
+          float xf[8], cf[8];
+          unpack<bf16_t>(load16(xr + e0), xf);
+          unpack<bf16_t>(load16(row + e0 * 2), cf);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc = fma((double)xf[e], (double)cf[e], acc);
+        }
+        if (acc > bv) {  // c ascends within a lane, so strict > keeps the lowest index
+          bv = acc;
+          bi = c;
+        }
+      }
+      for (int off = 32; off >= 1; off >>= 1) {
+        const double ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) {
+          bv = ov;
+          bi = oi;
+        }
+      }
+      if (lane == 0) a[point] = bi;
+    }
+    __syncthreads();
+    sort_segment(a, order + (size_t)si.unit * N_idx + si.seg_start, count + (size_t)sg * kk,
+                 start + (size_t)sg * kk, si.L_s, kk, key_bits, hist);
+    __syncthreads();
+    if (t + 1 < iters) {
+      for (int c = tid / LPR; c < si.k_s; c += GROUPS)
+        update_cluster<bf16_t, D>(xhat, chat, order, count, start, si, sg * kk + c, N_idx, tid % LPR);
+      __syncthreads();
+    }
+  }
+}
+
 // ============================================================================
 // Finalize: sizes, offsets, mean of raw keys, value sums, permuted rows.
 // ============================================================================
@@ -714,7 +849,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     const int32_t* __restrict__ count, const int32_t* __restrict__ start, T* __restrict__ centroids,
     T* __restrict__ vsum, int32_t* __restrict__ sizes, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, T* __restrict__ k_perm, T* __restrict__ v_perm, int S, int L, int kk,
-    int N, int N_idx, int n_sink, int m, int nclusters, int row_stride) {
+    int N, int N_idx, int n_sink, int m, int mc, int nclusters, int row_stride) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   const int gc = blockIdx.x * GROUPS + grp;
@@ -728,9 +863,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(
   const size_t orow = (size_t)si.unit * row_stride;  // rows per unit in perm / k_perm / v_perm
   const int row0 = si.seg_start + st;
   if (sub == 0) {
-    sizes[(size_t)si.unit * m + cid] = n;
-    offsets[(size_t)si.unit * (m + 1) + cid] = row0;
-    if (cid == m - 1) offsets[(size_t)si.unit * (m + 1) + m] = N_idx;
+    sizes[(size_t)si.unit * mc + cid] = n;  // mc: clusters per unit in the meta-index arrays
+    offsets[(size_t)si.unit * (mc + 1) + cid] = row0;
+    if (cid == m - 1) offsets[(size_t)si.unit * (mc + 1) + m] = N_idx;
   }
   const int32_t* ord = order + urow + si.seg_start + st;
   const T* Ku = K + ((size_t)si.unit * N + n_sink + si.seg_start) * D + sub * EPC;
@@ -771,8 +906,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     oc[e] = quant_store<T>(n > 0 ? ka[e] / (double)n : 0.0);
     ov[e] = quant_store<T>(va[e]);
   }
-  store16(centroids + ((size_t)si.unit * m + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(oc));
-  store16(vsum + ((size_t)si.unit * m + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(ov));
+  store16(centroids + ((size_t)si.unit * mc + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(oc));
+  store16(vsum + ((size_t)si.unit * mc + cid) * D + sub * EPC, *reinterpret_cast<uint4*>(ov));
 }
 
 // Steady rows: the first ns and the last (N - local_start) tokens of every unit.
@@ -827,6 +962,13 @@ BuildGeom build_geometry(const wave_index& ix) {
   g.off_init = o;   o = align_up(o + (size_t)g.segs * ix.d * sizeof(double));  // segment means
   g.total = o;
   return g;
+}
+
+// WAVE_NO_SMALL_KMEANS=1 in the environment keeps short segments on the one-launch-per-step
+// kernels (the tests run both forms against the oracle).
+static bool no_small_kmeans() {
+  const char* e = getenv("WAVE_NO_SMALL_KMEANS");
+  return e && e[0] == '1';
 }
 
 static int key_bits_for(int kk) {
@@ -918,7 +1060,15 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
   const size_t sort_lds = ((size_t)W * kk + kk) * sizeof(int);
   const int kb = key_bits_for(kk);
   const int cl_grid = (ncl + GROUPS - 1) / GROUPS;
-  for (int t = 0; t < iters; ++t) {
+  bool small = false;
+  if constexpr (sizeof(T) == 2) {
+    const int Lmax = L < N_idx ? L : N_idx;
+    small = Lmax <= SMALL_L_MAX && kk <= SMALL_K_MAX && !no_small_kmeans();
+    if (small)
+      WAVE_LAUNCH("kmeans_small", (kmeans_small_kernel<D>), g.segs, 64 * SMALL_NW, small_kmeans_lds<D>(kk), st,
+                  xhat, chat, assign, order, count, start, S, L, kk, N_idx, iters, kb);
+  }
+  for (int t = 0; t < iters && !small; ++t) {
     launch_assign<T, D>(xhat, chat, assign, flag, nflag, S, L, kk, N_idx, g.segs, st);
     WAVE_LAUNCH("refine", (refine_kernel<T, D>), 1024, 256, 0, st, xhat, chat, assign, flag, nflag, S,
                 L, kk, N_idx);
@@ -931,7 +1081,7 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
               static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,
               static_cast<T*>(ix.k_perm), static_cast<T*>(ix.v_perm), S, L, kk, ix.N, N_idx, ns, ix.m,
-              ncl, row_stride(ix));
+              cluster_stride(ix), ncl, row_stride(ix));
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 

@@ -164,6 +164,8 @@ __device__ __forceinline__ int xcd_logical_block(int bid, int nblocks) {
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // rows per unit in perm / k_perm / v_perm
 inline int row_stride(const wave_index& ix) { return ix.row_capacity > 0 ? ix.row_capacity : ix.N_idx; }
+// clusters per unit in centroids / vsum / sizes (and + 1 entries in offsets)
+inline int cluster_stride(const wave_index& ix) { return ix.cluster_capacity > 0 ? ix.cluster_capacity : ix.m; }
 // rows per unit in k_steady / v_steady
 inline int steady_stride(const wave_index& ix) { return ix.steady_capacity > 0 ? ix.steady_capacity : ix.p; }
 

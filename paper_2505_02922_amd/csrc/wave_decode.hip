@@ -86,7 +86,7 @@ struct DenseLds {
 template <typename T, int D, int G, int NT, bool PREFETCH = false>
 __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* __restrict__ C,
                                              const int32_t* __restrict__ su, float* __restrict__ z,
-                                             int unit, int bh0, int m, int c0, int nrows,
+                                             int unit, int bh0, int m, int mc, int c0, int nrows,
                                              const DenseLds<T, D, G, NT>& lds,
                                              float* __restrict__ tile_max = nullptr) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64, GROUPS = NWV * RPW;
@@ -118,7 +118,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
       if (hj < G) v = load16(q + ((size_t)(bh0 + hj) * D + 32 * s2 + 8 * kb));
       qb[s2] = __builtin_bit_cast(bf16x8_t, v);
     }
-    const T* Cu = C + ((size_t)unit * m + c0) * D;
+    const T* Cu = C + ((size_t)unit * mc + c0) * D;
     const int lrow = lane / CPR, lch = lane % CPR;
     float cn2 = 0.f;
     const int ntile = (nrows + 15) / 16;
@@ -190,7 +190,7 @@ __device__ __forceinline__ void dense_scores(const T* __restrict__ q, const T* _
     float qf[G][EPC];
 #pragma unroll
     for (int g = 0; g < G; ++g) unpack<T>(load16(q + ((size_t)(bh0 + g) * D + sub * EPC)), qf[g]);
-    const T* Cu = C + ((size_t)unit * m + c0) * D + sub * EPC;
+    const T* Cu = C + ((size_t)unit * mc + c0) * D + sub * EPC;
     float cn2 = 0.f;  // per-lane maximum of its chunk's squared sum; summed over lanes below
     for (int c = grp; c < nrows; c += GROUPS * U) {
       uint4 raw[U];
@@ -248,7 +248,7 @@ __device__ __forceinline__ float dense_cn2(const DenseLds<T, D, G, NT>& lds) {
 // part_head0 + g * head_stride.  All NT threads call this.
 template <typename T, int D, int G, int NT>
 __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
-                                               const int32_t* __restrict__ su, int unit, int m, int c0,
+                                               const int32_t* __restrict__ su, int unit, int m, int mc, int c0,
                                                int nrows, float scale_log2,
                                                const DenseLds<T, D, G, NT>& lds,
                                                float* __restrict__ part_head0, size_t head_stride) {
@@ -260,7 +260,7 @@ __device__ __forceinline__ void dense_estimate(const T* __restrict__ vsum,
   const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
   float* zw = lds.zw;
   float* smem = lds.smem;
-  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+  const T* Vu = vsum + ((size_t)unit * mc + c0) * D + sub * EPC;
   // ---- B: weights relative to the range maximum -----------------------------------
   float zmax[G];
 #pragma unroll
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(256, 4) void dense_kernel(const T* __restrict__ q, 
                                                     const T* __restrict__ vsum,
                                                     const int32_t* __restrict__ sizes,
                                                     float* __restrict__ z, float* __restrict__ cn2part,
-                                                    int Hkv, int m, int chunks, int slots, int slot0,
+                                                    int Hkv, int m, int mc, int chunks, int slots, int slot0,
                                                     float scale_log2, float* __restrict__ part) {
   using Lds = DenseLds<T, D, G, 256>;
   __shared__ __attribute__((aligned(16))) char lds_raw[Lds::score_bytes];
@@ -379,11 +379,11 @@ __global__ __launch_bounds__(256, 4) void dense_kernel(const T* __restrict__ q, 
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int bh0 = b * Hq + h * G;
   const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-  const int32_t* su = sizes + (size_t)unit * m + c0;
-  dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+  const int32_t* su = sizes + (size_t)unit * mc + c0;
+  dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, mc, c0, nrows, lds);
   __syncthreads();
   if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
-  dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
+  dense_estimate<T, D, G, 256>(vsum, su, unit, m, mc, c0, nrows, scale_log2, lds,
                                part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
                                (size_t)slots * (D + 2));
 }
@@ -394,7 +394,7 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, const T* __restrict__ C,
                                                     const int32_t* __restrict__ sizes,
                                                     float* __restrict__ z, float* __restrict__ cn2part,
-                                                    int Hkv, int m, int chunks,
+                                                    int Hkv, int m, int mc, int chunks,
                                                     float* __restrict__ tile_max) {
   using Lds = DenseLds<T, D, G, 256>;
   __shared__ __attribute__((aligned(16))) char lds_raw[Lds::score_bytes];
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void score_kernel(const T* __restrict__ q, con
   const int b = unit / Hkv, h = unit - b * Hkv, Hq = Hkv * G;
   const int bh0 = b * Hq + h * G;
   const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-  dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
+  dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * mc + c0, z, unit, bh0, m, mc, c0, nrows, lds,
                                    sizeof(T) == 2 ? tile_max : nullptr);
   __syncthreads();
   if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
@@ -572,7 +572,7 @@ template <typename T, int D, int NT>
 __device__ __forceinline__ void select_streaming(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -582,7 +582,7 @@ __device__ __forceinline__ void select_streaming(
   const int unit = b * Hkv + hq / G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* zz = z + (size_t)bh * m;
-  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const int32_t* off = offsets + (size_t)unit * (mc + 1);
   int32_t* ids = sel_ids + (size_t)bh * rcap;
   int32_t* pref = sel_pref + (size_t)bh * (rcap + 1);
   int32_t* srow = sel_row + (size_t)bh * rcap;
@@ -720,7 +720,7 @@ __device__ __forceinline__ void select_streaming(
     } else {
       mode = 2;
       // exact fp64 scores of the candidates
-      const T* Cu = C + (size_t)unit * m * D;
+      const T* Cu = C + (size_t)unit * mc * D;
       for (int i = tid; i < n_cand; i += NT) {
         const T* row = Cu + (size_t)cand_id[i] * D;
         double acc = 0.0;
@@ -835,7 +835,7 @@ __device__ __forceinline__ void select_streaming(
     }
     __syncthreads();  // ids[] complete
     if (write_neg)
-      negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, min(nsel, rcap),
+      negative_partial<T, D, NT>(vsum + (size_t)unit * mc * D, off, zz, ids, min(nsel, rcap),
                                  nvalid > 0 ? zmax : 0.f, scale_log2,
                                  part + ((size_t)bh * slots + neg_slot) * (D + 2));
   }
@@ -845,12 +845,12 @@ template <typename T, int D, int NT>
 __global__ __launch_bounds__(NT) void select_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot) {
-  select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+  select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                              usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
                              vsum, scale_log2, part, slots, neg_slot, blockIdx.x);
 }
@@ -893,7 +893,7 @@ template <typename T, int D, int NT, int VPT, bool LDSK>
 __device__ __forceinline__ int select_core(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -906,7 +906,7 @@ __device__ __forceinline__ int select_core(
   const int unit = b * Hkv + hq / G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* zz = z + (size_t)bh * m;
-  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const int32_t* off = offsets + (size_t)unit * (mc + 1);
   int32_t* ids = view.ids_ptr ? view.ids_ptr : sel_ids + (size_t)bh * rcap;
   const int npos = view.npos;  // positions ranked here; position i is cluster cid(i)
   auto cid = [&](int i) { return view.idmap ? view.idmap[i] : view.id_base + i; };
@@ -1017,7 +1017,7 @@ __device__ __forceinline__ int select_core(
   uint64_t zc64[4] = {0, 0, 0, 0}, t64 = 0;
   int need_eq64 = 0;
   auto key64_of = [&](int i) -> uint64_t {
-    const T* rowp = C + ((size_t)unit * m + cid(i)) * D;
+    const T* rowp = C + ((size_t)unit * mc + cid(i)) * D;
     double acc = 0.0;
     for (int e = 0; e < D; ++e) acc = fma(to_f64(q[(size_t)bh * D + e]), to_f64(rowp[e]), acc);
     const uint64_t u = (uint64_t)__double_as_longlong(acc + 0.0);
@@ -1288,7 +1288,7 @@ __device__ __forceinline__ int select_core(
       mode = 2;  // the whole band is taken; no ranking needed
     } else {
       mode = 2;
-      const T* Cu = C + (size_t)unit * m * D;
+      const T* Cu = C + (size_t)unit * mc * D;
       for (int i = tid; i < n_cand; i += NT) {
         const T* rowp = Cu + (size_t)cid(cand_id[i]) * D;
         double acc = 0.0;
@@ -1447,7 +1447,7 @@ __device__ __forceinline__ int select_core(
   __syncthreads();
   WAVE_STAMP(trace, 15);
   if (!view.no_neg)
-    negative_partial<T, D, NT>(vsum + (size_t)unit * m * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
+    negative_partial<T, D, NT>(vsum + (size_t)unit * mc * D, off, zz, ids, nsel, nvalid > 0 ? zmax : 0.f,
                                scale_log2, part + ((size_t)bh * slots + neg_slot) * (D + 2));
   WAVE_STAMP(trace, 16);
   *ntok_out = carry;
@@ -1458,14 +1458,14 @@ template <typename T, int D, int NT, int VPT, bool LDSK>
 __global__ __launch_bounds__(NT) void select_cached_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
     float* __restrict__ part, int slots, int neg_slot) {
   extern __shared__ uint32_t dyn_keys[];  // NT * ceil(m / NT) keys when LDSK
   int ntok;
-  select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+  select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                                    usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out,
                                    user_selected, vsum, scale_log2, part, slots, neg_slot, blockIdx.x,
                                    dyn_keys, nullptr, nullptr, 0, &ntok,
@@ -1739,7 +1739,7 @@ __device__ __forceinline__ void gather_role(
     const T* __restrict__ v_perm, const int32_t* __restrict__ sel_ids,
     const int32_t* __restrict__ nsel_arr, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const T* __restrict__ vsum, int Hq, int Hkv,
-    int N_idx /* rows per unit in k_perm / v_perm */, int m, int rcap, int chunks, int slots,
+    int N_idx /* rows per unit in k_perm / v_perm */, int m, int mc, int rcap, int chunks, int slots,
     float scale_log2, int own_neg, float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
   const int wg = xcd_logical_block(block, nblocks);
@@ -1760,14 +1760,14 @@ __device__ __forceinline__ void gather_role(
   const int nsel = nsel_arr[bh];
   const int c_lo = (int)((long long)chunk * nsel / chunks), c_hi = (int)((long long)(chunk + 1) * nsel / chunks);
   const int32_t* ids = sel_ids + (size_t)bh * rcap;
-  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const int32_t* off = offsets + (size_t)unit * (mc + 1);
   const float* zz = z + (size_t)bh * m;
 
   AttnState<T, D, 1> st;
   st.init(q + (size_t)bh * D, sub, scale_log2);
   const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
   const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
-  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+  const T* VSu = vsum + (size_t)unit * mc * D + sub * EPC;
 
   for (int cb = c_lo; cb < c_hi; cb += GATHER_TILE) {
     const int nc = min(GATHER_TILE, c_hi - cb);
@@ -1842,10 +1842,10 @@ __global__ __launch_bounds__(256) void gather_kernel(
     const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
     const int32_t* __restrict__ sel_ids, const int32_t* __restrict__ nsel_arr,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int N_idx, int m, int rcap, int chunks, int slots, float scale_log2, int own_neg,
+    int Hq, int Hkv, int N_idx, int m, int mc, int rcap, int chunks, int slots, float scale_log2, int own_neg,
     float* __restrict__ part) {
   gather_role<T, D>(blockIdx.x, gridDim.x, q, k_perm, v_perm, sel_ids, nsel_arr, offsets, z, vsum, Hq, Hkv,
-                    N_idx, m, rcap, chunks, slots, scale_log2, own_neg, part);
+                    N_idx, m, mc, rcap, chunks, slots, scale_log2, own_neg, part);
 }
 
 // Estimation zone with a budget: the clusters of the (ascending) list ids2 that
@@ -1859,7 +1859,7 @@ __device__ __forceinline__ void est_gather_role(
     int block, const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
     const int32_t* __restrict__ ids1_all, const int32_t* __restrict__ nsel1_arr,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
+    int Hq, int Hkv, int m, int mc, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
     float* __restrict__ part) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW;
   const int bh = block / chunks, chunk = block - bh * chunks;
@@ -1877,9 +1877,9 @@ __device__ __forceinline__ void est_gather_role(
     for (int i = threadIdx.x; i < nsel1; i += 256) s_ids1[i] = ids1g[i];
   __syncthreads();
   const int32_t* ids1 = staged ? s_ids1 : ids1g;
-  const int32_t* off = offsets + (size_t)unit * (m + 1);
+  const int32_t* off = offsets + (size_t)unit * (mc + 1);
   const float* zz = z + (size_t)bh * m;
-  const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+  const T* VSu = vsum + (size_t)unit * mc * D + sub * EPC;
   const int c_lo = (int)((long long)chunk * nsel2 / chunks), c_hi = (int)((long long)(chunk + 1) * nsel2 / chunks);
   AttnState<T, D, 1> st;
   st.reset();
@@ -1932,9 +1932,9 @@ __global__ __launch_bounds__(256) void est_gather_kernel(
     const int32_t* __restrict__ ids2_all, const int32_t* __restrict__ nsel2_arr,
     const int32_t* __restrict__ ids1_all, const int32_t* __restrict__ nsel1_arr,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int m, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
+    int Hq, int Hkv, int m, int mc, int rcap2, int rcap1, int chunks, int slots, int slot0, float scale_log2,
     float* __restrict__ part) {
-  est_gather_role<T, D>(blockIdx.x, ids2_all, nsel2_arr, ids1_all, nsel1_arr, offsets, z, vsum, Hq, Hkv, m,
+  est_gather_role<T, D>(blockIdx.x, ids2_all, nsel2_arr, ids1_all, nsel1_arr, offsets, z, vsum, Hq, Hkv, m, mc,
                         rcap2, rcap1, chunks, slots, slot0, scale_log2, part);
 }
 
@@ -1947,15 +1947,15 @@ __global__ __launch_bounds__(256) void gather_est_kernel(
     const int32_t* __restrict__ ids1, const int32_t* __restrict__ nsel1,
     const int32_t* __restrict__ ids2, const int32_t* __restrict__ nsel2,
     const int32_t* __restrict__ offsets, const float* __restrict__ z, const T* __restrict__ vsum,
-    int Hq, int Hkv, int N_idx, int m, int rcap1, int rcap2, int gather_chunks, int est_chunks, int slots,
+    int Hq, int Hkv, int N_idx, int m, int mc, int rcap1, int rcap2, int gather_chunks, int est_chunks, int slots,
     int gather_slot0, int est_slot0, int n_est_wgs, float scale_log2, float* __restrict__ part) {
   if ((int)blockIdx.x < n_est_wgs) {
-    est_gather_role<T, D>(blockIdx.x, ids2, nsel2, ids1, nsel1, offsets, z, vsum, Hq, Hkv, m, rcap2, rcap1,
+    est_gather_role<T, D>(blockIdx.x, ids2, nsel2, ids1, nsel1, offsets, z, vsum, Hq, Hkv, m, mc, rcap2, rcap1,
                           est_chunks, slots, est_slot0, scale_log2, part);
     return;
   }
   gather_role<T, D>((int)blockIdx.x - n_est_wgs, (int)gridDim.x - n_est_wgs, q, k_perm, v_perm, ids1, nsel1,
-                    offsets, z, vsum, Hq, Hkv, N_idx, m, rcap1, gather_chunks, slots, scale_log2, 0,
+                    offsets, z, vsum, Hq, Hkv, N_idx, m, mc, rcap1, gather_chunks, slots, scale_log2, 0,
                     part + (size_t)gather_slot0 * (D + 2));
 }
 
@@ -1980,7 +1980,7 @@ template <typename T, int D, int NT, int VPT, bool LDSK>
 __global__ __launch_bounds__(NT) void select_gather_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -2033,7 +2033,7 @@ __global__ __launch_bounds__(NT) void select_gather_kernel(
   if (p > 0 && steady_first) steady_rows();
   int ntok;
   const int nsel = select_core<T, D, NT, VPT, LDSK>(
-      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids,
+      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc, usel_stride, sel_ids,
       sel_pref, sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots,
       neg_slot, bh, dyn_keys, s_pref, s_row, FUSED_STAGE, &ntok,
       SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr});
@@ -2134,7 +2134,7 @@ template <typename T, int D, int NT, int VPT>
 __global__ __launch_bounds__(NT) void select_two_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int mwords, uint32_t* __restrict__ bitmap, int r1, int rcap1, int32_t* __restrict__ ids1,
+    int m, int mwords, int mc, uint32_t* __restrict__ bitmap, int r1, int rcap1, int32_t* __restrict__ ids1,
     int32_t* __restrict__ nsel1, int32_t* __restrict__ user_selected, int r2, int rcap2,
     int32_t* __restrict__ ids2, int32_t* __restrict__ nsel2, const T* __restrict__ vsum, float scale_log2) {
   extern __shared__ uint32_t dyn_keys[];
@@ -2142,7 +2142,7 @@ __global__ __launch_bounds__(NT) void select_two_kernel(
   const bool second = blockIdx.x & 1;
   int ntok;
   select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, second ? r2 : r1,
-                                   second ? rcap2 : rcap1, mwords, second ? r2 : r1, second ? ids2 : ids1,
+                                   second ? rcap2 : rcap1, mwords, mc, second ? r2 : r1, second ? ids2 : ids1,
                                    nullptr, nullptr, bitmap, second ? nsel2 : nsel1,
                                    second ? nullptr : user_selected, vsum, scale_log2, nullptr, 0, 0, bh,
                                    dyn_keys, nullptr, nullptr, 0, &ntok,
@@ -2173,7 +2173,7 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void dense_steady_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const T* __restrict__ vsum,
     const int32_t* __restrict__ sizes, float* __restrict__ z, float* __restrict__ cn2part, int Hkv,
-    int m, int chunks, int slots, int slot0, float scale_log2, float* __restrict__ part,
+    int m, int mc, int chunks, int slots, int slot0, float scale_log2, float* __restrict__ part,
     int n_dense_wgs, const T* __restrict__ k_steady, const T* __restrict__ v_steady, int p,
     int p_stride, int steady_chunks, int steady_rows, int steady_slot0) {
   using Lds = DenseLds<T, D, G, 256>;
@@ -2188,11 +2188,11 @@ __global__ __launch_bounds__(256) void dense_steady_kernel(
     const int b = unit / Hkv, h = unit - b * Hkv;
     const int bh0 = b * Hq + h * G;
     const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-    const int32_t* su = sizes + (size_t)unit * m + c0;
-    dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, c0, nrows, lds);
+    const int32_t* su = sizes + (size_t)unit * mc + c0;
+    dense_scores<T, D, G, 256, true>(q, C, su, z, unit, bh0, m, mc, c0, nrows, lds);
     __syncthreads();
     if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
-    dense_estimate<T, D, G, 256>(vsum, su, unit, m, c0, nrows, scale_log2, lds,
+    dense_estimate<T, D, G, 256>(vsum, su, unit, m, mc, c0, nrows, scale_log2, lds,
                                  part + ((size_t)bh0 * slots + slot0 + chunk) * (D + 2),
                                  (size_t)slots * (D + 2));
     return;
@@ -2222,7 +2222,7 @@ struct SideWork {
 template <typename T, int D, int G, int NT>
 __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* __restrict__ q,
                                           const float* __restrict__ z, const T* __restrict__ vsum,
-                                          int Hq, int Hkv, int m, float scale_log2,
+                                          int Hq, int Hkv, int m, int mc, float scale_log2,
                                           float* __restrict__ part, int slots, char* lds_raw) {
   if (wg < sw.n_est_wgs) {
     // Estimation terms of sw.est_rows clusters of one unit for its G heads, as a
@@ -2241,7 +2241,7 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
     const int sub = lane % LPR, grp = wave * RPW + lane / LPR;
     AttnState<T, D, G> st;
     st.reset();  // the queries are not needed: the scores are given
-    const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+    const T* Vu = vsum + ((size_t)unit * mc + c0) * D + sub * EPC;
     // The range's scores and sizes are staged in LDS with coalesced loads (a
     // group's own 4-byte reads of them would be one memory request per row and
     // head); the value sums stream with the next pass's rows already in flight.
@@ -2257,7 +2257,7 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
       float zv[G];
 #pragma unroll
       for (int g = 0; g < G; ++g) zv[g] = z[(size_t)(bh0 + g) * m + c0 + i];
-      const int sz = sw.sizes[(size_t)unit * m + c0 + i];
+      const int sz = sw.sizes[(size_t)unit * mc + c0 + i];
 #pragma unroll
       for (int g = 0; g < G; ++g) zs[g * sw.est_rows + i] = zv[g] * scale_log2;
       ms[i] = (float)sz;
@@ -2309,7 +2309,7 @@ __device__ __forceinline__ void side_role(int wg, const SideWork& sw, const T* _
 // from LDS, the next pass's rows already in flight.  One partial per head.
 template <typename T, int D, int G, int NT, int U = 4>
 __device__ __forceinline__ void estimate_range(int wg, const SideWork& sw, const float* __restrict__ z,
-                                               const T* __restrict__ vsum, int Hq, int Hkv, int m,
+                                               const T* __restrict__ vsum, int Hq, int Hkv, int m, int mc,
                                                float scale_log2, float* __restrict__ part, int slots,
                                                char* lds_raw) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, NWV = NT / 64;
@@ -2325,7 +2325,7 @@ __device__ __forceinline__ void estimate_range(int wg, const SideWork& sw, const
   float* ms = zw + (size_t)sw.est_rows * ZG;        // [est_rows]: the size as a float
   float* smem = zw;                                 // the last step reuses the space
   __shared__ float red[NWV][2 * G];
-  const T* Vu = vsum + ((size_t)unit * m + c0) * D + sub * EPC;
+  const T* Vu = vsum + ((size_t)unit * mc + c0) * D + sub * EPC;
   auto load_rows = [&](int i, uint4 (&dst)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) dst[u] = load16_stream(Vu + (size_t)min(i + u * GROUPS, nrows - 1) * D);
@@ -2339,7 +2339,7 @@ __device__ __forceinline__ void estimate_range(int wg, const SideWork& sw, const
     float zv[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) zv[g] = z[(size_t)(bh0 + g) * m + c0 + i];
-    const int sz = sw.sizes[(size_t)unit * m + c0 + i];
+    const int sz = sw.sizes[(size_t)unit * mc + c0 + i];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float v = zv[g] * scale_log2;  // -inf for an empty cluster
@@ -2458,7 +2458,7 @@ template <typename T, int D, int G, int NT, int VPT>
 __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -2471,14 +2471,14 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void slices_side_kernel(
     const int base = sl * slice_len, len = min(slice_len, m - base);
     int ntok;
     select_core<T, D, NT, VPT, true>(
-        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, mc, usel_stride, sel_ids, sel_pref,
         sel_row, bitmap, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
         dyn_keys, nullptr, nullptr, 0, &ntok,
         SelView{len, base, nullptr, nullptr, 1, slice_ids + ((size_t)bh * nslices + sl) * r,
                 slice_z + ((size_t)bh * nslices + sl) * r});
     return;
   }
-  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, mc, scale_log2, part,
                          slots, reinterpret_cast<char*>(dyn_keys));
 }
 
@@ -2635,7 +2635,7 @@ template <typename T, int D, int G, int NT, int VPT>
 __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void filter_side_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -2656,12 +2656,12 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void filter_side_kernel(
     __syncthreads();
     int ntok;
     select_core<T, D, NT, VPT, true>(
-        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, usel_stride, sel_ids, sel_pref,
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, r, mwords, mc, usel_stride, sel_ids, sel_pref,
         sel_row, bitmap, nsel_out, nullptr, vsum, scale_log2, part, slots, neg_slot, bh,
         dyn_keys, nullptr, nullptr, 0, &ntok, SelView{len, base, nullptr, nullptr, 1, ids_out, z_out});
     return;
   }
-  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, mc, scale_log2, part,
                          slots, reinterpret_cast<char*>(dyn_keys));
 }
 
@@ -2669,7 +2669,7 @@ template <typename T, int D, int G, int NT, int VPT>
 __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out,
     int32_t* __restrict__ user_selected, const T* __restrict__ vsum, float scale_log2,
@@ -2683,7 +2683,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
     // as holes, the lists are one ascending id map of nslices * r positions.
     const int bh = blockIdx.x;
     int ntok;
-    select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+    select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                                      usel_stride, sel_ids, sel_pref, sel_row, bitmap,
                                      nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot,
                                      bh, dyn_keys, nullptr, nullptr, 0, &ntok,
@@ -2691,7 +2691,7 @@ __global__ __launch_bounds__(NT, G <= 4 ? 4 : 2) void combine_side_kernel(
                                              slice_z + (size_t)bh * nslices * r, 2, nullptr, nullptr});
     return;
   }
-  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, scale_log2, part,
+  side_role<T, D, G, NT>((int)blockIdx.x - n_select_wgs, sw, q, z, vsum, Hq, Hkv, m, mc, scale_log2, part,
                          slots, reinterpret_cast<char*>(dyn_keys));
 }
 
@@ -2796,7 +2796,7 @@ template <typename T, int D, int NT>
 __device__ __forceinline__ void select_filtered(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
     float scale_log2, float* __restrict__ part, int slots, int neg_slot, int bh,
@@ -3012,14 +3012,14 @@ __device__ __forceinline__ void select_filtered(
     __syncthreads();
     WAVE_STAMP(trace, 3);
     nsel = select_core<T, D, NT, FILT_VPT, true>(
-        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
+        q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc, usel_stride, sel_ids, sel_pref,
         sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys,
         s_pref, s_row, FILT_CAP - 1, &ntok,
         SelView{cnt, 0, cand_id, cand_z, 0, nullptr, nullptr, s_ids, 1, guard});
     __syncthreads();
     WAVE_STAMP(trace, 4);
   } else {
-    select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+    select_streaming<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                                usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
                                vsum, scale_log2, part, slots, neg_slot, bh, 0);
     __syncthreads();
@@ -3040,7 +3040,7 @@ template <typename T, int D, int NT>
 __device__ __forceinline__ void select_direct(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
     float scale_log2, float* __restrict__ part, int slots, int neg_slot, int bh, int stage,
@@ -3051,7 +3051,7 @@ __device__ __forceinline__ void select_direct(
   int32_t* s_ids = s_row + stage;
   int ntok;
   const int nsel = select_core<T, D, NT, 64, true>(
-      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, usel_stride, sel_ids, sel_pref,
+      q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc, usel_stride, sel_ids, sel_pref,
       sel_row, bitmap, nsel_out, user_selected, vsum, scale_log2, part, slots, neg_slot, bh, skeys, s_pref,
       s_row, stage, &ntok, SelView{m, 0, nullptr, nullptr, 0, nullptr, nullptr, s_ids, 1});
   __syncthreads();
@@ -3076,7 +3076,7 @@ template <typename T, int D, int G, int NT, bool FILTERED>
 __global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_estimate_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
-    int m, int r, int rcap, int mwords, int usel_stride, int32_t* __restrict__ sel_ids,
+    int m, int r, int rcap, int mwords, int mc, int usel_stride, int32_t* __restrict__ sel_ids,
     int32_t* __restrict__ sel_pref, int32_t* __restrict__ sel_row, uint32_t* __restrict__ bitmap,
     int32_t* __restrict__ nsel_out, int32_t* __restrict__ user_selected, const T* __restrict__ vsum,
     float scale_log2, float* __restrict__ part, int slots, int neg_slot,
@@ -3092,12 +3092,12 @@ __global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_esti
                                   : (int)((long long)(b + 1) * n_select_wgs / total) > sel_before;
   if (is_select) {
     if constexpr (FILTERED)
-      select_filtered<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+      select_filtered<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                                 usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
                                 vsum, scale_log2, part, slots, neg_slot, sel_before, tile_max, lo,
                                 reinterpret_cast<char*>(dyn_keys));
     else
-      select_direct<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords,
+      select_direct<T, D, NT>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, r, rcap, mwords, mc,
                               usel_stride, sel_ids, sel_pref, sel_row, bitmap, nsel_out, user_selected,
                               vsum, scale_log2, part, slots, neg_slot, sel_before, stage, lo,
                               reinterpret_cast<char*>(dyn_keys));
@@ -3134,7 +3134,7 @@ __global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_esti
   WAVE_STAMP(tbuf, 32 + 2 * (te / n_select_wgs));
 #endif
   // (small workgroups: twice the rows in flight per lane group)
-  estimate_range<T, D, G, NT, (NT <= 256 && G <= 4 ? 8 : 4)>(b - sel_before, sw, z, vsum, Hq, Hkv, m, scale_log2,
+  estimate_range<T, D, G, NT, (NT <= 256 && G <= 4 ? 8 : 4)>(b - sel_before, sw, z, vsum, Hq, Hkv, m, mc, scale_log2,
                                                              part, slots, reinterpret_cast<char*>(dyn_keys));
 #ifdef WAVE_TRACE
   WAVE_STAMP(tbuf, 33 + 2 * (te / n_select_wgs));
@@ -3145,7 +3145,7 @@ __global__ __launch_bounds__(NT, (G <= 4 || !FILTERED) ? 4 : 2) void select_esti
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256, 4) void score_steady_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ sizes,
-    float* __restrict__ z, float* __restrict__ cn2part, int Hkv, int m, int chunks,
+    float* __restrict__ z, float* __restrict__ cn2part, int Hkv, int m, int mc, int chunks,
     float* __restrict__ tile_max, int n_score_wgs, const T* __restrict__ k_steady,
     const T* __restrict__ v_steady, int p, int p_stride, int steady_chunks, int steady_rows, int slots,
     int steady_slot0, float scale_log2, float* __restrict__ part, int32_t* __restrict__ work,
@@ -3165,7 +3165,7 @@ __global__ __launch_bounds__(256, 4) void score_steady_kernel(
     const int b = unit / Hkv, h = unit - b * Hkv;
     const int bh0 = b * Hq + h * G;
     const int c0 = chunk * DENSE_ROWS, nrows = min(DENSE_ROWS, m - c0);
-    dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * m + c0, z, unit, bh0, m, c0, nrows, lds,
+    dense_scores<T, D, G, 256, true>(q, C, sizes + (size_t)unit * mc + c0, z, unit, bh0, m, mc, c0, nrows, lds,
                                      sizeof(T) == 2 ? tile_max : nullptr);
     __syncthreads();
     if (threadIdx.x == 0) cn2part[(size_t)unit * chunks + chunk] = dense_cn2(lds);
@@ -3212,7 +3212,7 @@ __global__ __launch_bounds__(256) void gather_list_kernel(
     const T* __restrict__ q, const T* __restrict__ k_perm, const T* __restrict__ v_perm,
     const int32_t* __restrict__ sel_pref, const int32_t* __restrict__ sel_row,
     const int32_t* __restrict__ sel_ids, const ListOut lo, int wtotal, const float* __restrict__ z,
-    const T* __restrict__ vsum, int Hq, int Hkv, int N_idx /* rows per unit */, int m, int rcap,
+    const T* __restrict__ vsum, int Hq, int Hkv, int N_idx /* rows per unit */, int m, int mc, int rcap,
     float scale_log2, float* __restrict__ part_g) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, RPW = 64 / LPR, GROUPS = 4 * RPW, U = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -3247,7 +3247,7 @@ __global__ __launch_bounds__(256) void gather_list_kernel(
     st.init(q + (size_t)bh * D, sub, scale_log2);
     const T* Ku = k_perm + (size_t)unit * N_idx * D + sub * EPC;
     const T* Vu = v_perm + (size_t)unit * N_idx * D + sub * EPC;
-    const T* VSu = vsum + (size_t)unit * m * D + sub * EPC;
+    const T* VSu = vsum + (size_t)unit * mc * D + sub * EPC;
     const int nc_all = t0 < t1 ? a1 - a0 + 1 : 0;
     for (int cb = 0; cb < nc_all; cb += GATHER_TILE) {
       const int nc = min(GATHER_TILE, nc_all - cb);
@@ -3497,6 +3497,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
   float* part = reinterpret_cast<float*>(w + g.off_part);
   const T* q = static_cast<const T*>(q_);
   const int units = ix.B * ix.Hkv, heads = ix.B * Hq, m = ix.m;
+  const int mc = cluster_stride(ix);  // clusters per unit in the meta-index arrays
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const int r = m > 0 ? (topk < m ? topk : m) : 0;
 
@@ -3510,30 +3511,30 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                    g.wmain, g.chunk_tokens};
       // (the steady zone rides with the selection launch; this kernel's steady role stays idle)
       WAVE_LAUNCH("scores", (score_steady_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
-                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
+                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, mc, g.score_chunks,
                   g.list_filtered ? reinterpret_cast<float*>(w + g.off_tile_max) : nullptr,
                   units * g.score_chunks, static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 0, g.steady_rows,
                   g.slots, 0, scale_log2, part, lo.work, lo.work_count, g.wtotal);
     } else if (g.sliced)
       WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
-                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks,
+                  static_cast<const T*>(ix.centroids), ix.sizes, z, cn2, ix.Hkv, m, mc, g.score_chunks,
                   reinterpret_cast<float*>(w + g.off_tile_max));
     else if (!g.fused && g.steady_chunks > 0)
       WAVE_LAUNCH("meta_index+steady", (dense_steady_kernel<T, D, G>),
                   units * (g.score_chunks + g.steady_chunks), 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
-                  ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part,
+                  ix.Hkv, m, mc, g.score_chunks, g.slots, est_slot0, scale_log2, part,
                   units * g.score_chunks, static_cast<const T*>(ix.k_steady),
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows,
                   g.gather_chunks);
     else
       WAVE_LAUNCH("meta_index", (dense_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q,
                   static_cast<const T*>(ix.centroids), static_cast<const T*>(ix.vsum), ix.sizes, z, cn2,
-                  ix.Hkv, m, g.score_chunks, g.slots, est_slot0, scale_log2, part);
+                  ix.Hkv, m, mc, g.score_chunks, g.slots, est_slot0, scale_log2, part);
 #define WAVE_SELECT_ARGS                                                                           \
   q, static_cast<const T*>(ix.centroids), ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, r,    \
-      g.rcap, g.mwords, topk, sel, pref, srow, bitmap, nsel, selected,                        \
+      g.rcap, g.mwords, mc, topk, sel, pref, srow, bitmap, nsel, selected,                        \
       static_cast<const T*>(ix.vsum), scale_log2, part, g.slots, neg_slot
     const size_t key_lds = sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512);
     if (g.fused) {
@@ -3565,7 +3566,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                     static_cast<const float*>(nullptr), lo, g.stage, heads, sw);
       WAVE_LAUNCH("gather", (gather_list_kernel<T, D>), g.gather_wgs, 256, 0, st, q,
                   static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), pref, srow, sel, lo,
-                  g.wtotal, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
+                  g.wtotal, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, mc, g.rcap,
                   scale_log2, reinterpret_cast<float*>(w + g.off_part_g));
       // (few heads: many threads per head, every partial in one trip; many heads: small workgroups)
       if (heads <= 256)
@@ -3616,7 +3617,7 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
       if (g.gather_chunks > 0)
         WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                     static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), sel, nsel,
-                    ix.offsets, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, g.rcap,
+                    ix.offsets, z, static_cast<const T*>(ix.vsum), Hq, ix.Hkv, row_stride(ix), m, mc, g.rcap,
                     g.gather_chunks, g.slots, scale_log2, g.neg_in_gather, part);
     }
 #undef WAVE_SELECT_ARGS
@@ -3726,6 +3727,7 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const T* C = static_cast<const T*>(ix.centroids);
   const T* VS = static_cast<const T*>(ix.vsum);
   const int units = ix.B * ix.Hkv, heads = ix.B * Hq, m = ix.m;
+  const int mc = cluster_stride(ix);  // clusters per unit in the meta-index arrays
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const int slots = g.slots + 1, spare_slot = g.slots;
 
@@ -3734,18 +3736,18 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   // one launch (neither needs the other); the merge.
   if (m <= 512 * 32 && est_clusters > 0) {
     WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>), units * (g.score_chunks + g.steady_chunks),
-                256, 0, st, q, C, ix.sizes, z, cn2, ix.Hkv, m, g.score_chunks, static_cast<float*>(nullptr),
+                256, 0, st, q, C, ix.sizes, z, cn2, ix.Hkv, m, mc, g.score_chunks, static_cast<float*>(nullptr),
                 units * g.score_chunks, static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady),
                 ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows, slots, 0, scale_log2, part,
                 static_cast<int32_t*>(nullptr), static_cast<int32_t*>(nullptr), 0);
     WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32>), 2 * heads, 512,
                 sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, q, C, ix.offsets, z, cn2,
-                g.score_chunks, Hq, ix.Hkv, m, g.mwords, bitmap, g.r, g.rcap1, ids1, nsel1, selected, g.k2,
+                g.score_chunks, Hq, ix.Hkv, m, g.mwords, mc, bitmap, g.r, g.rcap1, ids1, nsel1, selected, g.k2,
                 g.rcap2, ids2, nsel2, VS, scale_log2);
     const int n_est = heads * g.est_chunks;
     WAVE_LAUNCH("gather+estimate", (gather_est_kernel<T, D>), n_est + heads * g.gather_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1, ids2, nsel2,
-                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, g.rcap1, g.rcap2, g.gather_chunks,
+                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, mc, g.rcap1, g.rcap2, g.gather_chunks,
                 g.est_chunks, slots, g.steady_chunks, g.steady_chunks + g.gather_chunks, n_est, scale_log2,
                 part);
     if (heads <= 256)
@@ -3756,11 +3758,11 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
     return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
   }
   WAVE_LAUNCH("scores", (score_kernel<T, D, G>), units * g.score_chunks, 256, 0, st, q, C, ix.sizes, z,
-              cn2, ix.Hkv, m, g.score_chunks, static_cast<float*>(nullptr));
+              cn2, ix.Hkv, m, mc, g.score_chunks, static_cast<float*>(nullptr));
   // the k best clusters of every head as an ascending id list (ids, nsel)
   auto select_ids = [&](int k, int rcap, int sliced, int32_t* ids, int32_t* nsel, int32_t* usel) {
 #define WAVE_SEL(k_)                                                                                \
-  q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, k_, rcap, g.mwords, k_, ids, pref, srow,   \
+  q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, k_, rcap, g.mwords, mc, k_, ids, pref, srow,   \
       bitmap, nsel, usel, VS, scale_log2, part, slots, spare_slot
     if (sliced) {
       const int npos_max = g.nslices * k;
@@ -3793,11 +3795,11 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   if (g.gather_chunks > 0)
     WAVE_LAUNCH("gather", (gather_kernel<T, D>), heads * g.gather_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1,
-                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, g.rcap1, g.gather_chunks, slots, scale_log2, 0,
+                ix.offsets, z, VS, Hq, ix.Hkv, row_stride(ix), m, mc, g.rcap1, g.gather_chunks, slots, scale_log2, 0,
                 part + (size_t)g.steady_chunks * (D + 2));
   if (g.est_chunks > 0)
     WAVE_LAUNCH("estimate", (est_gather_kernel<T, D>), heads * g.est_chunks, 256, 0, st, ids2, nsel2, ids1,
-                nsel1, ix.offsets, z, VS, Hq, ix.Hkv, m, g.rcap2, g.rcap1, g.est_chunks, slots,
+                nsel1, ix.offsets, z, VS, Hq, ix.Hkv, m, mc, g.rcap2, g.rcap1, g.est_chunks, slots,
                 g.steady_chunks + g.gather_chunks, scale_log2, part);
   WAVE_LAUNCH("merge", (merge_kernel<D>), heads, MERGE_THREADS, 0, st, part, g.slots, slots, out, lse);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;

@@ -30,8 +30,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 14 int32 fields, 9 pointers, 4 int32 fields (the index update's)
-    assert ctypes.sizeof(wb.wave_index) == 14 * 4 + 9 * 8 + 4 * 4
+    # 14 int32 fields, 9 pointers, 5 int32 fields (the index update's and the capacities), padded
+    # to the pointers' alignment
+    assert ctypes.sizeof(wb.wave_index) == 14 * 4 + 9 * 8 + 5 * 4 + 4
     assert wb.wave_index.centroids.offset == 56
     assert wb.wave_index.appended_segments.offset == 56 + 72
 
@@ -126,6 +127,28 @@ def test_row_capacity_in_the_plan():
                                        (ctypes.c_size_t * 9)(), None)
         assert st == 0 and cn.N_idx == 4932 + 256 * (n_new // 256)
         assert cn.row_capacity == (6000 if keeps else 0), (n_new, cn.row_capacity)
+
+
+def test_cluster_capacity_in_the_plan():
+    """Room for more clusters than the index holds: the four meta-index arrays follow the capacity,
+    too small a capacity is refused, and the plan of an update keeps it while the clusters fit."""
+    c, sizes, _, _ = wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, cluster_capacity=400)
+    assert c.m == 320 and c.cluster_capacity == 400      # 4 full segments + 836 tokens: 5 x 64 clusters
+    assert sizes[0] == sizes[1] == 6 * 400 * 256 and sizes[2] == 6 * 400 * 4 and sizes[3] == 6 * 401 * 4
+    assert sizes[5] == 6 * c.N_idx * 256                  # the rows stay dense
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, cluster_capacity=319)
+    assert e.value.status == 2
+    with pytest.raises(wb.WaveError) as e:
+        wb.wave_index_plan(torch.bfloat16, 2, 3, 128, 5000, 4, 64, 1024, 64, cluster_capacity=-1)
+    assert e.value.status == 1
+    L_ = wb.lib()
+    for n_new, keeps in ((1280, True), (1536, False)):    # 5 or 6 update segments of 16 clusters
+        cn = wb.wave_index()
+        st = L_.wave_index_append_plan(ctypes.byref(c), n_new, 64, 256, 16, ctypes.byref(cn),
+                                       (ctypes.c_size_t * 9)(), None)
+        assert st == 0 and cn.m == 320 + 16 * (n_new // 256)
+        assert cn.cluster_capacity == (400 if keeps else 0), (n_new, cn.cluster_capacity)
 
 
 def test_status_strings():

@@ -179,6 +179,22 @@ def test_build_matches_oracle_then_decode(case):
     _decode_and_check(wl, ix, index_ref, q, pu.retrieve_count(wl), case)
 
 
+@pytest.mark.parametrize("case", ["bf16_g4", "bf16_g7", "bf16_d64", "bf16_many_heads_g7"])
+def test_short_segments_build_the_same_index_launch_by_launch(case, monkeypatch):
+    """Short segments are clustered by one workgroup per segment that runs all iterations (the
+    default, which the other build tests cover); WAVE_NO_SMALL_KMEANS=1 keeps them on the kernels
+    of the long segments, one launch per step.  Both against the oracle."""
+    wl = CASES[case]
+    K, V, _ = _inputs(wl)
+    index_ref = pu.oracle_build(wl, K, V)
+    monkeypatch.setenv("WAVE_NO_SMALL_KMEANS", "1")
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    torch.cuda.synchronize()
+    monkeypatch.delenv("WAVE_NO_SMALL_KMEANS")
+    assert _compare_index(wl, ix, index_ref, case) == 0
+
+
 def test_all_retrieved_is_full_attention():
     wl = CASES["bf16_g4"]
     K, V, q = _inputs(wl, 1)
@@ -429,6 +445,13 @@ def test_more_near_equal_scores_than_the_candidate_list_holds(m, r):
         pu.check_outputs(o_g, np.array([l_g]), o, np.array([l]), dtype, tag)
 
 
+def _used(ix, nm, b, h):
+    """The entries in use of one unit's array (capacities leave room behind them)."""
+    n = {"sizes": ix.m, "centroids": ix.m, "vsum": ix.m, "offsets": ix.m + 1, "perm": ix.N_idx,
+         "k_perm": ix.N_idx, "v_perm": ix.N_idx, "k_steady": ix.p, "v_steady": ix.p}[nm]
+    return ix.t[nm][b, h][:n]
+
+
 @pytest.mark.parametrize("name,units", [("llama8b_120k_b16", [(0, 0), (15, 7)]),
                                         ("llama8b_32k", [(0, 0), (0, 3), (0, 7)]),
                                         ("llama8b_1m", [(0, 5)]),
@@ -437,17 +460,23 @@ def test_full_size_workload_sampled_units(name, units):
     """The benchmark's own workloads at full size, in the launch configuration
     bench.py times: whole-batch GPU build and decode; the oracle builds and
     decodes the sampled (sequence, KV head) units from the same keys and values
-    and every array of those units, their selected sets and outputs must agree."""
+    and every array of those units, their selected sets and outputs must agree.
+    The 120K x 16 index is built with room for new rows and clusters, as the benchmark's
+    index update has it: the update below then writes in place."""
     wl = WL[name]
     dev = torch.device("cuda")
     K, V = synth.make_kv(wl, device=dev)
     q = synth.make_queries(wl, 3, device=dev)
+    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+    U, ku = 1024, 64
+    caps = {}
+    if name == "llama8b_120k_b16":
+        caps = dict(row_capacity=plan.N_idx + 2 * U, cluster_capacity=plan.m + 2 * ku)
     ix = wb.wave_index_build(K, V, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment,
-                             wl.iters, 0)
+                             wl.iters, 0, **caps)
     r = pu.retrieve_count(wl)
     out, lse, sel = wb.wave_attention_decode(q, ix, r, want_selected=True)
     torch.cuda.synchronize()
-    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
     qn = q.double().cpu().numpy()
     refs = {}
     for (b, h) in units:
@@ -455,11 +484,10 @@ def test_full_size_workload_sampled_units(name, units):
                             wl.iters, 0, b, h, wl.dtype)
         refs[(b, h)] = ref
         tag = f"{name} b={b} h={h}"
-        assert np.array_equal(ix.sizes[b, h].cpu().numpy(), ref.sizes), tag
-        assert np.array_equal(ix.offsets[b, h].cpu().numpy(), ref.offsets), tag
-        assert np.array_equal(ix.perm[b, h].cpu().numpy(), ref.perm), tag
+        for nm in ("sizes", "offsets", "perm"):
+            assert np.array_equal(_used(ix, nm, b, h).cpu().numpy(), getattr(ref, nm)), (tag, nm)
         for nm in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
-            assert np.array_equal(ix.t[nm][b, h].float().cpu().numpy(),
+            assert np.array_equal(_used(ix, nm, b, h).float().cpu().numpy(),
                                   getattr(ref, nm).astype(np.float32)), (tag, nm)
         for g in range(wl.G):
             hq = h * wl.G + g
@@ -474,7 +502,6 @@ def test_full_size_workload_sampled_units(name, units):
     # (the paper's update segment size), 64 clusters, on the whole batch; sampled units
     # against the oracle's update of its own index, then decode on the grown index
     del out, lse, sel
-    U, ku = 1024, 64
     gen = torch.Generator(device=dev)
     gen.manual_seed(17)
     Kn = (K[:, :, -U:] + 0.05 * torch.randn(wl.B, wl.Hkv, U, wl.d, generator=gen, device=dev).to(K.dtype)).contiguous()
@@ -482,17 +509,19 @@ def test_full_size_workload_sampled_units(name, units):
     ix2 = wb.wave_index_append(ix, Kn, Vn, wl.n_local, U, ku, wl.iters, 0)
     torch.cuda.synchronize()
     assert (ix2.N, ix2.m, ix2.N_idx, ix2.n_local) == (wl.N + U, ix.m + ku, ix.N_idx + U, wl.n_local)
+    # in place: the new rows and clusters went behind the old ones in the same buffers
+    assert ix2.k_perm.data_ptr() == ix.k_perm.data_ptr() and ix2.centroids.data_ptr() == ix.centroids.data_ptr()
+    assert ix2.row_capacity == ix.row_capacity and ix2.cluster_capacity == ix.cluster_capacity
     out, lse, sel = wb.wave_attention_decode(q, ix2, r, want_selected=True)
     torch.cuda.synchronize()
     for (b, h) in units:
         ref = wo.append_unit(refs[(b, h)], Kn[b, h].double().cpu().numpy(), Vn[b, h].double().cpu().numpy(),
                              wl.n_local, U, ku, wl.iters, 0, b, h)
         tag = f"{name} grown b={b} h={h}"
-        assert np.array_equal(ix2.sizes[b, h].cpu().numpy(), ref.sizes), tag
-        assert np.array_equal(ix2.offsets[b, h].cpu().numpy(), ref.offsets), tag
-        assert np.array_equal(ix2.perm[b, h].cpu().numpy(), ref.perm), tag
+        for nm in ("sizes", "offsets", "perm"):
+            assert np.array_equal(_used(ix2, nm, b, h).cpu().numpy(), getattr(ref, nm)), (tag, nm)
         for nm in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
-            assert np.array_equal(ix2.t[nm][b, h].float().cpu().numpy(),
+            assert np.array_equal(_used(ix2, nm, b, h).float().cpu().numpy(),
                                   getattr(ref, nm).astype(np.float32)), (tag, nm)
         for g in range(wl.G):
             hq = h * wl.G + g
@@ -594,13 +623,17 @@ _SHORT = _small("tiny_f32", name="f32_short", N=50, n_sink=4, n_local=64, segmen
                 clusters_per_segment=128, iters=3, retrieve_abs=2)
 
 
-@pytest.mark.parametrize("case,n_news,U,ku,cap,scap", [("bf16_g4", (300, 37, 1000), 256, 16, 0, 0),
-                                                       ("bf16_g4", (300, 37, 1, 1000), 256, 16, 5400, 480),
-                                                       ("tiny_f32", (5, 200), 64, 8, 0, 0),
-                                                       ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140),
-                                                       ("bf16_d64", (130,), 128, 200, 0, 0),
-                                                       (_SHORT, (10, 100), 32, 4, 0, 0)])
-def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap):
+@pytest.mark.parametrize("case,n_news,U,ku,cap,scap,ccap", [
+    ("bf16_g4", (300, 37, 1000), 256, 16, 0, 0, 0),
+    ("bf16_g4", (300, 37, 1, 1000), 256, 16, 5400, 480, 0),
+    ("bf16_g4", (300, 37, 1, 1000), 256, 16, 8192, 480, 470),   # room for every new row and cluster
+    ("bf16_g4", (300, 37, 1, 1000), 256, 16, 8192, 0, 420),     # the room for clusters runs out
+    ("tiny_f32", (5, 200), 64, 8, 0, 0, 0),
+    ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140, 0),
+    ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140, 4096),
+    ("bf16_d64", (130,), 128, 200, 0, 0, 0),
+    (_SHORT, (10, 100), 32, 4, 0, 0, 0)])
+def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap, ccap):
     """Incremental index update through the C ABI, several times in a row (without and with
     flushed update segments, more clusters asked for than an update segment has tokens, an
     index with no clusters yet; once with room for the new rows and the new steady rows,
@@ -613,8 +646,9 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap)
     K0, V0 = Kall[:, :, :wl.N].contiguous(), Vall[:, :, :wl.N].contiguous()
     ref = pu.oracle_build(wl, K0, V0)
     ix = wb.wave_index_build(K0.cuda(), V0.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
-                             wl.clusters_per_segment, wl.iters, 0, row_capacity=cap, steady_capacity=scap)
-    first, shared_rows, shared_steady = ix, 0, 0
+                             wl.clusters_per_segment, wl.iters, 0, row_capacity=cap, steady_capacity=scap,
+                             cluster_capacity=ccap)
+    first, shared_rows, shared_steady, shared_meta = ix, 0, 0, 0
     pos = wl.N
     for n_new in n_news:
         Kn, Vn = Kall[:, :, pos:pos + n_new].contiguous(), Vall[:, :, pos:pos + n_new].contiguous()
@@ -623,6 +657,7 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap)
         torch.cuda.synchronize()
         shared_rows += int(ix.k_perm.data_ptr() == before.k_perm.data_ptr() and ix.m > before.m)
         shared_steady += int(ix.k_steady.data_ptr() == before.k_steady.data_ptr())
+        shared_meta += int(ix.centroids.data_ptr() == before.centroids.data_ptr() and ix.m > before.m)
         for (b, h), u in ref.items():
             ref[(b, h)] = wo.append_unit(u, Kn[b, h].double().numpy(), Vn[b, h].double().numpy(),
                                          wl.n_local, U, ku, wl.iters, 0, b, h)
@@ -633,12 +668,13 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap)
         for (b, h), u in ref.items():
             for name in ("sizes", "offsets", "perm"):
                 got = getattr(ix, name)[b, h].cpu().numpy()
-                got = got[:ix.N_idx] if name == "perm" else got
+                got = got[:ix.N_idx] if name == "perm" else got[:ix.m + (name == "offsets")]   # entries in use
                 assert np.array_equal(got, getattr(u, name)), (n_new, b, h, name)
             for name in ("centroids", "vsum", "k_perm", "v_perm", "k_steady", "v_steady"):
                 t = getattr(ix, name)[b, h]
                 t = t[:ix.N_idx] if name in ("k_perm", "v_perm") else t    # rows in use
                 t = t[:ix.p] if name in ("k_steady", "v_steady") else t
+                t = t[:ix.m] if name in ("centroids", "vsum") else t
                 got = t.float().cpu().numpy().astype(np.float64)
                 assert np.array_equal(got, getattr(u, name)), (n_new, b, h, name)
     assert ix.appended_segments > 0
@@ -648,9 +684,17 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap)
         assert shared_rows >= 1 and ix.row_capacity == cap      # the rows were added in place
     if cap == 5400:
         assert ix.row_capacity == 0                              # the room ran out: dense again
-    if cap:   # the index before the updates is untouched by rows written behind its own
+    if ccap == 470 or ccap == 4096:
+        assert shared_meta >= 1 and ix.cluster_capacity == ccap   # the clusters were added in place
+        assert ix.centroids.data_ptr() == first.centroids.data_ptr()
+    if ccap == 420:
+        assert shared_meta >= 1 and ix.cluster_capacity == 0      # the room ran out: dense again
+    if cap:   # the index before the updates is untouched by rows and clusters written behind its own
         u = pu.oracle_build(wl, K0, V0)[(0, 0)]
         assert np.array_equal(first.k_perm[0, 0, :first.N_idx].float().cpu().numpy().astype(np.float64), u.k_perm)
+        assert np.array_equal(first.centroids[0, 0, :first.m].float().cpu().numpy().astype(np.float64), u.centroids)
+        assert np.array_equal(first.sizes[0, 0, :first.m].cpu().numpy(), u.sizes)
+        assert np.array_equal(first.offsets[0, 0, :first.m + 1].cpu().numpy(), u.offsets)
     q = synth.make_queries(big, 2)
     wl_now = synth.scaled(big, n_local=ix.n_local)
     r = pu.retrieve_count(wl)
