@@ -250,17 +250,10 @@ AppendGeom append_geometry(const wave_index& old_ix, int n_new, int n_local_min,
   mi.m = g.F * g.ks;
   mi.N_idx = g.F * U;
   const size_t es = old_ix.dtype == WAVE_BF16 ? 2 : 4, units = (size_t)old_ix.B * old_ix.Hkv;
-  const size_t rows = units * (size_t)mi.N_idx * old_ix.d * es, crow = units * (size_t)mi.m * old_ix.d * es;
+  const size_t rows = units * (size_t)mi.N_idx * old_ix.d * es;
   size_t o = 0;
   g.off_k = o;       o = align_up(o + rows);
   g.off_v = o;       o = align_up(o + rows);
-  g.off_c = o;       o = align_up(o + crow);
-  g.off_vs = o;      o = align_up(o + crow);
-  g.off_sizes = o;   o = align_up(o + units * (size_t)mi.m * 4);
-  g.off_offsets = o; o = align_up(o + units * ((size_t)mi.m + 1) * 4);
-  g.off_perm = o;    o = align_up(o + units * (size_t)mi.N_idx * 4);
-  g.off_kp = o;      o = align_up(o + rows);
-  g.off_vp = o;      o = align_up(o + rows);
   g.off_build = o;
   if (g.F > 0) o = align_up(o + build_geometry(mi).total);
   g.total = g.F > 0 ? o : 0;

@@ -8,13 +8,13 @@
 // steps: (1) the old arrays are copied to the new strides; (2) the window (old
 // local rows, then the new tokens) is routed row by row, its flushed prefix to a
 // scratch key/value tensor and the rest to the new steady rows; (3) the flushed
-// tokens are built as an index of their own by the build's kernels, with their
-// segments numbered after the old ones for the seeding rule; (4) that index is
-// appended: centroids, value sums, sizes and rows as they are, offsets shifted
-// by the old row count, positions by the window's first position.  When the
-// row arrays (perm, k_perm, v_perm) of both indexes are the same buffers with
-// room left (row_capacity), step (1) skips them and step (4) writes the new
-// rows behind the old ones in place.
+// tokens are clustered by the build's kernels, with their segments numbered
+// after the old ones for the seeding rule, and the build's last step writes
+// their clusters and rows straight behind the old ones in the new index's
+// arrays (offsets continued from the old row count, positions from the window's
+// first position).  When arrays of both indexes are the same buffers with room
+// left (row_capacity for perm, k_perm, v_perm; cluster_capacity for the meta
+// index), step (1) skips them: the update then writes only what is new.
 #include "wave_common.h"
 
 namespace wave {
@@ -30,18 +30,6 @@ __global__ __launch_bounds__(256) void copy_units_kernel(C* __restrict__ dst, co
     dst[u * dst_stride + dst_off + j] = src[u * src_stride + j];
   }
 }
-__global__ __launch_bounds__(256) void copy_units_add_kernel(int32_t* __restrict__ dst,
-                                                             const int32_t* __restrict__ src, size_t n,
-                                                             size_t dst_stride, size_t src_stride,
-                                                             size_t dst_off, size_t src_off, int units,
-                                                             int32_t add) {
-  const size_t total = n * (size_t)units, step = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += step) {
-    const size_t u = i / n, j = i - u * n;
-    dst[u * dst_stride + dst_off + j] = src[u * src_stride + src_off + j] + add;
-  }
-}
-
 __global__ __launch_bounds__(256) void set_first_kernel(int32_t* __restrict__ dst, size_t stride, int units) {
   const int u = blockIdx.x * 256 + threadIdx.x;
   if (u < units) dst[(size_t)u * stride] = 0;
@@ -148,33 +136,23 @@ wave_status launch_append(const wave_index& o, const void* K_new, const void* V_
   }
   if (g.F == 0) return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 
-  // (3) the flushed tokens as an index of their own, segments numbered after the old ones
+  // (3) the flushed tokens are built as an index whose arrays are the new index's own, from
+  // the old clusters' and rows' end onwards and at the new index's strides: segments numbered
+  // after the old ones, offsets continued from the old row count, positions from the window's
+  // first token (window row w is token old N - old local count + w)
   wave_index mi = g.mini;
-  mi.centroids = w + g.off_c;
-  mi.vsum = w + g.off_vs;
-  mi.sizes = reinterpret_cast<int32_t*>(w + g.off_sizes);
-  mi.offsets = reinterpret_cast<int32_t*>(w + g.off_offsets);
-  mi.perm = reinterpret_cast<int32_t*>(w + g.off_perm);
-  mi.k_perm = w + g.off_kp;
-  mi.v_perm = w + g.off_vp;
-  const wave_status bs = launch_build(w + g.off_k, w + g.off_v, mi, iters, seed, w + g.off_build, st, o.S);
-  if (bs != WAVE_OK) return bs;
-
-  // (4) appended behind the old clusters and rows
-  copy_units<uint4>(nw.centroids, mi.centroids, (size_t)mi.m * rowc, cs_new * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
-  copy_units<uint4>(nw.vsum, mi.vsum, (size_t)mi.m * rowc, cs_new * rowc, (size_t)mi.m * rowc, (size_t)o.m * rowc, units, st);
-  copy_units<int32_t>(nw.sizes, mi.sizes, (size_t)mi.m, cs_new, (size_t)mi.m, (size_t)o.m, units, st);
-  // offsets[o.m + 1 + i] = old rows + mini offsets[i + 1]
-  WAVE_LAUNCH("append_copy", copy_units_add_kernel, grid_for((size_t)mi.m * units), 256, 0, st, nw.offsets,
-              mi.offsets, (size_t)mi.m, cs_new + 1, (size_t)mi.m + 1, (size_t)o.m + 1, (size_t)1, units,
-              o.N_idx);
-  // positions: window row w is token (old N - old local count) + w
-  WAVE_LAUNCH("append_copy", copy_units_add_kernel, grid_for((size_t)mi.N_idx * units), 256, 0, st, nw.perm,
-              mi.perm, (size_t)mi.N_idx, rs_new, (size_t)mi.N_idx, (size_t)o.N_idx, (size_t)0, units,
-              o.N - g.lc_old);
-  copy_units<uint4>(nw.k_perm, mi.k_perm, (size_t)mi.N_idx * rowc, rs_new * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
-  copy_units<uint4>(nw.v_perm, mi.v_perm, (size_t)mi.N_idx * rowc, rs_new * rowc, (size_t)mi.N_idx * rowc, (size_t)o.N_idx * rowc, units, st);
-  return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
+  const size_t rowb = (size_t)D * es;
+  mi.centroids = static_cast<char*>(nw.centroids) + (size_t)o.m * rowb;
+  mi.vsum = static_cast<char*>(nw.vsum) + (size_t)o.m * rowb;
+  mi.sizes = nw.sizes + o.m;
+  mi.offsets = nw.offsets + o.m;
+  mi.cluster_capacity = cluster_stride(nw);
+  mi.perm = nw.perm + o.N_idx;
+  mi.k_perm = static_cast<char*>(nw.k_perm) + (size_t)o.N_idx * rowb;
+  mi.v_perm = static_cast<char*>(nw.v_perm) + (size_t)o.N_idx * rowb;
+  mi.row_capacity = row_stride(nw);
+  return launch_build(w + g.off_k, w + g.off_v, mi, iters, seed, w + g.off_build, st, o.S, o.N_idx,
+                      o.N - g.lc_old);
 }
 
 }  // namespace wave

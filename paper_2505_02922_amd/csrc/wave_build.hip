@@ -67,7 +67,20 @@ __global__ __launch_bounds__(256) void seg_mean_kernel(const T* __restrict__ K, 
   double acc[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
-  for (int i = grp; i < si.L_s; i += GROUPS) {
+  int i = grp;
+  for (; i + 3 * GROUPS < si.L_s; i += 4 * GROUPS) {  // four rows in flight, added in row order
+    uint4 raw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) raw[u] = load16(Ku + (size_t)(i + u * GROUPS) * D);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float f[EPC];
+      unpack<T>(raw[u], f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+    }
+  }
+  for (; i < si.L_s; i += GROUPS) {
     float f[EPC];
     unpack<T>(load16(Ku + (size_t)i * D), f);
 #pragma unroll
@@ -443,6 +456,61 @@ __device__ __forceinline__ void resident_assign_fragments(const bf16_t* X, const
   }
 }
 
+// The same step for few centroid tiles (short segments): one accumulator set and no
+// instruction interleaving, the next fragment's rows requested before the current one is
+// worked on.  Same similarities, same epilogue, same emit.
+template <int D, int NW, typename Emit>
+__device__ __forceinline__ void lean_assign_fragments(const bf16_t* X, const char* cent, int L_s, int k_s,
+                                                      int f_hi, Emit&& emit) {
+  using RT = ResidentTile<D>;
+  constexpr int KS = RT::KS, ROWB = RT::ROWB;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int ntiles = (k_s + 31) / 32, nfull = k_s / 32;
+  constexpr float B0 = kAssignBias;
+  const floatx16 bias = {B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0, B0};
+  auto load_frag = [&](int fb, uint4 (&dst)[KS]) {
+    const int row = min(32 * fb + col, L_s - 1);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) dst[s] = load16(X + (size_t)row * D + (2 * s + half) * 8);
+  };
+  uint4 cur[KS], nxt[KS];
+  if (wave < f_hi) load_frag(wave, cur);
+  for (int fb = wave; fb < f_hi; fb += NW) {
+    if (fb + NW < f_hi) load_frag(fb + NW, nxt);
+    int best[1] = {0}, second[1] = {0}, btile[1] = {0};
+    for (int t = 0; t < ntiles; ++t) {
+      const char* tile = cent + (size_t)(32 * t + col) * ROWB + half * 16;
+      floatx16 acc[1];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, load16(tile + s * 32));
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, cur[s]);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bv, s == 0 ? bias : acc[0], 0, 0, 0);
+      }
+      if (t < nfull) assign_epilogue<1, false>(acc, best, second, btile, t, half, k_s);
+      else assign_epilogue<1, true>(acc, best, second, btile, t, half, k_s);
+    }
+    // lanes l and l ^ 32 hold the same points over disjoint centroid rows
+    int brow = (best[0] & 27) | (4 * half);
+    const int ob = __shfl_xor(best[0], 32), os = __shfl_xor(second[0], 32);
+    const int ot = __shfl_xor(btile[0], 32), orow = __shfl_xor(brow, 32);
+    const int nsec = max(min(best[0], ob), max(second[0], os));
+    if (ob > best[0]) {
+      best[0] = ob;
+      btile[0] = ot;
+      brow = orow;
+    }
+    const int point = 32 * fb + col;
+    if (half == 0 && point < L_s) {
+      const float gap = __int_as_float(best[0]) - (nsec > 0 ? __int_as_float(nsec) : 0.f);
+      emit(point, btile[0] * 32 + brow, gap < kAssignGuard);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
+  }
+}
+
 template <int D, int NF, int NW>
 __global__ __launch_bounds__(64 * NW) void assign_resident_kernel(
     const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ assign,
@@ -685,25 +753,36 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
 // ============================================================================
 // Update: one group of LPR lanes per cluster sums its members' xhat in fp64.
 // ============================================================================
-// Cluster gc = sg * kk + c of segment si: the calling group of LPR lanes (lane `sub` of it)
-// sums the members' rows and writes the new centroid.
-template <typename T, int D>
-__device__ __forceinline__ void update_cluster(const T* xhat, T* chat, const int32_t* order,
-                                               const int32_t* count, const int32_t* start,
-                                               const SegInfo& si, int gc, int N_idx, int sub) {
+// One cluster's update by the calling group of LPR lanes (lane `sub` of it): the n member
+// rows ord[0, n) of the segment's points X are summed in fp64 in that order, U loads in
+// flight, and the normalised sum goes to dst (the lane's 16-byte chunk of the centroid row).
+// (STREAM: the rows are read once per launch and should not displace other lines in the caches)
+template <typename T, int D, int U, bool STREAM>
+__device__ __forceinline__ void update_cluster(const T* X, const int32_t* ord, int n, T* dst, int sub) {
+  auto load_row = [](const T* p) { return STREAM ? load16_stream(p) : load16(p); };
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC;
-  const int n = count[gc], st = start[gc];
   if (n == 0) return;  // an empty cluster keeps its centroid
-  const int32_t* ord = order + (size_t)si.unit * N_idx + si.seg_start + st;
-  const T* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D + sub * EPC;
+  X += sub * EPC;
   double acc[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
   int i = 0;
-  for (; i + 4 <= n; i += 4) {
+  for (; i + U <= n; i += U) {
+    uint4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) raw[u] = load_row(X + (size_t)ord[i + u] * D);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[EPC];
+      unpack<T>(raw[u], f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+    }
+  }
+  if (U > 4 && i + 4 <= n) {
     uint4 raw[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) raw[u] = load16_stream(X + (size_t)ord[i + u] * D);
+    for (int u = 0; u < 4; ++u) raw[u] = load_row(X + (size_t)ord[i + u] * D);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float f[EPC];
@@ -711,6 +790,7 @@ __device__ __forceinline__ void update_cluster(const T* xhat, T* chat, const int
 #pragma unroll
       for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
     }
+    i += 4;
   }
   for (; i < n; ++i) {
     float f[EPC];
@@ -728,7 +808,7 @@ __device__ __forceinline__ void update_cluster(const T* xhat, T* chat, const int
   const double rn = 1.0 / nrm;
 #pragma unroll
   for (int e = 0; e < EPC; ++e) o[e] = quant_store<T>(div_shared(acc[e], nrm, rn));
-  store16(chat + (size_t)gc * D + sub * EPC, *reinterpret_cast<uint4*>(o));
+  store16(dst, *reinterpret_cast<uint4*>(o));
 }
 
 template <typename T, int D>
@@ -744,17 +824,20 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   const int sg = gc / kk, c = gc - sg * kk;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
   if (c >= si.k_s) return;
-  update_cluster<T, D>(xhat, chat, order, count, start, si, gc, N_idx, sub);
+  const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
+  update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC, sub);
 }
 
 // ============================================================================
 // Short segments (an index update's 1K tokens into 64 clusters; small builds): all T
-// iterations of one segment in ONE workgroup of 16 waves.  Per iteration: centroids
-// into LDS, assign (the resident MFMA form), near-ties re-decided with fp64
-// similarities by one wave each, the counting sort, the update; the steps are
-// those of the kernels above, separated by workgroup barriers instead of
-// launches (assignments, order and centroids still pass through global memory,
-// which one workgroup sees coherently).  Launches per build: 5 instead of 4 T + 3.
+// iterations of one segment in ONE workgroup of 16 waves, with the centroids, the
+// assignments, the sorted order and the cluster counts in LDS from the first
+// iteration to the last.  Per iteration: assign (the resident MFMA form), near-ties
+// re-decided with fp64 similarities by one wave each, the counting sort, the update
+// straight into the LDS centroid rows; the steps are those of the kernels above,
+// separated by workgroup barriers instead of launches.  Only the normalised keys are
+// read from global memory; the last iteration's order, counts and first positions
+// are written there for the finalize step.  Launches per build: 5 instead of 4 T + 3.
 // ============================================================================
 constexpr int SMALL_L_MAX = 2048;   // points per segment
 constexpr int SMALL_K_MAX = 128;    // clusters per segment
@@ -762,41 +845,57 @@ constexpr int SMALL_NW = 16;
 
 template <int D>
 inline size_t small_kmeans_lds(int kk) {
-  return (size_t)32 * ((kk + 31) / 32) * ResidentTile<D>::ROWB + sizeof(int) * ((size_t)SMALL_NW * kk + kk) +
-         sizeof(int) * SMALL_L_MAX;
+  return (size_t)32 * ((kk + 31) / 32) * ResidentTile<D>::ROWB +
+         sizeof(int) * ((size_t)SMALL_NW * kk + kk + 2 * SMALL_L_MAX + 2 * (size_t)kk);
 }
 
 template <int D>
 __global__ __launch_bounds__(64 * SMALL_NW) void kmeans_small_kernel(
-    const bf16_t* __restrict__ xhat, bf16_t* chat, int32_t* assign, int32_t* order, int32_t* count,
-    int32_t* start, int S, int L, int kk, int N_idx, int iters, int key_bits) {
+    const bf16_t* __restrict__ xhat, const bf16_t* __restrict__ chat, int32_t* __restrict__ order,
+    int32_t* __restrict__ count, int32_t* __restrict__ start, int S, int L, int kk, int N_idx, int iters,
+    int key_bits) {
   using RT = ResidentTile<D>;
   constexpr int NT = 64 * SMALL_NW, LPR = D / 8, GROUPS = NT / LPR;
   extern __shared__ __attribute__((aligned(16))) char small_lds[];
   char* cent = small_lds;
-  int* hist = reinterpret_cast<int*>(small_lds + (size_t)32 * ((kk + 31) / 32) * RT::ROWB);
-  int* flags = hist + SMALL_NW * kk + kk;
+  int* hist = reinterpret_cast<int*>(small_lds + (size_t)32 * ((kk + 31) / 32) * RT::ROWB);  // sort_segment's
+  int* a_s = hist + SMALL_NW * kk + kk;   // cluster of every point
+  int* ord_s = a_s + SMALL_L_MAX;         // points by cluster; before the sort: the near-tie list
+  int* cnt_s = ord_s + SMALL_L_MAX;
+  int* first_s = cnt_s + kk;
+  int* flags = ord_s;
   __shared__ int nflag;
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bf16_t* X = xhat + ((size_t)si.unit * N_idx + si.seg_start) * D;
-  bf16_t* Cs = chat + (size_t)sg * kk * D;
-  int32_t* a = assign + (size_t)si.unit * N_idx + si.seg_start;
+  const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
+  const bf16_t* X = xhat + p0 * D;
   const int nfrag = (si.L_s + 31) / 32;
+  resident_load_centroids<D, NT>(chat + (size_t)sg * kk * D, si.k_s, cent);
+#ifdef WAVE_TRACE  // phase times of workgroup 0 (100 MHz clock), printed at the end
+  unsigned long long tp[5] = {0, 0, 0, 0, 0}, tl = wall_clock64();
+  int nf_total = 0;
+#define WAVE_PHASE(k) do { const unsigned long long now_ = wall_clock64(); tp[k] += now_ - tl; tl = now_; } while (0)
+#else
+#define WAVE_PHASE(k) do { } while (0)
+#endif
   for (int t = 0; t < iters; ++t) {
-    resident_load_centroids<D, NT>(Cs, si.k_s, cent);
     if (tid == 0) nflag = 0;
     __syncthreads();
-    resident_assign_fragments<D, 1, SMALL_NW>(X, cent, si.L_s, si.k_s, 0, nfrag,
-                                              [&](int point, int cluster, bool near_tie) {
-                                                a[point] = cluster;
-                                                if (near_tie) flags[atomicAdd(&nflag, 1)] = point;
-                                              });
+    WAVE_PHASE(0);
+    lean_assign_fragments<D, SMALL_NW>(X, cent, si.L_s, si.k_s, nfrag,
+                                       [&](int point, int cluster, bool near_tie) {
+                                         a_s[point] = cluster;
+                                         if (near_tie) flags[atomicAdd(&nflag, 1)] = point;
+                                       });
     __syncthreads();
+    WAVE_PHASE(1);
     // near-ties: fp64 similarities in index order against the LDS copy of the centroids,
     // ties to the lowest centroid (the arithmetic of refine_kernel)
     const int nf = nflag;
+#ifdef WAVE_TRACE
+    nf_total += nf;
+#endif
     for (int it = wave; it < nf; it += SMALL_NW) {
       const int point = flags[it];
       const bf16_t* xr = X + (size_t)point * D;
@@ -826,17 +925,30 @@ __global__ __launch_bounds__(64 * SMALL_NW) void kmeans_small_kernel(
           bi = oi;
         }
       }
-      if (lane == 0) a[point] = bi;
+      if (lane == 0) a_s[point] = bi;
     }
     __syncthreads();
-    sort_segment(a, order + (size_t)si.unit * N_idx + si.seg_start, count + (size_t)sg * kk,
-                 start + (size_t)sg * kk, si.L_s, kk, key_bits, hist);
+    WAVE_PHASE(2);
+    sort_segment(a_s, ord_s, cnt_s, first_s, si.L_s, kk, key_bits, hist);
     __syncthreads();
-    if (t + 1 < iters) {
+    WAVE_PHASE(3);
+    if (t + 1 < iters)
       for (int c = tid / LPR; c < si.k_s; c += GROUPS)
-        update_cluster<bf16_t, D>(xhat, chat, order, count, start, si, sg * kk + c, N_idx, tid % LPR);
-      __syncthreads();
-    }
+        update_cluster<bf16_t, D, 8, false>(X, ord_s + first_s[c], cnt_s[c],
+                                     reinterpret_cast<bf16_t*>(cent + (size_t)c * RT::ROWB) + (tid % LPR) * 8,
+                                     tid % LPR);
+    WAVE_PHASE(4);
+  }
+#ifdef WAVE_TRACE
+  if (blockIdx.x == 0 && (tid == 0 || tid == 1023))
+    printf("kmeans_small tid %d (x10 ns): top %llu assign %llu refine %llu sort %llu update %llu; near-ties %d\n", tid,
+           tp[0], tp[1], tp[2], tp[3], tp[4], nf_total);
+#endif
+#undef WAVE_PHASE
+  for (int i = tid; i < si.L_s; i += NT) order[p0 + i] = ord_s[i];
+  for (int c = tid; c < kk; c += NT) {
+    count[(size_t)sg * kk + c] = cnt_s[c];
+    start[(size_t)sg * kk + c] = first_s[c];
   }
 }
 
@@ -849,7 +961,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     const int32_t* __restrict__ count, const int32_t* __restrict__ start, T* __restrict__ centroids,
     T* __restrict__ vsum, int32_t* __restrict__ sizes, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, T* __restrict__ k_perm, T* __restrict__ v_perm, int S, int L, int kk,
-    int N, int N_idx, int n_sink, int m, int mc, int nclusters, int row_stride) {
+    int N, int N_idx, int n_sink, int m, int mc, int nclusters, int row_stride, int row_base, int pos_base) {
+  // row_base, pos_base: added to the offsets and to the positions (an update's clusters continue
+  // the rows and the token positions of the index they are written behind)
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   const int gc = blockIdx.x * GROUPS + grp;
@@ -864,8 +978,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(
   const int row0 = si.seg_start + st;
   if (sub == 0) {
     sizes[(size_t)si.unit * mc + cid] = n;  // mc: clusters per unit in the meta-index arrays
-    offsets[(size_t)si.unit * (mc + 1) + cid] = row0;
-    if (cid == m - 1) offsets[(size_t)si.unit * (mc + 1) + m] = N_idx;
+    offsets[(size_t)si.unit * (mc + 1) + cid] = row0 + row_base;
+    if (cid == m - 1) offsets[(size_t)si.unit * (mc + 1) + m] = N_idx + row_base;
   }
   const int32_t* ord = order + urow + si.seg_start + st;
   const T* Ku = K + ((size_t)si.unit * N + n_sink + si.seg_start) * D + sub * EPC;
@@ -881,7 +995,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     float f[EPC];
     store16(k_perm + (orow + row0 + i) * D + sub * EPC, k0);
     store16(v_perm + (orow + row0 + i) * D + sub * EPC, v0);
-    if (sub == 0) perm[orow + row0 + i] = n_sink + si.seg_start + pa;
+    if (sub == 0) perm[orow + row0 + i] = n_sink + si.seg_start + pa + pos_base;
     unpack<T>(k0, f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
@@ -891,7 +1005,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     if (i + 1 < n) {
       store16(k_perm + (orow + row0 + i + 1) * D + sub * EPC, k1);
       store16(v_perm + (orow + row0 + i + 1) * D + sub * EPC, v1);
-      if (sub == 0) perm[orow + row0 + i + 1] = n_sink + si.seg_start + pb;
+      if (sub == 0) perm[orow + row0 + i + 1] = n_sink + si.seg_start + pb + pos_base;
       unpack<T>(k1, f);
 #pragma unroll
       for (int e = 0; e < EPC; ++e) ka[e] += (double)f[e];
@@ -1006,7 +1120,8 @@ static void launch_assign(const T* xhat, const T* chat, int32_t* assign, int32_t
 
 template <typename T, int D>
 static wave_status build_td(const void* K_, const void* V_, const wave_index& ix, int iters,
-                            uint64_t seed, void* ws, hipStream_t st, int seg_id_base) {
+                            uint64_t seed, void* ws, hipStream_t st, int seg_id_base, int row_base,
+                            int pos_base) {
   const T* K = static_cast<const T*>(K_);
   const T* V = static_cast<const T*>(V_);
   const int units = ix.B * ix.Hkv;
@@ -1066,7 +1181,7 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     small = Lmax <= SMALL_L_MAX && kk <= SMALL_K_MAX && !no_small_kmeans();
     if (small)
       WAVE_LAUNCH("kmeans_small", (kmeans_small_kernel<D>), g.segs, 64 * SMALL_NW, small_kmeans_lds<D>(kk), st,
-                  xhat, chat, assign, order, count, start, S, L, kk, N_idx, iters, kb);
+                  xhat, chat, order, count, start, S, L, kk, N_idx, iters, kb);
   }
   for (int t = 0; t < iters && !small; ++t) {
     launch_assign<T, D>(xhat, chat, assign, flag, nflag, S, L, kk, N_idx, g.segs, st);
@@ -1081,18 +1196,18 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
               static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,
               static_cast<T*>(ix.k_perm), static_cast<T*>(ix.v_perm), S, L, kk, ix.N, N_idx, ns, ix.m,
-              cluster_stride(ix), ncl, row_stride(ix));
+              cluster_stride(ix), ncl, row_stride(ix), row_base, pos_base);
   return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
 }
 
 wave_status launch_build(const void* K, const void* V, const wave_index& ix, int iters, uint64_t seed,
-                         void* ws, hipStream_t st, int seg_id_base) {
+                         void* ws, hipStream_t st, int seg_id_base, int row_base, int pos_base) {
   if (ix.dtype == WAVE_BF16) {
-    if (ix.d == 128) return build_td<bf16_t, 128>(K, V, ix, iters, seed, ws, st, seg_id_base);
-    if (ix.d == 64) return build_td<bf16_t, 64>(K, V, ix, iters, seed, ws, st, seg_id_base);
+    if (ix.d == 128) return build_td<bf16_t, 128>(K, V, ix, iters, seed, ws, st, seg_id_base, row_base, pos_base);
+    if (ix.d == 64) return build_td<bf16_t, 64>(K, V, ix, iters, seed, ws, st, seg_id_base, row_base, pos_base);
   } else {
-    if (ix.d == 128) return build_td<float, 128>(K, V, ix, iters, seed, ws, st, seg_id_base);
-    if (ix.d == 64) return build_td<float, 64>(K, V, ix, iters, seed, ws, st, seg_id_base);
+    if (ix.d == 128) return build_td<float, 128>(K, V, ix, iters, seed, ws, st, seg_id_base, row_base, pos_base);
+    if (ix.d == 64) return build_td<float, 64>(K, V, ix, iters, seed, ws, st, seg_id_base, row_base, pos_base);
   }
   return WAVE_ERR_SHAPE;
 }

@@ -235,12 +235,13 @@ wave_status launch_full_attention(const void* q, const void* K, const void* V, i
                                   int Hkv, int N, int d, float* out, float* lse, void* ws,
                                   hipStream_t st);
 wave_status launch_build(const void* K, const void* V, const wave_index& ix, int iters,
-                         uint64_t seed, void* ws, hipStream_t st, int seg_id_base = 0);
+                         uint64_t seed, void* ws, hipStream_t st, int seg_id_base = 0, int row_base = 0,
+                         int pos_base = 0);
 // Incremental update: geometry of its workspace and the launches (wave_append.hip).
 struct AppendGeom {
   int F, ks, lc_old;              // flushed segments, clusters per update segment, old local count
   wave_index mini;                // the flushed tokens as an index of their own (pointers unset)
-  size_t off_k, off_v, off_c, off_vs, off_sizes, off_offsets, off_perm, off_kp, off_vp, off_build, total;
+  size_t off_k, off_v, off_build, total;  // the flushed keys and values, the build's workspace
 };
 AppendGeom append_geometry(const wave_index& old_ix, int n_new, int n_local_min, int U, int k_u);
 wave_status launch_append(const wave_index& old_ix, const void* K_new, const void* V_new, int n_new,
