@@ -257,8 +257,12 @@ wave_status wave_attention_decode_static(const void *q, const wave_index *ix, in
  * wave_attention_decode itself; est_clusters = 0 leaves the exact zones only.
  * Same arguments otherwise; the workspace size comes from
  * wave_attention_decode_budget_workspace (0 if the arguments are invalid).
- * This path is not tuned: scores, two selections, steady, retrieval,
- * estimation and merge are launches of their own. */
+ * Up to 65536 clusters per KV head it runs in four launches (scores with the
+ * steady zone, both selections at once, retrieval with estimation, merge);
+ * beyond that its steps are launches of their own.  Every head reads its own
+ * estimated clusters' value sums, so a budget moves about as many bytes as
+ * estimating every cluster once per KV head and is not faster than
+ * wave_attention_decode. */
 size_t wave_attention_decode_budget_workspace(const wave_index *ix, int Hq, int topk_clusters,
                                               int est_clusters);
 wave_status wave_attention_decode_budget(const void *q, const wave_index *ix, int Hq,

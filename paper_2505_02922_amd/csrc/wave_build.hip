@@ -667,8 +667,14 @@ constexpr int SORT_HIST_INTS = 11264;  // LDS budget for the per-wave counters
 
 // One segment's points a[0, L_s) sorted into ord[] by the calling workgroup of W waves;
 // per-cluster counts and first positions to cnt[] / first[] (kk entries each).
+// prev (may be null): the clusters of the round before, replaced by this round's on the way; when
+// a point's cluster differs from it (and `compare` is set: not in the first round), both clusters
+// are marked in changed[] (plain stores of 1: who wins does not matter).  The update step
+// recomputes only marked clusters: a cluster nobody entered or left keeps its member sum and with
+// it, bit for bit, its centroid.
 __device__ __forceinline__ void sort_segment(const int32_t* a, int32_t* ord, int32_t* cnt, int32_t* first,
-                                             int L_s, int kk, int key_bits, int* hist) {
+                                             int L_s, int kk, int key_bits, int* hist, int32_t* prev = nullptr,
+                                             int32_t* changed = nullptr, bool compare = false) {
   const int W = blockDim.x >> 6;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int* tot = hist + W * kk;
@@ -676,7 +682,18 @@ __device__ __forceinline__ void sort_segment(const int32_t* a, int32_t* ord, int
   __syncthreads();
   const int stripe = (L_s + W - 1) / W;
   const int s0 = min(L_s, wave * stripe), s1 = min(L_s, s0 + stripe);
-  for (int i = s0 + lane; i < s1; i += 64) atomicAdd(&hist[wave * kk + a[i]], 1);
+  for (int i = s0 + lane; i < s1; i += 64) {
+    const int c = a[i];
+    atomicAdd(&hist[wave * kk + c], 1);
+    if (prev) {
+      const int before = prev[i];
+      if (compare && before != c) {
+        changed[before] = 1;
+        changed[c] = 1;
+      }
+      prev[i] = c;
+    }
+  }
   __syncthreads();
   // per cluster: exclusive scan over the waves, total into tot[]
   for (int c = tid; c < kk; c += blockDim.x) {
@@ -740,14 +757,17 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ order,
                                                     int32_t* __restrict__ count,
                                                     int32_t* __restrict__ start,
-                                                    int32_t* __restrict__ flag_count, int S, int L,
-                                                    int kk, int N_idx, int key_bits) {
+                                                    int32_t* __restrict__ flag_count,
+                                                    int32_t* __restrict__ prev,
+                                                    int32_t* __restrict__ changed, int first_round, int S,
+                                                    int L, int kk, int N_idx, int key_bits) {
   extern __shared__ int hist[];  // [W][kk], then kk ints of scan space
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
   if (sg == 0 && threadIdx.x == 0) *flag_count = 0;  // the refine pass before this one has consumed it
   sort_segment(assign + (size_t)si.unit * N_idx + si.seg_start, order + (size_t)si.unit * N_idx + si.seg_start,
-               count + (size_t)sg * kk, start + (size_t)sg * kk, si.L_s, kk, key_bits, hist);
+               count + (size_t)sg * kk, start + (size_t)sg * kk, si.L_s, kk, key_bits, hist,
+               prev + (size_t)si.unit * N_idx + si.seg_start, changed + (size_t)sg * kk, !first_round);
 }
 
 // ============================================================================
@@ -815,7 +835,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
                                                      const int32_t* __restrict__ order,
                                                      const int32_t* __restrict__ count,
-                                                     const int32_t* __restrict__ start, int S, int L,
+                                                     const int32_t* __restrict__ start,
+                                                     int32_t* __restrict__ changed, int all, int S, int L,
                                                      int kk, int N_idx, int nclusters) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
@@ -824,6 +845,11 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   const int sg = gc / kk, c = gc - sg * kk;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
   if (c >= si.k_s) return;
+  // Only clusters that a point entered or left in this round (marked by the sort step) are
+  // summed again; `all`: the first round, every cluster.  The mark is consumed here.
+  const int touched = changed[gc];
+  if (sub == 0) changed[gc] = 0;
+  if (!all && !touched) return;
   const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
   update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC, sub);
 }
@@ -1070,7 +1096,8 @@ BuildGeom build_geometry(const wave_index& ix) {
   g.off_chat = o;   o = align_up(o + ncl * ix.d * es);
   g.off_assign = o; o = align_up(o + pts * sizeof(int32_t));
   g.off_order = o;  o = align_up(o + pts * sizeof(int32_t));
-  g.off_count = o;  o = align_up(o + 2 * ncl * sizeof(int32_t));   // count, then start
+  g.off_prev = o;   o = align_up(o + pts * sizeof(int32_t));
+  g.off_count = o;  o = align_up(o + 3 * ncl * sizeof(int32_t));   // count, start, changed marks
   g.off_flag = o;   o = align_up(o + pts * sizeof(int32_t));
   g.off_nflag = o;  o = align_up(o + 256);
   g.off_init = o;   o = align_up(o + (size_t)g.segs * ix.d * sizeof(double));  // segment means
@@ -1151,6 +1178,8 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
   const int ncl = g.segs * kk;
   int32_t* count = reinterpret_cast<int32_t*>(w + g.off_count);
   int32_t* start = count + ncl;
+  int32_t* changed = start + ncl;  // per cluster: a point entered or left it in the current round
+  int32_t* prev = reinterpret_cast<int32_t*>(w + g.off_prev);  // every point's cluster of the round before
   int32_t* flag = reinterpret_cast<int32_t*>(w + g.off_flag);
   int32_t* nflag = reinterpret_cast<int32_t*>(w + g.off_nflag);
   double* mean = reinterpret_cast<double*>(w + g.off_init);
@@ -1187,11 +1216,12 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     launch_assign<T, D>(xhat, chat, assign, flag, nflag, S, L, kk, N_idx, g.segs, st);
     WAVE_LAUNCH("refine", (refine_kernel<T, D>), 1024, 256, 0, st, xhat, chat, assign, flag, nflag, S,
                 L, kk, N_idx);
+    // (first round: nothing to compare with, every cluster is updated and every mark cleared)
     WAVE_LAUNCH("sort", sort_kernel, g.segs, 64 * W, sort_lds, st, assign, order, count, start, nflag,
-                S, L, kk, N_idx, kb);
+                prev, changed, t == 0 ? 1 : 0, S, L, kk, N_idx, kb);
     if (t + 1 < iters)
       WAVE_LAUNCH("update", (update_kernel<T, D>), cl_grid, 256, 0, st, xhat, chat, order, count,
-                  start, S, L, kk, N_idx, ncl);
+                  start, changed, t == 0 ? 1 : 0, S, L, kk, N_idx, ncl);
   }
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
               static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,

@@ -205,7 +205,7 @@ struct DecodeGeom {
 DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk);
 
 struct BuildGeom {
-  size_t off_xhat, off_chat, off_assign, off_order, off_count, off_flag, off_nflag, off_init, total;
+  size_t off_xhat, off_chat, off_assign, off_order, off_prev, off_count, off_flag, off_nflag, off_init, total;
   int units, segs;                 // B*Hkv, units * S
 };
 BuildGeom build_geometry(const wave_index& ix);

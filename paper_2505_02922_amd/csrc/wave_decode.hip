@@ -2130,7 +2130,7 @@ __device__ __forceinline__ void steady_rows_partial(const T* __restrict__ q,
 // Two selections of every head in one launch (the r best and the r + e best clusters of the
 // budgeted estimation zone): even workgroups take the first, odd ones the second.  Each
 // leaves its ascending id list and count.
-template <typename T, int D, int NT, int VPT>
+template <typename T, int D, int NT, int VPT, bool LDSK>
 __global__ __launch_bounds__(NT) void select_two_kernel(
     const T* __restrict__ q, const T* __restrict__ C, const int32_t* __restrict__ offsets,
     const float* __restrict__ z, const float* __restrict__ cn2part, int cn2_chunks, int Hq, int Hkv,
@@ -2141,7 +2141,7 @@ __global__ __launch_bounds__(NT) void select_two_kernel(
   const int bh = blockIdx.x >> 1;
   const bool second = blockIdx.x & 1;
   int ntok;
-  select_core<T, D, NT, VPT, true>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, second ? r2 : r1,
+  select_core<T, D, NT, VPT, LDSK>(q, C, offsets, z, cn2part, cn2_chunks, Hq, Hkv, m, second ? r2 : r1,
                                    second ? rcap2 : rcap1, mwords, mc, second ? r2 : r1, second ? ids2 : ids1,
                                    nullptr, nullptr, bitmap, second ? nsel2 : nsel1,
                                    second ? nullptr : user_selected, vsum, scale_log2, nullptr, 0, 0, bh,
@@ -2770,11 +2770,13 @@ __device__ __forceinline__ void publish_token_ranges(int bh, int nsel, int ntok,
 // bound T of the head's r-th largest score (at least r maxima reach T, so r
 // different clusters score at least T): one histogram sweep over m / 16 values
 // and a scan.  With the fp32 error bound `guard`, every cluster the exact ranking
-// could select scores at least T - guard.  One sweep over the head's scores
-// counts those clusters per (sweep, wave), a second lists them in ascending
-// order in LDS (about 1.1 r on clustered data), and the exact ranking
-// (select_core: fp64 re-scoring inside the guard band, ties to the lower id) runs
-// on that list.  The workgroup then leaves everything the retrieval launch
+// could select scores at least T - guard.  Only tiles whose maximum reaches that
+// bound can hold such a cluster: they are listed from the table, their scores
+// read (16 per tile) and the passing ones marked in an LDS bitmap of all
+// clusters, one atomic per tile; a scan of the bitmap gives the passing clusters
+// in ascending order (about 1.1 r on clustered data), their scores are read
+// again in that order, and the exact ranking (select_core: fp64 re-scoring
+// inside the guard band, ties to the lower id) runs on that list.  The workgroup then leaves everything the retrieval launch
 // needs: ids, first rows, running token counts, the first cluster of every token
 // range, and the selected clusters' estimation terms with a minus sign.  When no
 // bound exists (fewer than r tiles) or more than FILT_CAP clusters pass (many
@@ -2786,8 +2788,7 @@ constexpr int FILT_VPT = FILT_CAP / FILT_NT;
 constexpr int FILT_MAX_SWEEPS = 256;   // of FILT_NT scores each
 // LDS of the selecting role: ids and scores of the clusters that pass, the bitmap of all
 // clusters (whose space the histogram uses before it and the exact ranking's keys after it),
-// the selected ids (before them: the passing clusters in the order they were found), and
-// the scores that go with that unordered list
+// the selected ids, and FILT_CAP spare words
 constexpr size_t FILT_LDS = sizeof(int) * (4 * (size_t)FILT_CAP + (size_t)FILT_MAX_SWEEPS * FILT_NT / 32);
 // largest r the filtered selection is used for: about 1.1 r clusters pass on clustered data
 inline int filtered_max_r() { return (FILT_CAP - 64) * 4 / 5; }
@@ -2818,8 +2819,6 @@ __device__ __forceinline__ void select_filtered(
   int* f_hist = reinterpret_cast<int*>(skeys);            // free until the exact ranking loads its keys
   uint32_t* fbits = reinterpret_cast<uint32_t*>(dyn) + 2 * FILT_CAP;  // bitmap of the clusters that pass
   int32_t* s_ids = reinterpret_cast<int32_t*>(dyn) + 2 * FILT_CAP + FILT_MAX_SWEEPS * NT / 32;
-  int32_t* uid = s_ids;                                  // passing clusters as found (unordered) ...
-  float* uz = reinterpret_cast<float*>(s_ids + FILT_CAP);  // ... and their scores
   __shared__ int f_scan[NW];
   __shared__ int f_sh[4];
   __shared__ float f_shf[2];
@@ -2943,32 +2942,18 @@ __device__ __forceinline__ void select_filtered(
           for (int j = 0; j < SCORE_TILE; ++j) sc[u][j] = zz[min(t16[u] + j, m - 1)];
         }
       }
-      uint32_t pm[TB];  // bit j: score j of tile u passes
-      int nmine = 0;
+      // a tile's 16 pass bits are half a bitmap word: one LDS atomic per tile
+      static_assert(SCORE_TILE == 16, "a tile is half a bitmap word");
 #pragma unroll
       for (int u = 0; u < TB; ++u) {
-        pm[u] = 0u;
+        uint32_t pm = 0u;  // bit j: score j of tile u passes
         if (e0 + u * NT + tid < ntl) {
 #pragma unroll
           for (int j = 0; j < SCORE_TILE; ++j)
-            if (t16[u] + j < m && order_key(sc[u][j] + 0.0f) >= kt) pm[u] |= 1u << j;
+            if (t16[u] + j < m && order_key(sc[u][j] + 0.0f) >= kt) pm |= 1u << j;
         }
-        nmine += __popc(pm[u]);
+        if (pm) atomicOr(&fbits[t16[u] >> 5], pm << (t16[u] & 31));
       }
-      int slot = wave_excl_scan_alloc(nmine, &f_sh[2]);
-#pragma unroll
-      for (int u = 0; u < TB; ++u)
-#pragma unroll
-        for (int j = 0; j < SCORE_TILE; ++j)
-          if ((pm[u] >> j) & 1u) {
-            const int i = t16[u] + j;
-            atomicOr(&fbits[i >> 5], 1u << (i & 31));
-            if (slot < FILT_CAP) {
-              uid[slot] = i;
-              uz[slot] = sc[u][j] + 0.0f;
-            }
-            ++slot;
-          }
     }
   }
   __syncthreads();
@@ -2999,15 +2984,15 @@ __device__ __forceinline__ void select_filtered(
       }
     }
     __syncthreads();  // (also: every thread has read its bitmap words; the key region is free)
-    // the scores were seen when the bits were set: each finds its place in the ordered list
-    for (int u = tid; u < cnt; u += NT) {
-      const int id = uid[u];
-      int a = 0, e = cnt;  // the position of id in cand_id[0, cnt)
-      while (e - a > 1) {
-        const int mid = (a + e) >> 1;
-        if (cand_id[mid] <= id) a = mid; else e = mid;
-      }
-      cand_z[a] = uz[u];
+    // the listed clusters' scores, read again in list order (four requests in flight per thread)
+    static_assert(FILT_CAP == 4 * NT, "four candidates per thread");
+    {
+      float zv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) zv[u] = zz[cand_id[min(u * NT + tid, cnt - 1)]];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (u * NT + tid < cnt) cand_z[u * NT + tid] = zv[u] + 0.0f;
     }
     __syncthreads();
     WAVE_STAMP(trace, 3);
@@ -3731,19 +3716,25 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const int slots = g.slots + 1, spare_slot = g.slots;
 
-  // Keys of a head fit in LDS: four launches.  The scores with the steady zone as extra
-  // workgroups; both selections at once (two workgroups per head); retrieval and estimation in
-  // one launch (neither needs the other); the merge.
-  if (m <= 512 * 32 && est_clusters > 0) {
+  // Keys of a head fit in LDS (whole, or their upper halves with a re-read hot range): four
+  // launches.  The scores with the steady zone as extra workgroups; both selections at once (two
+  // workgroups per head); retrieval and estimation in one launch (neither needs the other); the merge.
+  if (m <= 1024 * 64 && est_clusters > 0) {
     WAVE_LAUNCH("scores+steady", (score_steady_kernel<T, D, G>), units * (g.score_chunks + g.steady_chunks),
                 256, 0, st, q, C, ix.sizes, z, cn2, ix.Hkv, m, mc, g.score_chunks, static_cast<float*>(nullptr),
                 units * g.score_chunks, static_cast<const T*>(ix.k_steady), static_cast<const T*>(ix.v_steady),
                 ix.p, steady_stride(ix), g.steady_chunks, g.steady_rows, slots, 0, scale_log2, part,
                 static_cast<int32_t*>(nullptr), static_cast<int32_t*>(nullptr), 0);
-    WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32>), 2 * heads, 512,
-                sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, q, C, ix.offsets, z, cn2,
-                g.score_chunks, Hq, ix.Hkv, m, g.mwords, mc, bitmap, g.r, g.rcap1, ids1, nsel1, selected, g.k2,
-                g.rcap2, ids2, nsel2, VS, scale_log2);
+#define WAVE_TWO_ARGS                                                                                   \
+  q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, g.mwords, mc, bitmap, g.r, g.rcap1, ids1, nsel1, \
+      selected, g.k2, g.rcap2, ids2, nsel2, VS, scale_log2
+    if (m <= 512 * 32)
+      WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32, true>), 2 * heads, 512,
+                  sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, WAVE_TWO_ARGS);
+    else
+      WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 1024, 64, false>), 2 * heads, 1024,
+                  sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_TWO_ARGS);
+#undef WAVE_TWO_ARGS
     const int n_est = heads * g.est_chunks;
     WAVE_LAUNCH("gather+estimate", (gather_est_kernel<T, D>), n_est + heads * g.gather_chunks, 256, 0, st, q,
                 static_cast<const T*>(ix.k_perm), static_cast<const T*>(ix.v_perm), ids1, nsel1, ids2, nsel2,
