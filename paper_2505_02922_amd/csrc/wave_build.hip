@@ -854,6 +854,46 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC, sub);
 }
 
+// The update of the later rounds, when most clusters are untouched: a workgroup reads the marks
+// of 256 consecutive clusters at once, lists the marked ones in LDS and its 16-lane groups take
+// them from the list (one mark per group and workgroup, as in update_kernel, is a round trip and
+// a workgroup launch per 16 clusters even when none of them changed).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void update_touched_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
+                                                             const int32_t* __restrict__ order,
+                                                             const int32_t* __restrict__ count,
+                                                             const int32_t* __restrict__ start,
+                                                             int32_t* __restrict__ changed, int S, int L,
+                                                             int kk, int N_idx, int nclusters) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  __shared__ int list[256];
+  __shared__ int wave_n[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int gc_mine = blockIdx.x * 256 + tid;
+  const bool on = gc_mine < nclusters && changed[gc_mine] != 0;
+  if (on) changed[gc_mine] = 0;
+  const uint64_t mk = __ballot(on);
+  if (lane == 0) wave_n[wave] = __popcll(mk);
+  __syncthreads();
+  int base = 0, n = 0;
+  for (int w = 0; w < 4; ++w) {
+    base += w < wave ? wave_n[w] : 0;
+    n += wave_n[w];
+  }
+  if (on) list[base + __popcll(mk & ((1ull << lane) - 1ull))] = gc_mine;
+  __syncthreads();
+  const int sub = tid % LPR;
+  for (int j = tid / LPR; j < n; j += GROUPS) {
+    const int gc = list[j];
+    const int sg = gc / kk, c = gc - sg * kk;
+    const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+    if (c >= si.k_s) continue;
+    const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
+    update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC,
+                                  sub);
+  }
+}
+
 // ============================================================================
 // Short segments (an index update's 1K tokens into 64 clusters; small builds): all T
 // iterations of one segment in ONE workgroup of 16 waves, with the centroids, the
@@ -1219,9 +1259,14 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     // (first round: nothing to compare with, every cluster is updated and every mark cleared)
     WAVE_LAUNCH("sort", sort_kernel, g.segs, 64 * W, sort_lds, st, assign, order, count, start, nflag,
                 prev, changed, t == 0 ? 1 : 0, S, L, kk, N_idx, kb);
-    if (t + 1 < iters)
-      WAVE_LAUNCH("update", (update_kernel<T, D>), cl_grid, 256, 0, st, xhat, chat, order, count,
-                  start, changed, t == 0 ? 1 : 0, S, L, kk, N_idx, ncl);
+    if (t + 1 < iters) {
+      if (t == 0)
+        WAVE_LAUNCH("update", (update_kernel<T, D>), cl_grid, 256, 0, st, xhat, chat, order, count,
+                    start, changed, 1, S, L, kk, N_idx, ncl);
+      else
+        WAVE_LAUNCH("update", (update_touched_kernel<T, D>), (ncl + 255) / 256, 256, 0, st, xhat, chat,
+                    order, count, start, changed, S, L, kk, N_idx, ncl);
+    }
   }
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,
               static_cast<T*>(ix.centroids), static_cast<T*>(ix.vsum), ix.sizes, ix.offsets, ix.perm,
