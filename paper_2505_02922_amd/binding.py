@@ -447,11 +447,19 @@ def wave_profile_read() -> Dict[str, Tuple[float, int]]:
 
 def index_from_arrays(dtype: torch.dtype, B: int, Hkv: int, d: int, N: int, n_sink: int, n_local: int,
                       segment_len: int, clusters_per_segment: int, arrays: Dict[str, torch.Tensor],
-                      device="cuda") -> Index:
+                      device="cuda", row_capacity: int = 0, steady_capacity: int = 0,
+                      cluster_capacity: int = 0) -> Index:
     """Imports an index from host arrays (the index is plain data: importing it
-    is copying its nine arrays)."""
-    ix = alloc_index(dtype, B, Hkv, d, N, n_sink, n_local, segment_len, clusters_per_segment, device)
+    is copying its nine arrays).  The arrays are dense; with capacities the device arrays have
+    room behind each unit's entries."""
+    ix = alloc_index(dtype, B, Hkv, d, N, n_sink, n_local, segment_len, clusters_per_segment, device,
+                     row_capacity=row_capacity, steady_capacity=steady_capacity,
+                     cluster_capacity=cluster_capacity)
+    used = {"centroids": ix.m, "vsum": ix.m, "sizes": ix.m, "offsets": ix.m + 1, "perm": ix.N_idx,
+            "k_perm": ix.N_idx, "v_perm": ix.N_idx, "k_steady": ix.p, "v_steady": ix.p}
     for name in BUFFER_NAMES:
-        if ix.t[name].numel():
-            ix.t[name].copy_(arrays[name].reshape(ix.t[name].shape).to(ix.t[name].dtype))
+        t = ix.t[name]
+        if t.numel():
+            n = used[name]
+            t[:, :, :n].copy_(arrays[name].reshape((B, Hkv, n) + tuple(t.shape[3:])).to(t.dtype))
     return ix

@@ -101,13 +101,19 @@ def _decode_and_check(wl, ix_gpu, index_ref, q, r, what):
 
 @pytest.mark.parametrize("case", list(CASES))
 def test_decode_on_oracle_index(case):
-    """Decode kernels alone: the index is the oracle's, copied to the device."""
+    """Decode kernels alone: the index is the oracle's, copied to the device, into arrays with
+    room behind every unit's clusters, rows and steady rows (odd amounts: the kernels must take
+    the units' strides from the capacities, not from m, N_idx and p)."""
     wl = CASES[case]
     K, V, q = _inputs(wl)
     index_ref = pu.oracle_build(wl, K, V)
     arrays = pu.oracle_index_arrays(wl, index_ref)
+    plan = index_ref[(0, 0)].plan
     ix = wb.index_from_arrays(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
-                              wl.segment_len, wl.clusters_per_segment, arrays)
+                              wl.segment_len, wl.clusters_per_segment, arrays,
+                              row_capacity=plan.N_idx + 3, steady_capacity=index_ref[(0, 0)].k_steady.shape[0] + 1,
+                              cluster_capacity=plan.m + 5)
+    assert ix.cluster_capacity == plan.m + 5
     m = ix.m
     for r in sorted({0, 1, pu.retrieve_count(wl), m // 2, m, m + 3}):
         _decode_and_check(wl, ix, index_ref, q, r, case)
@@ -575,7 +581,8 @@ def test_decode_with_estimation_budget(case):
     index_ref = pu.oracle_build(wl, K, V)
     arrays = pu.oracle_index_arrays(wl, index_ref)
     ix = wb.index_from_arrays(wl.torch_dtype(), wl.B, wl.Hkv, wl.d, wl.N, wl.n_sink, wl.n_local,
-                              wl.segment_len, wl.clusters_per_segment, arrays)
+                              wl.segment_len, wl.clusters_per_segment, arrays,
+                              cluster_capacity=index_ref[(0, 0)].plan.m + 7)   # (strides other than m)
     m = ix.m
     qn = q.double().numpy()
     r0 = pu.retrieve_count(wl)
