@@ -8,6 +8,8 @@
 // 16-byte chunks, so one wave-wide load covers 1 KiB of contiguous rows; dot
 // products are reduced over those lanes with DPP.  Logits are kept in base-2
 // units (logit * log2 e) so that the exponential is a bare v_exp_f32.
+#include <stdlib.h>
+
 #include "wave_common.h"
 
 namespace wave {
@@ -3373,7 +3375,11 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
   g.list_filtered = (r > 0 && m > 16384 && m <= FILT_NT * FILT_MAX_SWEEPS && r <= filtered_max_r()) ? 1 : 0;
   // (up to about three heads per CU the fused kernel below, one workgroup per head with all
   // of them resident at once, is faster; beyond that, or with uneven heads, its tail is long)
-  g.listed = (g.list_filtered || (m > 0 && r > 0 && heads > 768 && m <= 512 * 32)) ? 1 : 0;
+  int listed_min_heads = 768;
+#ifdef WAVE_TUNE  // tuning builds only: launch shapes from the environment
+  if (const char* e = getenv("WAVE_LISTED_MIN_HEADS")) listed_min_heads = atoi(e);
+#endif
+  g.listed = (g.list_filtered || (m > 0 && r > 0 && heads > listed_min_heads && m <= 512 * 32)) ? 1 : 0;
   if (g.listed) {
     g.fused = 0;
     g.sliced = 0;
@@ -3396,12 +3402,18 @@ DecodeGeom decode_geometry(const wave_index& ix, int Hq, int topk) {
     } else {
       g.est_rows = G <= 4 ? 1024 : 512;  // many heads: several rounds of workgroups anyway
     }
+#ifdef WAVE_TUNE
+    if (const char* e = getenv("WAVE_EST_ROWS")) g.est_rows = atoi(e);
+#endif
     g.est_chunks = (m + g.est_rows - 1) / g.est_rows;
     // tokens per range: about one resident round of retrieval workgroups (4 per CU) when
     // there are few tokens, never more than 512 (several rounds of equal pieces then)
     const double tokens = expect * heads;
     int ctok = (int)((tokens + 1023) / 1024);
     g.chunk_tokens = ctok < 256 ? 256 : (ctok > 512 ? 512 : ctok);
+#ifdef WAVE_TUNE
+    if (const char* e = getenv("WAVE_CHUNK_TOKENS")) g.chunk_tokens = atoi(e);
+#endif
     const long long ranges = (long long)(tokens / g.chunk_tokens) + 1;
     // heavy-tailed cluster sizes select large clusters: room for three times the expected
     // ranges (a head that finds the list full still retrieves, as one range)
@@ -3529,7 +3541,10 @@ static wave_status decode_tdg(const void* q_, const wave_index& ix, int Hq, int 
                   static_cast<const T*>(ix.v_steady), ix.p, steady_stride(ix), 2, out, lse);
     } else if (g.listed) {
       const size_t lds_est = sizeof(float) * ((G + 3) / 4 * 4 + 1) * (size_t)g.est_rows;
-      const int nt = g.list_filtered ? FILT_NT : select_direct_threads(m);
+      int nt = g.list_filtered ? FILT_NT : select_direct_threads(m);
+#ifdef WAVE_TUNE
+      if (const char* e = getenv("WAVE_SEL_NT")) nt = g.list_filtered ? nt : atoi(e);
+#endif
       const size_t lds_merge = sizeof(float) * (nt / 64) * G * (D + 2);  // the estimation role's last step
       size_t lds = g.list_filtered ? FILT_LDS : select_direct_lds(m, g.stage);
       if (lds < lds_est) lds = lds_est;
