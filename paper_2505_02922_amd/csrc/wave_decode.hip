@@ -3743,9 +3743,14 @@ static wave_status budget_tdg(const void* q_, const wave_index& ix, int Hq, int 
 #define WAVE_TWO_ARGS                                                                                   \
   q, C, ix.offsets, z, cn2, g.score_chunks, Hq, ix.Hkv, m, g.mwords, mc, bitmap, g.r, g.rcap1, ids1, nsel1, \
       selected, g.k2, g.rcap2, ids2, nsel2, VS, scale_log2
-    if (m <= 512 * 32)
+    // (with 16-bit keys four workgroups fit a CU instead of three: 769 .. 1024 selections are then
+    // all resident at once instead of running in two rounds; a selection by itself is slower so)
+    if (m <= 512 * 32 && (2 * heads <= 768 || 2 * heads > 1024))
       WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32, true>), 2 * heads, 512,
                   sizeof(uint32_t) * 512 * (size_t)((m + 511) / 512), st, WAVE_TWO_ARGS);
+    else if (m <= 512 * 32)
+      WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 512, 32, false>), 2 * heads, 512,
+                  sizeof(uint16_t) * 512 * (size_t)((m + 511) / 512), st, WAVE_TWO_ARGS);
     else
       WAVE_LAUNCH("select x2", (select_two_kernel<T, D, 1024, 64, false>), 2 * heads, 1024,
                   sizeof(uint16_t) * 1024 * (size_t)((m + 1023) / 1024), st, WAVE_TWO_ARGS);

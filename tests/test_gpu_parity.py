@@ -571,11 +571,13 @@ def test_full_attention_is_the_limit_of_the_wave_decode():
     assert float((l1 - l2).abs().max()) < 2e-5
 
 
-@pytest.mark.parametrize("case", ["tiny_f32", "bf16_g4", "bf16_g7", "bf16_d64", "f32_d128"])
+@pytest.mark.parametrize("case", ["tiny_f32", "bf16_g4", "bf16_g7", "bf16_d64", "f32_d128",
+                                  "bf16_many_heads_g7", "bf16_listed_heads"])
 def test_decode_with_estimation_budget(case):
     """The estimation-zone budget (the e best-ranked clusters after the retrieved ones are
     estimated, the rest ignored) against the oracle, including e = 0 and budgets that
-    reach every cluster (then it is the plain decode)."""
+    reach every cluster (then it is the plain decode).  392 heads: both selections of every
+    head in one resident round on 16-bit keys; 800 heads: on 32-bit keys in several rounds."""
     wl = CASES[case]
     K, V, q = _inputs(wl, 1)
     index_ref = pu.oracle_build(wl, K, V)
