@@ -175,7 +175,12 @@ wave_status wave_index_append(const wave_index *old_ix, const void *K_new, const
  *   K, V       DEVICE [B,Hkv,N,d] dtype, read only, may be released after the
  *              stream work completes
  *   ix         dimensions + planned fields + the nine DEVICE buffers (written)
- *   workspace  DEVICE, 256-byte aligned, >= build_workspace_bytes */
+ *   workspace  DEVICE, 256-byte aligned, >= build_workspace_bytes
+ * From the second round on, only clusters that a point entered or left are
+ * summed again (the others keep their centroid bit for bit).  bf16 segments of
+ * at most 2048 tokens and 128 clusters are clustered by one workgroup each that
+ * runs all rounds; WAVE_NO_SMALL_KMEANS=1 in the environment keeps them on the
+ * kernels of the long segments (same result, one launch per step). */
 wave_status wave_index_build(const void *K, const void *V, wave_index *ix, int iters,
                              uint64_t seed, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
