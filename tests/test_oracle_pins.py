@@ -570,3 +570,34 @@ def test_storage_rounding_of_a_centroid_stays_within_the_stated_logit_bound():
             assert lc <= lme + bound
             worst = max(worst, lc - lme)
     assert worst < 0.1     # e^0.1: a tenth of a bit of the fp32 result
+
+
+def test_a_cluster_nobody_entered_or_left_keeps_its_centroid():
+    """Spherical k-means update: the centroid is a function of the member set alone, so a
+    cluster whose members are the same after two consecutive assign steps has the same
+    centroid, bit for bit, after both updates; and on clustered keys most clusters are in that
+    state after a few rounds (which is what lets an implementation sum only the others again).
+    An empty cluster keeps its centroid by the rule for empty clusters."""
+    wl = synth.scaled(synth.WORKLOADS["llama8b_32k"], B=1, Hkv=1, Hq=4, N=4 + 64 + 2048, n_local=64,
+                      segment_len=2048, clusters_per_segment=128, iters=8)
+    K, _ = synth.make_kv(wl)
+    plan = wo.make_plan(wl.N, wl.n_sink, wl.n_local, wl.segment_len, wl.clusters_per_segment)
+    lo, Ls, ks = plan.seg_start[0], plan.seg_len[0], plan.seg_k[0]
+    trace = []
+    wo.kmeans_segment(K[0, 0, lo:lo + Ls].double().numpy(), wo.init_indices(0, 0, 0, 0, Ls, ks), wl.iters,
+                      wl.dtype, trace)
+    same_total, checked = [], 0
+    for t in range(1, len(trace) - 1):
+        a_prev, a_now = trace[t - 1][2], trace[t][2]
+        c_after_prev, c_after_now = trace[t][1], trace[t + 1][1]   # centroids after update t-1 and t
+        moved = a_prev != a_now
+        touched = np.zeros(ks, dtype=bool)
+        touched[a_prev[moved]] = True
+        touched[a_now[moved]] = True
+        same = ~touched
+        assert np.array_equal(c_after_now[same], c_after_prev[same]), t
+        same_total.append(same.mean())
+        checked += int(same.sum())
+    assert checked > 0
+    assert same_total[-1] > same_total[0]          # fewer and fewer clusters change
+    assert same_total[-1] > 0.5
