@@ -1108,9 +1108,10 @@ __global__ __launch_bounds__(256) void steady_copy_kernel(const T* __restrict__ 
 }
 
 __global__ void zero_int_kernel(int32_t* p) { *p = 0; }
-__global__ void fill_int_kernel(int32_t* p, int n, int32_t v) {
+// p[i * stride] = v for i < n
+__global__ void fill_int_kernel(int32_t* p, int n, size_t stride, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
+  if (i < n) p[(size_t)i * stride] = v;
 }
 
 // ============================================================================
@@ -1202,9 +1203,10 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
                 steady_stride(ix), rows);
   }
   if (ix.m == 0) {
-    // nothing to cluster: the offsets array is the single entry offsets[0] = 0 per unit
+    // nothing to cluster: offsets[0] = 0 in every unit (units are cluster_stride + 1 entries apart)
     if (ix.offsets)
-      WAVE_LAUNCH("fill", fill_int_kernel, (units + 255) / 256, 256, 0, st, ix.offsets, units, 0);
+      WAVE_LAUNCH("fill", fill_int_kernel, (units + 255) / 256, 256, 0, st, ix.offsets, units,
+                  (size_t)cluster_stride(ix) + 1, 0);
     return hipGetLastError() == hipSuccess ? WAVE_OK : WAVE_ERR_HIP;
   }
 

@@ -641,7 +641,8 @@ _SHORT = _small("tiny_f32", name="f32_short", N=50, n_sink=4, n_local=64, segmen
     ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140, 0),
     ("tiny_f32", (5, 1, 200, 3), 64, 8, 8192, 140, 4096),
     ("bf16_d64", (130,), 128, 200, 0, 0, 0),
-    (_SHORT, (10, 100), 32, 4, 0, 0, 0)])
+    (_SHORT, (10, 100), 32, 4, 0, 0, 0),
+    (_SHORT, (10, 100), 32, 4, 8192, 0, 64)])   # nothing indexed yet, with room: the first clusters in place
 def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap, ccap):
     """Incremental index update through the C ABI, several times in a row (without and with
     flushed update segments, more clusters asked for than an update segment has tokens, an
@@ -693,6 +694,8 @@ def test_index_append_matches_oracle_then_decode(case, n_news, U, ku, cap, scap,
         assert shared_rows >= 1 and ix.row_capacity == cap      # the rows were added in place
     if cap == 5400:
         assert ix.row_capacity == 0                              # the room ran out: dense again
+    if ccap == 64:
+        assert shared_meta >= 1 and ix.cluster_capacity == ccap
     if ccap == 470 or ccap == 4096:
         assert shared_meta >= 1 and ix.cluster_capacity == ccap   # the clusters were added in place
         assert ix.centroids.data_ptr() == first.centroids.data_ptr()
