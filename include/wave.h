@@ -151,7 +151,9 @@ wave_status wave_index_plan(wave_index *ix, size_t bytes[WAVE_INDEX_BUFFERS],
  * the same steady_capacity >= the new p: only the new tokens' rows are then
  * written, behind the old window); workspace DEVICE, 256-byte aligned.  The
  * plan keeps old_ix's row_capacity, cluster_capacity and steady_capacity while
- * the grown index fits in them and reports 0 (dense) otherwise.  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
+ * the grown index fits in them and reports 0 (dense) otherwise.  An array that
+ * both indexes name must have the same stride per unit in both
+ * (WAVE_ERR_ARG otherwise).  Errors: as wave_index_build; WAVE_ERR_SHAPE if new_ix is not the
  * plan of (old_ix, n_new, n_local_min, U, k_u) or old N < n_sink. */
 wave_status wave_index_append_plan(const wave_index *old_ix, int n_new, int n_local_min,
                                    int update_segment_len, int update_clusters, wave_index *new_ix,

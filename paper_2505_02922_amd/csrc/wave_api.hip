@@ -337,8 +337,13 @@ wave_status wave_index_append(const wave_index* old_ix, const void* K_new, const
                         new_ix->k_perm, new_ix->v_perm};
     const bool in_place = new_ix->row_capacity > 0 && new_ix->row_capacity == old_ix->row_capacity;
     const bool meta_in_place = new_ix->cluster_capacity > 0 && new_ix->cluster_capacity == old_ix->cluster_capacity;
-    for (int i = 0; i < 7; ++i)
+    for (int i = 0; i < 7; ++i) {
       if (g.F > 0 && a[i] && a[i] == b[i] && !(i >= 4 ? in_place : meta_in_place)) return WAVE_ERR_ARG;
+      // an array both indexes name is read with one stride per unit
+      if (a[i] && a[i] == b[i] &&
+          (i >= 4 ? row_stride(*old_ix) != row_stride(*new_ix) : cluster_stride(*old_ix) != cluster_stride(*new_ix)))
+        return WAVE_ERR_ARG;
+    }
     const bool steady_in_place = g.F == 0 && new_ix->steady_capacity > 0 &&
                                  new_ix->steady_capacity == old_ix->steady_capacity;
     if (old_ix->k_steady && !steady_in_place &&

@@ -333,6 +333,22 @@ def test_append_refuses_bad_arguments_on_the_host():
     cn.k_perm = c0.k_perm                               # rows in place without room for them
     assert app(cn, fake, wsb.value) == 1
     cn.k_perm = 0x2000
+    cn.centroids = c0.centroids                         # clusters in place without room for them
+    assert app(cn, fake, wsb.value) == 1
+    cn.centroids = 0x2000
+    # an update that flushes nothing may share the clustered arrays, but not at other strides
+    cs = wb.wave_index()
+    assert L_.wave_index_append_plan(ctypes.byref(c0), 10, 64, 256, 16, ctypes.byref(cs), sizes, None) == 0
+    assert cs.appended_segments == 0
+    for name in wb.BUFFER_NAMES:
+        setattr(cs, name, 0x2000 if name in ("k_steady", "v_steady") else 0x1000)
+    small = lambda new: L_.wave_index_append(ctypes.byref(c0), fake, fake, 10, 64, 256, 16, 3, 0,
+                                             ctypes.byref(new), None, 0, ctypes.c_void_p(1))
+    cs.cluster_capacity = cs.m + 8
+    assert small(cs) == 1
+    cs.cluster_capacity = 0
+    cs.row_capacity = cs.N_idx + 8
+    assert small(cs) == 1
     c0.appended_segments = 0
     # an index that holds update segments cannot be rebuilt by the plain build
     cn2 = wb.wave_index()
