@@ -764,7 +764,10 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
   extern __shared__ int hist[];  // [W][kk], then kk ints of scan space
   const int sg = blockIdx.x;
   const SegInfo si = seg_info(sg, S, L, kk, N_idx);
-  if (sg == 0 && threadIdx.x == 0) *flag_count = 0;  // the refine pass before this one has consumed it
+  if (sg == 0 && threadIdx.x == 0) {
+    flag_count[0] = 0;  // the refine pass before this one has consumed it
+    flag_count[1] = 0;  // the list of large clusters the update step of this round fills
+  }
   sort_segment(assign + (size_t)si.unit * N_idx + si.seg_start, order + (size_t)si.unit * N_idx + si.seg_start,
                count + (size_t)sg * kk, start + (size_t)sg * kk, si.L_s, kk, key_bits, hist,
                prev + (size_t)si.unit * N_idx + si.seg_start, changed + (size_t)sg * kk, !first_round);
@@ -773,57 +776,94 @@ __global__ __launch_bounds__(1024) void sort_kernel(const int32_t* __restrict__ 
 // ============================================================================
 // Update: one group of LPR lanes per cluster sums its members' xhat in fp64.
 // ============================================================================
-// One cluster's update by the calling group of LPR lanes (lane `sub` of it): the n member
-// rows ord[0, n) of the segment's points X are summed in fp64 in that order, U loads in
-// flight, and the normalised sum goes to dst (the lane's 16-byte chunk of the centroid row).
-// (STREAM: the rows are read once per launch and should not displace other lines in the caches)
-template <typename T, int D, int U, bool STREAM>
-__device__ __forceinline__ void update_cluster(const T* X, const int32_t* ord, int n, T* dst, int sub) {
-  auto load_row = [](const T* p) { return STREAM ? load16_stream(p) : load16(p); };
-  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC;
-  if (n == 0) return;  // an empty cluster keeps its centroid
-  X += sub * EPC;
-  double acc[EPC];
+// Exponent fields of the nonzero elements of a 16-byte chunk: their smallest and largest
+// (a subnormal counts as exponent field 1, which has the same unit in the last place).
+template <typename T>
+__device__ __forceinline__ void exponent_range(const uint4& raw, int& emin, int& emax);
+template <>
+__device__ __forceinline__ void exponent_range<bf16_t>(const uint4& raw, int& emin, int& emax) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-  for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t v = h ? w[i] >> 16 : w[i] & 0xffffu;
+      if (v & 0x7fffu) {
+        const int e = max(1, (int)((v >> 7) & 0xffu));
+        emin = min(emin, e);
+        emax = max(emax, e);
+      }
+    }
+  }
+}
+template <>
+__device__ __forceinline__ void exponent_range<float>(const uint4& raw, int& emin, int& emax) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (w[i] & 0x7fffffffu) {
+      const int e = max(1, (int)((w[i] >> 23) & 0xffu));
+      emin = min(emin, e);
+      emax = max(emax, e);
+    }
+}
+template <typename T>
+struct MantissaBits;
+template <>
+struct MantissaBits<bf16_t> {
+  static constexpr int value = 7;
+};
+template <>
+struct MantissaBits<float> {
+  static constexpr int value = 23;
+};
+
+// The member rows ord[0, n) of the segment's points X (already offset to the lane's chunk)
+// added to acc in fp64 in that order, U loads in flight.  STATS: also the exponent range of
+// what was added.  (STREAM: the rows are read once per launch and should not displace other
+// lines in the caches.)
+template <typename T, int D, int U, bool STREAM, bool STATS>
+__device__ __forceinline__ void sum_members(const T* X, const int32_t* ord, int n,
+                                            double (&acc)[Elem<T>::EPC], int& emin, int& emax) {
+  auto load_row = [](const T* p) { return STREAM ? load16_stream(p) : load16(p); };
+  constexpr int EPC = Elem<T>::EPC;
+  auto add = [&](const uint4& raw) {
+    float f[EPC];
+    unpack<T>(raw, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
+    if (STATS) exponent_range<T>(raw, emin, emax);
+  };
   int i = 0;
   for (; i + U <= n; i += U) {
     uint4 raw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) raw[u] = load_row(X + (size_t)ord[i + u] * D);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float f[EPC];
-      unpack<T>(raw[u], f);
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
-    }
+    for (int u = 0; u < U; ++u) add(raw[u]);
   }
   if (U > 4 && i + 4 <= n) {
     uint4 raw[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) raw[u] = load_row(X + (size_t)ord[i + u] * D);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float f[EPC];
-      unpack<T>(raw[u], f);
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
-    }
+    for (int u = 0; u < 4; ++u) add(raw[u]);
     i += 4;
   }
-  for (; i < n; ++i) {
-    float f[EPC];
-    unpack<T>(load16(X + (size_t)ord[i] * D), f);
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) acc[e] += (double)f[e];
-  }
+  for (; i < n; ++i) add(load16(X + (size_t)ord[i] * D));
+}
+
+// The member sum of a cluster, normalised and rounded, to dst (the lane's 16-byte chunk of the
+// centroid row); members that cancel keep the centroid.
+template <typename T, int D>
+__device__ __forceinline__ void finish_centroid(const double (&acc)[Elem<T>::EPC], T* dst) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC;
   double n2 = 0.0;
 #pragma unroll
   for (int e = 0; e < EPC; ++e) n2 = fma(acc[e], acc[e], n2);
   n2 = group_sum_f64<LPR>(n2);
   const double nrm = sqrt(n2);
-  if (!(nrm > 0.0)) return;  // members cancel: keep the centroid
+  if (!(nrm > 0.0)) return;
   T o[EPC];
   const double rn = 1.0 / nrm;
 #pragma unroll
@@ -831,13 +871,106 @@ __device__ __forceinline__ void update_cluster(const T* X, const int32_t* ord, i
   store16(dst, *reinterpret_cast<uint4*>(o));
 }
 
+// One cluster's update by the calling group of LPR lanes (lane `sub` of it): the n member
+// rows ord[0, n) of the segment's points X are summed in fp64 in that order, U loads in
+// flight, and the normalised sum goes to dst.
+template <typename T, int D, int U, bool STREAM>
+__device__ __forceinline__ void update_cluster(const T* X, const int32_t* ord, int n, T* dst, int sub) {
+  constexpr int EPC = Elem<T>::EPC;
+  if (n == 0) return;  // an empty cluster keeps its centroid
+  double acc[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
+  int emin = 0, emax = 0;
+  sum_members<T, D, U, STREAM, false>(X + sub * EPC, ord, n, acc, emin, emax);
+  finish_centroid<T, D>(acc, dst);
+}
+
+// Clusters of more than UPD_BIG members (heavy-tailed data: a thousand tokens in one cluster)
+// are summed by all groups of the workgroup, a contiguous run of members each, and the
+// partial sums are added in run order.  The reference sum adds the members one by one, and
+// the two agree bit for bit when no addition rounds, in either order.  That is certain when
+// every partial sum of any subset of the addends is representable: all addends are multiples of
+// 2^q, q the unit in the last place of the smallest exponent present, and n of them below
+// 2^(emax + 1) in magnitude sum to less than n 2^(emax + 1); fp64 holds every multiple of 2^q
+// below 2^(q + 53), so  emax - emin + ceil(log2 n) <= 52 - (mantissa bits of the storage type)
+// suffices.  The exponent range is gathered on the way; a cluster that fails the test (a
+// component spread over more than 2^34 at bf16) is summed again one by one by one group.
+constexpr int UPD_BIG = 128;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void update_big_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
+                                                         const int32_t* __restrict__ order,
+                                                         const int32_t* __restrict__ count,
+                                                         const int32_t* __restrict__ start,
+                                                         const int32_t* __restrict__ big_list,
+                                                         const int32_t* __restrict__ big_count, int S, int L,
+                                                         int kk, int N_idx) {
+  constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
+  __shared__ double part[GROUPS * D];
+  __shared__ int erange[2 * GROUPS];
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int nbig = *big_count;
+#pragma unroll 1
+  for (int b = blockIdx.x; b < nbig; b += gridDim.x) {  // (the same for every thread of the workgroup)
+    const int gc = big_list[b];
+    const int sg = gc / kk;
+    const SegInfo si = seg_info(sg, S, L, kk, N_idx);
+    const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
+    const int n = count[gc];
+    const int32_t* ord = order + p0 + start[gc];
+    const T* X = xhat + p0 * D + sub * EPC;
+    const int per = (n + GROUPS - 1) / GROUPS;
+    const int i0 = min(n, grp * per), i1 = min(n, i0 + per);
+    double acc[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] = 0.0;
+    int emin = 255, emax = 0;
+    sum_members<T, D, 4, true, true>(X, ord + i0, i1 - i0, acc, emin, emax);
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) {
+      emin = min(emin, __shfl_xor(emin, off));
+      emax = max(emax, __shfl_xor(emax, off));
+    }
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) part[grp * D + sub * EPC + e] = acc[e];
+    if (sub == 0) {
+      erange[2 * grp] = emin;
+      erange[2 * grp + 1] = emax;
+    }
+    __syncthreads();
+    if (grp == 0) {
+      double tot[EPC];
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) tot[e] = part[sub * EPC + e];
+      int lo = erange[0], hi = erange[1];
+#pragma unroll 1
+      for (int g = 1; g < GROUPS; ++g) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) tot[e] += part[g * D + sub * EPC + e];
+        lo = min(lo, erange[2 * g]);
+        hi = max(hi, erange[2 * g + 1]);
+      }
+      const int lg = 32 - __clz(n - 1);  // ceil(log2 n), n > UPD_BIG
+      T* dst = chat + (size_t)gc * D + sub * EPC;
+      if (hi < lo || hi - lo + lg <= 52 - MantissaBits<T>::value)  // (hi < lo: every addend is zero)
+        finish_centroid<T, D>(tot, dst);
+      else
+        update_cluster<T, D, 4, true>(xhat + p0 * D, ord, n, dst, sub);
+    }
+    __syncthreads();
+  }
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat, T* __restrict__ chat,
                                                      const int32_t* __restrict__ order,
                                                      const int32_t* __restrict__ count,
                                                      const int32_t* __restrict__ start,
-                                                     int32_t* __restrict__ changed, int all, int S, int L,
-                                                     int kk, int N_idx, int nclusters) {
+                                                     int32_t* __restrict__ changed, int all,
+                                                     int32_t* __restrict__ big_list,
+                                                     int32_t* __restrict__ big_count, int S, int L, int kk,
+                                                     int N_idx, int nclusters) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   const int gc = blockIdx.x * GROUPS + grp;  // sg * kk + c
@@ -850,8 +983,13 @@ __global__ __launch_bounds__(256) void update_kernel(const T* __restrict__ xhat,
   const int touched = changed[gc];
   if (sub == 0) changed[gc] = 0;
   if (!all && !touched) return;
+  const int n = count[gc];
+  if (n > UPD_BIG) {  // left to update_big_kernel
+    if (sub == 0) big_list[atomicAdd(big_count, 1)] = gc;
+    return;
+  }
   const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
-  update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC, sub);
+  update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], n, chat + (size_t)gc * D + sub * EPC, sub);
 }
 
 // The update of the later rounds, when most clusters are untouched: a workgroup reads the marks
@@ -863,7 +1001,9 @@ __global__ __launch_bounds__(256) void update_touched_kernel(const T* __restrict
                                                              const int32_t* __restrict__ order,
                                                              const int32_t* __restrict__ count,
                                                              const int32_t* __restrict__ start,
-                                                             int32_t* __restrict__ changed, int S, int L,
+                                                             int32_t* __restrict__ changed,
+                                                             int32_t* __restrict__ big_list,
+                                                             int32_t* __restrict__ big_count, int S, int L,
                                                              int kk, int N_idx, int nclusters) {
   constexpr int EPC = Elem<T>::EPC, LPR = D / EPC, GROUPS = 256 / LPR;
   __shared__ int list[256];
@@ -888,9 +1028,14 @@ __global__ __launch_bounds__(256) void update_touched_kernel(const T* __restrict
     const int sg = gc / kk, c = gc - sg * kk;
     const SegInfo si = seg_info(sg, S, L, kk, N_idx);
     if (c >= si.k_s) continue;
+    const int members = count[gc];
+    if (members > UPD_BIG) {  // left to update_big_kernel
+      if (sub == 0) big_list[atomicAdd(big_count, 1)] = gc;
+      continue;
+    }
     const size_t p0 = (size_t)si.unit * N_idx + si.seg_start;
-    update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], count[gc], chat + (size_t)gc * D + sub * EPC,
-                                  sub);
+    update_cluster<T, D, 4, true>(xhat + p0 * D, order + p0 + start[gc], members,
+                                  chat + (size_t)gc * D + sub * EPC, sub);
   }
 }
 
@@ -1262,12 +1407,18 @@ static wave_status build_td(const void* K_, const void* V_, const wave_index& ix
     WAVE_LAUNCH("sort", sort_kernel, g.segs, 64 * W, sort_lds, st, assign, order, count, start, nflag,
                 prev, changed, t == 0 ? 1 : 0, S, L, kk, N_idx, kb);
     if (t + 1 < iters) {
-      if (t == 0)
+      // (large clusters go onto a list, which the third kernel takes: nflag[1] counts them and
+      // the flagged-point list, consumed by refine, is free to hold them)
+      if (t == 0) {
         WAVE_LAUNCH("update", (update_kernel<T, D>), cl_grid, 256, 0, st, xhat, chat, order, count,
-                    start, changed, 1, S, L, kk, N_idx, ncl);
-      else
+                    start, changed, 1, flag, nflag + 1, S, L, kk, N_idx, ncl);
+      } else {
         WAVE_LAUNCH("update", (update_touched_kernel<T, D>), (ncl + 255) / 256, 256, 0, st, xhat, chat,
-                    order, count, start, changed, S, L, kk, N_idx, ncl);
+                    order, count, start, changed, flag, nflag + 1, S, L, kk, N_idx, ncl);
+      }
+      const int big_grid = ncl / UPD_BIG + 1 < 2048 ? ncl / UPD_BIG + 1 : 2048;
+      WAVE_LAUNCH("update", (update_big_kernel<T, D>), big_grid, 256, 0, st, xhat, chat, order, count,
+                  start, flag, nflag + 1, S, L, kk, N_idx);
     }
   }
   WAVE_LAUNCH("finalize", (finalize_kernel<T, D>), cl_grid, 256, 0, st, K, V, order, count, start,

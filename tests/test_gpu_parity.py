@@ -250,6 +250,32 @@ def test_duplicate_keys_and_empty_clusters():
         _decode_and_check(wl, ix, index_ref, q, r, "dups")
 
 
+@pytest.mark.parametrize("tiny_exp", [None, -40])
+def test_large_clusters_are_summed_by_the_whole_workgroup(tiny_exp):
+    """Clusters of several hundred tokens (a 4096-token segment into 8 clusters): their update
+    is split over the groups of a workgroup, which equals the reference's one-by-one sum bit for
+    bit when no addition can round.  Second case: one channel keeps a zero segment mean (values in
+    +/- pairs) and holds values of 2^-40 beside values of order one, so that a cluster's sum over
+    that channel spans more exponents than fp64 can add without rounding: the kernel notices and
+    sums such a cluster one by one.  Every index array against the oracle's in both cases."""
+    wl = _small("llama8b_32k", name="bf16_large_clusters", N=4 + 60 + 4096, Hq=2, Hkv=1, segment_len=4096,
+                clusters_per_segment=8, n_local=60, n_components=8, iters=4, retrieve_abs=2)
+    K, V, q = _inputs(wl)
+    if tiny_exp is not None:
+        g = torch.Generator().manual_seed(3)
+        v = torch.randn(2048, generator=g)
+        v[::3] *= 2.0 ** tiny_exp                      # a third of the pairs are tiny
+        ch = torch.stack([v, -v], dim=1).reshape(-1)   # (+v, -v) side by side: every partial sum cancels
+        K = K.clone()
+        K[0, 0, wl.n_sink:wl.n_sink + 4096, 0] = ch.to(K.dtype)
+    index_ref = pu.oracle_build(wl, K, V)
+    assert index_ref[(0, 0)].sizes.max() > 128
+    ix = wb.wave_index_build(K.cuda(), V.cuda(), wl.n_sink, wl.n_local, wl.segment_len,
+                             wl.clusters_per_segment, wl.iters, 0)
+    assert _compare_index(wl, ix, index_ref, wl.name) == 0
+    _decode_and_check(wl, ix, index_ref, q, 2, wl.name)
+
+
 def test_errors_surface_as_status_codes():
     wl = CASES["bf16_d64"]
     K, V, q = _inputs(wl)
